@@ -1,0 +1,331 @@
+/*
+ * ss_oracle.c -- float64 CPU oracle for the selective scan (selective SSM, "S6").
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the GPU
+ * library is checked against.  It shares no code, header, table or helper with the
+ * HIP path and nothing in the product path may call it; only the test-suite, the
+ * smoke check and the benchmark's cpu_baseline leg load it.
+ *
+ * What it computes (paper: Section 2, Eq. 2a/2b recurrence; Eq. 4 zero-order hold;
+ * Algorithm 2 steps 5-6; Section 3.4 multiplicative SiLU gate; Section 3.6 softplus
+ * parameterisation of the step size).  For every batch b and channel d, independently
+ * (Section 2, "Structure and Dimensions": the SSM acts on each channel on its own, with
+ * a diagonal A of N numbers):
+ *
+ *   r_t      = Delta_raw[b,d,t] (+ bias[d])
+ *   delta_t  = softplus(r_t)                      (if softplus is on, else r_t)
+ *   abar_t,n = exp(delta_t * A[d,n])                                   (Eq. 4, A-bar)
+ *   bbar_t,n = delta_t * B[b,n,t]                 (default: first-order B-bar)
+ *            = (abar_t,n - 1)/A[d,n] * B[b,n,t]   (exact_zoh: Eq. 4, B-bar; A=0 -> delta_t)
+ *   h_t,n    = abar_t,n * h_{t-1,n} + bbar_t,n * u[b,d,t]              (Eq. 2a)
+ *   y_t      = sum_n C[b,n,t] * h_t,n  (+ Dskip[d] * u[b,d,t])         (Eq. 2b)
+ *   out_t    = y_t * z_t * sigmoid(z_t)           (if z is given, else y_t)
+ *
+ * with h_{-1} = h0[b,d,:] or 0, and h_last = h_{L-1}.  The time loop is the plain
+ * sequential recurrence: no scan re-association, no chunking, no fusion.
+ *
+ * The backward pass is the reverse-mode derivative of exactly the loop above, taken
+ * step by step (the paper only says that states are recomputed, Appendix D; the
+ * formulas are the chain rule).  All states of one (b,d) row are kept in memory
+ * (L*N doubles) while that row's gradient is formed.
+ *
+ * Layouts (row-major, last index fastest):
+ *   u, delta, z, out, dout, du, ddelta, dz : (B, D, L)
+ *   Bm, Cm, dB, dC                         : (B, N, L)
+ *   A, dA                                  : (D, N)
+ *   Dskip, bias, dD, dbias                 : (D)
+ *   h0, h_last, dh_last, dh0               : (B, D, N)
+ *
+ * Parity status: pinned (closed-form LTI convolution of Eq. 3, A=0 prefix sum,
+ * brute-force products of the unrolled recurrence, Theorem 1, the large/small step
+ * limits of Section 3.5.2, chunk continuation of Appendix D, finite differences).
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double softplus_f64(double r)
+{
+    /* log(1 + e^r) without overflow for either sign of r */
+    return r > 0.0 ? r + log1p(exp(-r)) : log1p(exp(r));
+}
+
+static double sigmoid_f64(double r)
+{
+    if (r >= 0.0) {
+        return 1.0 / (1.0 + exp(-r));
+    } else {
+        double e = exp(r);
+        return e / (1.0 + e);
+    }
+}
+
+/* phi(delta, A) multiplies B*u in the state update: delta for the first-order rule,
+ * (exp(delta*A) - 1)/A for the exact zero-order hold of Eq. 4. */
+static double phi_f64(int exact_zoh, double delta, double a)
+{
+    if (!exact_zoh || a == 0.0)
+        return delta;
+    return expm1(delta * a) / a;
+}
+
+static double dphi_ddelta_f64(int exact_zoh, double delta, double a)
+{
+    if (!exact_zoh)
+        return 1.0;
+    return exp(delta * a);
+}
+
+static double dphi_dA_f64(int exact_zoh, double delta, double a)
+{
+    if (!exact_zoh)
+        return 0.0;
+    if (a == 0.0)
+        return 0.5 * delta * delta;
+    return (delta * a * exp(delta * a) - expm1(delta * a)) / (a * a);
+}
+
+int ss_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Forward.  Optional pointers may be NULL: z, Dskip, bias, h0, h_last, y_pre.
+ * y_pre, when given, receives y_t before the gate.  Returns 0, or -1 on bad sizes. */
+int ss_oracle_fwd(int nb, int nd, long nl, int nn,
+                  const double *u, const double *delta, const double *z,
+                  const double *Bm, const double *Cm, const double *A,
+                  const double *Dskip, const double *bias, const double *h0,
+                  int softplus, int exact_zoh,
+                  double *out, double *h_last, double *y_pre, int nthreads)
+{
+    if (nb <= 0 || nd <= 0 || nl < 0 || nn <= 0)
+        return -1;
+#ifdef _OPENMP
+    if (nthreads <= 0)
+        nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+    long nrows = (long)nb * nd;
+#pragma omp parallel for schedule(static) num_threads(nthreads)
+    for (long row = 0; row < nrows; ++row) {
+        int b = (int)(row / nd), d = (int)(row % nd);
+        double *h = (double *)malloc(sizeof(double) * (size_t)nn);
+        for (int n = 0; n < nn; ++n)
+            h[n] = h0 ? h0[row * nn + n] : 0.0;
+        for (long t = 0; t < nl; ++t) {
+            double ut = u[row * nl + t];
+            double r = delta[row * nl + t] + (bias ? bias[d] : 0.0);
+            double dt = softplus ? softplus_f64(r) : r;
+            double y = 0.0;
+            for (int n = 0; n < nn; ++n) {
+                double a = A[(long)d * nn + n];
+                double abar = exp(dt * a);
+                double bbar = phi_f64(exact_zoh, dt, a) * Bm[((long)b * nn + n) * nl + t];
+                h[n] = abar * h[n] + bbar * ut;
+                y += Cm[((long)b * nn + n) * nl + t] * h[n];
+            }
+            if (Dskip)
+                y += Dskip[d] * ut;
+            if (y_pre)
+                y_pre[row * nl + t] = y;
+            if (z) {
+                double zt = z[row * nl + t];
+                y *= zt * sigmoid_f64(zt);
+            }
+            out[row * nl + t] = y;
+        }
+        if (h_last)
+            for (int n = 0; n < nn; ++n)
+                h_last[row * nn + n] = h[n];
+        free(h);
+    }
+    return 0;
+}
+
+/* Backward.  Required: dout and every forward input used by the flags.  Optional
+ * (may be NULL): z/dz, Dskip/dD, bias/dbias, h0/dh0, dh_last.  All gradient outputs
+ * that are given are overwritten.  Returns 0, -1 on bad sizes, -2 out of memory. */
+int ss_oracle_bwd(int nb, int nd, long nl, int nn,
+                  const double *u, const double *delta, const double *z,
+                  const double *Bm, const double *Cm, const double *A,
+                  const double *Dskip, const double *bias, const double *h0,
+                  int softplus, int exact_zoh,
+                  const double *dout, const double *dh_last,
+                  double *du, double *ddelta, double *dz,
+                  double *dB, double *dC, double *dA,
+                  double *dD, double *dbias, double *dh0, int nthreads)
+{
+    if (nb <= 0 || nd <= 0 || nl < 0 || nn <= 0)
+        return -1;
+#ifdef _OPENMP
+    if (nthreads <= 0)
+        nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+    memset(dB, 0, sizeof(double) * (size_t)nb * nn * nl);
+    memset(dC, 0, sizeof(double) * (size_t)nb * nn * nl);
+    memset(dA, 0, sizeof(double) * (size_t)nd * nn);
+    if (dD)
+        memset(dD, 0, sizeof(double) * (size_t)nd);
+    if (dbias)
+        memset(dbias, 0, sizeof(double) * (size_t)nd);
+    int failed = 0;
+
+#pragma omp parallel num_threads(nthreads)
+    {
+        /* per-thread: all states of one row, that row's step sizes, and private
+         * accumulators for the gradients that are summed over channels */
+        size_t ln = (size_t)nl * nn;
+        double *hs = (double *)malloc(sizeof(double) * (ln ? ln : 1));
+        double *dts = (double *)malloc(sizeof(double) * (size_t)(nl ? nl : 1));
+        double *rs = (double *)malloc(sizeof(double) * (size_t)(nl ? nl : 1));
+        double *dBp = (double *)malloc(sizeof(double) * (ln ? ln : 1));
+        double *dCp = (double *)malloc(sizeof(double) * (ln ? ln : 1));
+        double *g = (double *)malloc(sizeof(double) * (size_t)nn);
+        if (!hs || !dts || !rs || !dBp || !dCp || !g) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+            for (int b = 0; b < nb; ++b) {
+                memset(dBp, 0, sizeof(double) * ln);
+                memset(dCp, 0, sizeof(double) * ln);
+#pragma omp for schedule(static)
+                for (int d = 0; d < nd; ++d) {
+                    long row = (long)b * nd + d;
+                    const double *Arow = A + (long)d * nn;
+                    /* 1. recompute every state of this row with the forward loop */
+                    for (long t = 0; t < nl; ++t) {
+                        double ut = u[row * nl + t];
+                        double r = delta[row * nl + t] + (bias ? bias[d] : 0.0);
+                        double dt = softplus ? softplus_f64(r) : r;
+                        rs[t] = r;
+                        dts[t] = dt;
+                        for (int n = 0; n < nn; ++n) {
+                            double hprev = t > 0 ? hs[(t - 1) * nn + n]
+                                                 : (h0 ? h0[row * nn + n] : 0.0);
+                            double abar = exp(dt * Arow[n]);
+                            double bbar = phi_f64(exact_zoh, dt, Arow[n]) *
+                                          Bm[((long)b * nn + n) * nl + t];
+                            hs[t * nn + n] = abar * hprev + bbar * ut;
+                        }
+                    }
+                    /* 2. walk the loop backwards; g[n] holds d(loss)/d(h_t,n) coming
+                     *    from later steps (abar_{t+1} * g_{t+1}) on entry to step t */
+                    for (int n = 0; n < nn; ++n)
+                        g[n] = dh_last ? dh_last[row * nn + n] : 0.0;
+                    double dDacc = 0.0, dbacc = 0.0;
+                    for (long t = nl - 1; t >= 0; --t) {
+                        double ut = u[row * nl + t];
+                        double dt = dts[t];
+                        double dy = dout[row * nl + t];
+                        if (z) {
+                            double zt = z[row * nl + t];
+                            double s = sigmoid_f64(zt);
+                            double y = 0.0;
+                            for (int n = 0; n < nn; ++n)
+                                y += Cm[((long)b * nn + n) * nl + t] * hs[t * nn + n];
+                            if (Dskip)
+                                y += Dskip[d] * ut;
+                            /* d/dz [ z*sigmoid(z) ] = s*(1 + z*(1-s)) */
+                            dz[row * nl + t] = dy * y * s * (1.0 + zt * (1.0 - s));
+                            dy = dy * zt * s;
+                        }
+                        double du_t = 0.0, ddt = 0.0;
+                        if (Dskip) {
+                            du_t += Dskip[d] * dy;
+                            dDacc += dy * ut;
+                        }
+                        for (int n = 0; n < nn; ++n) {
+                            long bnt = ((long)b * nn + n) * nl + t;
+                            double a = Arow[n];
+                            double hprev = t > 0 ? hs[(t - 1) * nn + n]
+                                                 : (h0 ? h0[row * nn + n] : 0.0);
+                            double abar = exp(dt * a);
+                            double phi = phi_f64(exact_zoh, dt, a);
+                            /* y_t = sum C h_t  ->  dC, and dy enters g */
+                            dCp[n * nl + t] += dy * hs[t * nn + n];
+                            double gt = g[n] + Cm[bnt] * dy;
+                            /* h_t = abar*hprev + phi*B*u */
+                            double dabar = gt * hprev;
+                            double dphi = gt * Bm[bnt] * ut;
+                            dBp[n * nl + t] += gt * phi * ut;
+                            du_t += gt * phi * Bm[bnt];
+                            /* abar = exp(dt*a) ; phi = phi(dt, a) */
+                            ddt += dabar * a * abar + dphi * dphi_ddelta_f64(exact_zoh, dt, a);
+                            dA[(long)d * nn + n] += dabar * dt * abar +
+                                                    dphi * dphi_dA_f64(exact_zoh, dt, a);
+                            g[n] = abar * gt; /* flows on to h_{t-1} */
+                        }
+                        du[row * nl + t] = du_t;
+                        double draw = softplus ? ddt * sigmoid_f64(rs[t]) : ddt;
+                        ddelta[row * nl + t] = draw;
+                        dbacc += draw;
+                    }
+                    if (dh0)
+                        for (int n = 0; n < nn; ++n)
+                            dh0[row * nn + n] = g[n];
+                    if (dD)
+                        dD[d] += dDacc;
+                    if (dbias)
+                        dbias[d] += dbacc;
+                }
+#pragma omp critical
+                {
+                    double *dBb = dB + (size_t)b * ln, *dCb = dC + (size_t)b * ln;
+                    for (size_t i = 0; i < ln; ++i) {
+                        dBb[i] += dBp[i];
+                        dCb[i] += dCp[i];
+                    }
+                }
+#pragma omp barrier
+            }
+        }
+        free(hs); free(dts); free(rs); free(dBp); free(dCp); free(g);
+    }
+    return failed ? -2 : 0;
+}
+
+/* One recurrent step (Section 2, recurrent mode of Eq. 2): h is (B,D,N), updated in
+ * place; u_t, delta_t, z_t, out_t are (B,D); B_t, C_t are (B,N). */
+int ss_oracle_step(int nb, int nd, int nn, double *h,
+                   const double *u_t, const double *delta_t, const double *z_t,
+                   const double *B_t, const double *C_t, const double *A,
+                   const double *Dskip, const double *bias,
+                   int softplus, int exact_zoh, double *out_t)
+{
+    if (nb <= 0 || nd <= 0 || nn <= 0)
+        return -1;
+    for (int b = 0; b < nb; ++b) {
+        for (int d = 0; d < nd; ++d) {
+            long row = (long)b * nd + d;
+            double r = delta_t[row] + (bias ? bias[d] : 0.0);
+            double dt = softplus ? softplus_f64(r) : r;
+            double y = 0.0;
+            for (int n = 0; n < nn; ++n) {
+                double a = A[(long)d * nn + n];
+                double hn = exp(dt * a) * h[row * nn + n] +
+                            phi_f64(exact_zoh, dt, a) * B_t[(long)b * nn + n] * u_t[row];
+                h[row * nn + n] = hn;
+                y += C_t[(long)b * nn + n] * hn;
+            }
+            if (Dskip)
+                y += Dskip[d] * u_t[row];
+            if (z_t)
+                y *= z_t[row] * sigmoid_f64(z_t[row]);
+            out_t[row] = y;
+        }
+    }
+    return 0;
+}
