@@ -1,0 +1,252 @@
+"""Thin ctypes binding of the C-ABI library declared in ``include/ss_scan.h``.
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch appears here solely as the owner of device memory and streams.  The library must
+have been built (``python -m paper_2312_00752_amd.build``); loading fails loudly if it
+has not been.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libss_scan.so")
+
+SS_F32, SS_BF16 = 0, 1
+SS_DELTA_SOFTPLUS, SS_HAS_DELTA_BIAS, SS_HAS_D, SS_HAS_Z = 1, 2, 4, 8
+SS_HAS_H0, SS_WRITE_H_LAST, SS_SAVE_FOR_BWD = 16, 32, 64
+SS_OK, SS_ERR_NULL, SS_ERR_SHAPE, SS_ERR_UNSUPPORTED = 0, -1, -2, -3
+SS_ERR_ALIGN, SS_ERR_WORKSPACE, SS_ERR_LAUNCH = -4, -5, -6
+SS_MAX_DSTATE = 16
+SS_CHECKPOINT_STEPS = 32
+
+_vp = ctypes.c_void_p
+
+
+class FwdParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("seqlen", ctypes.c_int32),
+                ("dstate", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("u", _vp), ("delta", _vp), ("z", _vp), ("Bmat", _vp), ("Cmat", _vp),
+                ("A", _vp), ("Dskip", _vp), ("delta_bias", _vp), ("h0", _vp),
+                ("out", _vp), ("h_last", _vp), ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class BwdParams(ctypes.Structure):
+    _fields_ = [("fwd", FwdParams), ("dout", _vp), ("dh_last", _vp),
+                ("du", _vp), ("ddelta", _vp), ("dz", _vp), ("dB", _vp), ("dC", _vp),
+                ("dA", _vp), ("dD", _vp), ("ddelta_bias", _vp), ("dh0", _vp)]
+
+
+class StepParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("dstate", ctypes.c_int32),
+                ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("h", _vp), ("u_t", _vp), ("delta_t", _vp), ("z_t", _vp), ("B_t", _vp), ("C_t", _vp),
+                ("A", _vp), ("Dskip", _vp), ("delta_bias", _vp), ("out_t", _vp)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("%s is missing: build it with `python -m paper_2312_00752_amd.build`"
+                               % LIB_PATH)
+        l = ctypes.CDLL(LIB_PATH)
+        l.ss_workspace_bytes.restype = ctypes.c_size_t
+        l.ss_workspace_bytes.argtypes = [ctypes.POINTER(FwdParams), ctypes.c_int]
+        l.ss_scan_fwd.restype = ctypes.c_int
+        l.ss_scan_fwd.argtypes = [ctypes.POINTER(FwdParams), _vp]
+        l.ss_scan_bwd.restype = ctypes.c_int
+        l.ss_scan_bwd.argtypes = [ctypes.POINTER(BwdParams), _vp]
+        l.ss_step.restype = ctypes.c_int
+        l.ss_step.argtypes = [ctypes.POINTER(StepParams), _vp]
+        l.ss_strerror.restype = ctypes.c_char_p
+        l.ss_strerror.argtypes = [ctypes.c_int]
+        l.ss_version.restype = ctypes.c_int
+        l.ss_version.argtypes = []
+        _lib = l
+    return _lib
+
+
+class SsError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__("ss_scan error %d: %s" % (code, ss_strerror(code)))
+
+
+def ss_strerror(code):
+    return lib().ss_strerror(int(code)).decode()
+
+
+def ss_version():
+    return int(lib().ss_version())
+
+
+# ---------------------------------------------------------------- tensor marshalling
+def _io_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return SS_F32
+    if t.dtype == torch.bfloat16:
+        return SS_BF16
+    raise TypeError("io tensors must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _ptr(t, dtype=None, shape=None, name="tensor"):
+    """Device pointer of a dense CUDA tensor (or None)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus):
+    import torch
+    f32 = torch.float32
+    nb, nd, nl = u.shape
+    nn = A.shape[1]
+    io = u.dtype
+    p = FwdParams()
+    p.batch, p.dim, p.seqlen, p.dstate = nb, nd, nl, nn
+    p.io_dtype = _io_code(u)
+    flags = 0
+    p.u = _ptr(u, io, (nb, nd, nl), "u")
+    p.delta = _ptr(delta, io, (nb, nd, nl), "delta")
+    p.Bmat = _ptr(Bmat, io, (nb, nn, nl), "Bmat")
+    p.Cmat = _ptr(Cmat, io, (nb, nn, nl), "Cmat")
+    p.A = _ptr(A, f32, (nd, nn), "A")
+    if z is not None:
+        p.z = _ptr(z, io, (nb, nd, nl), "z")
+        flags |= SS_HAS_Z
+    if Dskip is not None:
+        p.Dskip = _ptr(Dskip, f32, (nd,), "Dskip")
+        flags |= SS_HAS_D
+    if delta_bias is not None:
+        p.delta_bias = _ptr(delta_bias, f32, (nd,), "delta_bias")
+        flags |= SS_HAS_DELTA_BIAS
+    if h0 is not None:
+        p.h0 = _ptr(h0, f32, (nb, nd, nn), "h0")
+        flags |= SS_HAS_H0
+    if delta_softplus:
+        flags |= SS_DELTA_SOFTPLUS
+    p.flags = flags
+    return p
+
+
+def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True):
+    p = FwdParams()
+    p.batch, p.dim, p.seqlen, p.dstate = batch, dim, seqlen, dstate
+    return int(lib().ss_workspace_bytes(ctypes.byref(p), int(bool(for_backward))))
+
+
+def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0=None,
+                delta_softplus=False, out=None, h_last=None, return_last_state=False,
+                workspace=None, stream=None):
+    """Enqueue the forward scan.  Returns (out, h_last or None).
+
+    ``workspace`` (a uint8 CUDA tensor of at least ``ss_workspace_bytes(...)`` bytes)
+    makes the call leave the checkpoints that ``ss_scan_bwd`` needs."""
+    import torch
+    p = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus)
+    if out is None:
+        out = torch.empty_like(u)
+    p.out = _ptr(out, u.dtype, u.shape, "out")
+    if return_last_state or h_last is not None:
+        if h_last is None:
+            h_last = torch.empty((p.batch, p.dim, p.dstate), dtype=torch.float32, device=u.device)
+        p.h_last = _ptr(h_last, torch.float32, (p.batch, p.dim, p.dstate), "h_last")
+        p.flags |= SS_WRITE_H_LAST
+    if workspace is not None:
+        p.workspace = _ptr(workspace, torch.uint8, None, "workspace")
+        p.workspace_bytes = workspace.numel()
+        p.flags |= SS_SAVE_FOR_BWD
+    rc = lib().ss_scan_fwd(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return out, h_last
+
+
+def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, delta_bias=None,
+                h0=None, delta_softplus=False, dh_last=None, want_dh0=False, stream=None):
+    """Enqueue the backward scan after a forward call that filled ``workspace``.
+
+    Returns a dict with du, ddelta, dz, dB, dC, dA, dD, ddelta_bias, dh0 (None where the
+    corresponding input was not given)."""
+    import torch
+    f32 = torch.float32
+    q = BwdParams()
+    q.fwd = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus)
+    nb, nd, nl, nn = q.fwd.batch, q.fwd.dim, q.fwd.seqlen, q.fwd.dstate
+    q.fwd.workspace = _ptr(workspace, torch.uint8, None, "workspace")
+    q.fwd.workspace_bytes = workspace.numel()
+    dev = u.device
+    g = {"du": torch.empty_like(u), "ddelta": torch.empty_like(u),
+         "dz": torch.empty_like(u) if z is not None else None,
+         "dB": torch.empty((nb, nn, nl), dtype=f32, device=dev),
+         "dC": torch.empty((nb, nn, nl), dtype=f32, device=dev),
+         "dA": torch.empty((nd, nn), dtype=f32, device=dev),
+         "dD": torch.empty((nd,), dtype=f32, device=dev) if Dskip is not None else None,
+         "ddelta_bias": torch.empty((nd,), dtype=f32, device=dev) if delta_bias is not None else None,
+         "dh0": torch.empty((nb, nd, nn), dtype=f32, device=dev) if want_dh0 else None}
+    q.dout = _ptr(dout, u.dtype, u.shape, "dout")
+    q.dh_last = _ptr(dh_last, f32, (nb, nd, nn), "dh_last")
+    for name in ("du", "ddelta", "dz", "dB", "dC", "dA", "dD", "ddelta_bias", "dh0"):
+        setattr(q, name, _ptr(g[name], None, None, name))
+    rc = lib().ss_scan_bwd(ctypes.byref(q), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return g
+
+
+def ss_step(h, u_t, delta_t, A, B_t, C_t, Dskip=None, z_t=None, delta_bias=None,
+            delta_softplus=False, out_t=None, stream=None):
+    """Enqueue one recurrent step; ``h`` (B,D,N) float32 is updated in place.  Returns out_t."""
+    import torch
+    f32 = torch.float32
+    nb, nd, nn = h.shape
+    io = u_t.dtype
+    p = StepParams()
+    p.batch, p.dim, p.dstate = nb, nd, nn
+    p.io_dtype = _io_code(u_t)
+    flags = SS_DELTA_SOFTPLUS if delta_softplus else 0
+    p.h = _ptr(h, f32, (nb, nd, nn), "h")
+    p.u_t = _ptr(u_t, io, (nb, nd), "u_t")
+    p.delta_t = _ptr(delta_t, io, (nb, nd), "delta_t")
+    p.B_t = _ptr(B_t, io, (nb, nn), "B_t")
+    p.C_t = _ptr(C_t, io, (nb, nn), "C_t")
+    p.A = _ptr(A, f32, (nd, nn), "A")
+    if z_t is not None:
+        p.z_t = _ptr(z_t, io, (nb, nd), "z_t")
+        flags |= SS_HAS_Z
+    if Dskip is not None:
+        p.Dskip = _ptr(Dskip, f32, (nd,), "Dskip")
+        flags |= SS_HAS_D
+    if delta_bias is not None:
+        p.delta_bias = _ptr(delta_bias, f32, (nd,), "delta_bias")
+        flags |= SS_HAS_DELTA_BIAS
+    p.flags = flags
+    if out_t is None:
+        out_t = torch.empty_like(u_t)
+    p.out_t = _ptr(out_t, io, (nb, nd), "out_t")
+    rc = lib().ss_step(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return out_t

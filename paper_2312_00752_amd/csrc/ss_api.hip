@@ -1,0 +1,183 @@
+// C-ABI entry points: host-side validation and dispatch only (see include/ss_scan.h).
+#include <hip/hip_runtime.h>
+
+#include "ss_kernels.h"
+#include "ss_scan.h"
+
+namespace {
+
+constexpr uint32_t kFwdFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z |
+                               SS_HAS_H0 | SS_WRITE_H_LAST | SS_SAVE_FOR_BWD;
+constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z;
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace layout (all float): [checkpoints nchunks*B*D*16][dA partials B*D*16]
+// [dD partials B*D][dbias partials B*D], each block 256-byte aligned.
+struct WsLayout {
+    size_t ckpt_off, dA_off, dD_off, db_off, total;
+};
+WsLayout ws_layout(int B, int D, int L)
+{
+    const size_t nchunks = (size_t)(L + SS_CHECKPOINT_STEPS - 1) / SS_CHECKPOINT_STEPS;
+    const size_t rows = (size_t)B * D;
+    WsLayout w;
+    w.ckpt_off = 0;
+    w.dA_off = round_up(nchunks * rows * 16 * sizeof(float), 256);
+    w.dD_off = w.dA_off + round_up(rows * 16 * sizeof(float), 256);
+    w.db_off = w.dD_off + round_up(rows * sizeof(float), 256);
+    w.total = w.db_off + round_up(rows * sizeof(float), 256);
+    return w;
+}
+
+int check_fwd(const ss_fwd_params* p, bool for_bwd)
+{
+    if (!p) return SS_ERR_NULL;
+    if (p->batch < 1 || p->dim < 1 || p->dstate < 1 || p->seqlen < 0) return SS_ERR_SHAPE;
+    if (p->dstate > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
+    if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+    if (p->flags & ~kFwdFlags) return SS_ERR_UNSUPPORTED;
+    const bool empty = p->seqlen == 0;  // tensors with a zero-length axis may be NULL
+    if (!p->A) return SS_ERR_NULL;
+    if (!empty && (!p->u || !p->delta || !p->Bmat || !p->Cmat)) return SS_ERR_NULL;
+    if (!empty && !for_bwd && !p->out) return SS_ERR_NULL;
+    if (!empty && (p->flags & SS_HAS_Z) && !p->z) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_D) && !p->Dskip) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_DELTA_BIAS) && !p->delta_bias) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_H0) && !p->h0) return SS_ERR_NULL;
+    if (!for_bwd && (p->flags & SS_WRITE_H_LAST) && !p->h_last) return SS_ERR_NULL;
+    const void* io[] = {p->u, p->delta, p->z, p->Bmat, p->Cmat, for_bwd ? nullptr : p->out};
+    for (const void* q : io)
+        if (q && !aligned(q, 16)) return SS_ERR_ALIGN;
+    const void* f32[] = {p->A, p->Dskip, p->delta_bias, p->h0, for_bwd ? nullptr : p->h_last};
+    for (const void* q : f32)
+        if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
+    if (for_bwd || (p->flags & SS_SAVE_FOR_BWD)) {
+        const size_t need = ws_layout(p->batch, p->dim, p->seqlen).total;
+        if (!p->workspace || p->workspace_bytes < need) return SS_ERR_WORKSPACE;
+        if (!aligned(p->workspace, 256)) return SS_ERR_ALIGN;
+    }
+    return SS_OK;
+}
+
+ss::FwdArgs make_fwd_args(const ss_fwd_params* p)
+{
+    ss::FwdArgs a{};
+    a.B = p->batch; a.D = p->dim; a.L = p->seqlen; a.N = p->dstate;
+    a.flags = p->flags;
+    a.vec_ok = p->seqlen % 8 == 0;
+    a.u = p->u; a.delta = p->delta; a.z = (p->flags & SS_HAS_Z) ? p->z : nullptr;
+    a.Bm = p->Bmat; a.Cm = p->Cmat; a.A = p->A;
+    a.Dskip = p->Dskip; a.bias = p->delta_bias; a.h0 = p->h0;
+    a.out = p->out;
+    a.h_last = (p->flags & SS_WRITE_H_LAST) ? p->h_last : nullptr;
+    a.ckpt = nullptr;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ss_workspace_bytes(const ss_fwd_params* p, int for_backward)
+{
+    if (!p || !for_backward) return 0;
+    if (p->batch < 1 || p->dim < 1 || p->seqlen < 0) return 0;
+    return ws_layout(p->batch, p->dim, p->seqlen).total;
+}
+
+int ss_scan_fwd(const ss_fwd_params* p, void* stream)
+{
+    const int rc = check_fwd(p, false);
+    if (rc != SS_OK) return rc;
+    ss::FwdArgs a = make_fwd_args(p);
+    if (p->flags & SS_SAVE_FOR_BWD)
+        a.ckpt = reinterpret_cast<float*>(static_cast<char*>(p->workspace) +
+                                          ws_layout(p->batch, p->dim, p->seqlen).ckpt_off);
+    return ss::launch_fwd(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+}
+
+int ss_scan_bwd(const ss_bwd_params* p, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    const int rc = check_fwd(&p->fwd, true);
+    if (rc != SS_OK) return rc;
+    const ss_fwd_params* f = &p->fwd;
+    const bool empty = f->seqlen == 0;
+    if (!p->dA) return SS_ERR_NULL;
+    if (!empty && (!p->dout || !p->du || !p->ddelta || !p->dB || !p->dC)) return SS_ERR_NULL;
+    if (!empty && (f->flags & SS_HAS_Z) && !p->dz) return SS_ERR_NULL;
+    if ((f->flags & SS_HAS_D) && !p->dD) return SS_ERR_NULL;
+    if ((f->flags & SS_HAS_DELTA_BIAS) && !p->ddelta_bias) return SS_ERR_NULL;
+    const void* io[] = {p->dout, p->du, p->ddelta, p->dz};
+    for (const void* q : io)
+        if (q && !aligned(q, 16)) return SS_ERR_ALIGN;
+    const void* f32[] = {p->dh_last, p->dB, p->dC, p->dA, p->dD, p->ddelta_bias, p->dh0};
+    for (const void* q : f32)
+        if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
+
+    const WsLayout w = ws_layout(f->batch, f->dim, f->seqlen);
+    char* ws = static_cast<char*>(f->workspace);
+    ss::BwdArgs a{};
+    a.f = make_fwd_args(f);
+    a.f.out = nullptr;
+    a.f.h_last = nullptr;
+    a.f.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
+    a.dout = p->dout; a.dh_last = p->dh_last;
+    a.du = p->du; a.ddelta = p->ddelta; a.dz = (f->flags & SS_HAS_Z) ? p->dz : nullptr;
+    a.dB = p->dB; a.dC = p->dC;
+    a.dA_part = reinterpret_cast<float*>(ws + w.dA_off);
+    a.dD_part = reinterpret_cast<float*>(ws + w.dD_off);
+    a.db_part = reinterpret_cast<float*>(ws + w.db_off);
+    a.dh0 = p->dh0;
+    a.dA = p->dA;
+    a.dD = (f->flags & SS_HAS_D) ? p->dD : nullptr;
+    a.dbias = (f->flags & SS_HAS_DELTA_BIAS) ? p->ddelta_bias : nullptr;
+    return ss::launch_bwd(a, f->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+}
+
+int ss_step(const ss_step_params* p, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    if (p->batch < 1 || p->dim < 1 || p->dstate < 1) return SS_ERR_SHAPE;
+    if (p->dstate > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
+    if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+    if (p->flags & ~kStepFlags) return SS_ERR_UNSUPPORTED;
+    if (!p->h || !p->u_t || !p->delta_t || !p->B_t || !p->C_t || !p->A || !p->out_t) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_Z) && !p->z_t) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_D) && !p->Dskip) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_DELTA_BIAS) && !p->delta_bias) return SS_ERR_NULL;
+    if (!aligned(p->h, 16)) return SS_ERR_ALIGN;
+    const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
+    const void* io[] = {p->u_t, p->delta_t, p->z_t, p->B_t, p->C_t, p->out_t};
+    for (const void* q : io)
+        if (q && !aligned(q, esz)) return SS_ERR_ALIGN;
+    const void* f32[] = {p->A, p->Dskip, p->delta_bias};
+    for (const void* q : f32)
+        if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
+    ss::StepArgs a{};
+    a.B = p->batch; a.D = p->dim; a.N = p->dstate; a.flags = p->flags;
+    a.h = p->h; a.u_t = p->u_t; a.delta_t = p->delta_t; a.z_t = p->z_t;
+    a.B_t = p->B_t; a.C_t = p->C_t; a.A = p->A; a.Dskip = p->Dskip; a.bias = p->delta_bias;
+    a.out_t = p->out_t;
+    return ss::launch_step(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+}
+
+const char* ss_strerror(int code)
+{
+    switch (code) {
+    case SS_OK: return "success";
+    case SS_ERR_NULL: return "a required pointer is NULL";
+    case SS_ERR_SHAPE: return "batch, dim and dstate must be >= 1 and seqlen >= 0";
+    case SS_ERR_UNSUPPORTED: return "unsupported dstate, io_dtype or flag";
+    case SS_ERR_ALIGN: return "a pointer is not aligned as required";
+    case SS_ERR_WORKSPACE: return "workspace missing or too small";
+    case SS_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    default: return "unknown error code";
+    }
+}
+
+int ss_version(void) { return 100; }
+
+}  // extern "C"

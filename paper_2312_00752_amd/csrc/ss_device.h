@@ -1,0 +1,227 @@
+// Device-side helpers shared by the selective-scan kernels (gfx950 only).
+//
+// Work decomposition used by every scan kernel in this library.  A workgroup of NWAVES
+// waves owns ROWS (b,d) rows of one batch entry and walks the sequence in chunks of
+// CHUNK_T steps.  In the "state view" lane l of every wave is row l, and wave w carries
+// states 4w..4w+3 of that row in registers: the recurrence of Eq. 2a runs as a plain
+// sequential loop with the minimum per-(t,n) work (one exp, three multiply-adds), no scan
+// re-association overhead, and -- because all lanes of a wave share b, t and n -- B and C
+// are wave-uniform and come through the scalar data path instead of LDS.  In the
+// "pointwise view" thread i is (row i/4, 8-step slice i%4): it does the per-(b,d,t) work
+// (softplus, gate, conversions) on coalesced 16-byte global accesses.  The two views
+// exchange data through LDS tiles of ROWS x CHUNK_T floats.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ss {
+
+constexpr int WAVE = 64;
+constexpr int STATES_PER_LANE = 4;
+constexpr int NWAVES = 4;                              // covers N <= 16
+constexpr int ROWS = WAVE;                             // rows per workgroup
+constexpr int THREADS = NWAVES * WAVE;                 // 256
+constexpr int NPAD = STATES_PER_LANE * NWAVES;         // 16
+constexpr int CHUNK_T = 32;                            // == SS_CHECKPOINT_STEPS
+constexpr int SLICE = CHUNK_T * ROWS / THREADS;        // 8 steps per thread in the pointwise view
+constexpr int SLICES = CHUNK_T / SLICE;                // 4 threads per row in the pointwise view
+constexpr int TPAD = CHUNK_T + 4;                      // LDS row pitch (floats) of (row, t) tiles
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+typedef uint16_t bf16_t;  // storage only; arithmetic is always float
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float rcp_fast(float x) { return __builtin_amdgcn_rcpf(x); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(uint32_t(v) << 16); }
+
+// float -> bf16, round to nearest even (NaN stays NaN)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t x = __float_as_uint(f);
+    uint32_t r = (x + 0x7fffu + ((x >> 16) & 1u)) >> 16;
+    return (f != f) ? 0x7fc0u : r;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// softplus(r) = log(1 + e^r) and sigmoid(r), sharing one exponential.
+// For e^r below 2^-12 the series e - e^2/2 replaces log(1+e), which would lose the
+// low bits of e; above r = 20 softplus(r) = r to float precision.
+__device__ __forceinline__ void softplus_sigmoid(float r, float& sp, float& sg)
+{
+    float e = exp2_fast(r * LOG2E);
+    float one_e = 1.0f + e;
+    float big = log2_fast(one_e) * LN2;
+    float small = e - 0.5f * e * e;
+    sp = (e < 2.44140625e-4f) ? small : big;
+    sp = (r > 20.0f) ? r : sp;
+    float inv = rcp_fast(one_e);          // 1/(1+e^r)
+    sg = (r > 20.0f) ? 1.0f : e * inv;    // e^r/(1+e^r); avoids inf*0 for huge r
+}
+__device__ __forceinline__ float sigmoid_fast(float z)
+{
+    return rcp_fast(1.0f + exp2_fast(-z * LOG2E));
+}
+
+// ---- 8 consecutive io elements <-> 8 floats -------------------------------------------
+// VEC: every row starts 16-byte aligned and L is a multiple of 8, so a slice is either
+// whole (nvalid == 8, one or two 16-byte accesses) or empty.  Otherwise the `nvalid`
+// leading elements are accessed one by one; the rest read as zero / are not written.
+template <typename T> struct io8;
+
+template <> struct io8<float> {
+    struct raw { float4 a, b; };
+    template <bool VEC>
+    static __device__ __forceinline__ raw load(const float* p, int nvalid)
+    {
+        raw r;
+        if (VEC) {  // nvalid is 0 or 8
+            r.a = r.b = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (nvalid == 8) {
+                r.a = *reinterpret_cast<const float4*>(p);
+                r.b = *reinterpret_cast<const float4*>(p + 4);
+            }
+        } else {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (j < nvalid) ? p[j] : 0.0f;
+            r.a = make_float4(v[0], v[1], v[2], v[3]);
+            r.b = make_float4(v[4], v[5], v[6], v[7]);
+        }
+        return r;
+    }
+    static __device__ __forceinline__ void unpack(const raw& r, float (&v)[8])
+    {
+        v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
+        v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+    }
+    template <bool VEC>
+    static __device__ __forceinline__ void store(float* p, const float (&v)[8], int nvalid)
+    {
+        if (VEC) {
+            if (nvalid == 8) {
+                *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < nvalid) p[j] = v[j];
+        }
+    }
+};
+
+template <> struct io8<bf16_t> {
+    struct raw { uint4 w; };
+    template <bool VEC>
+    static __device__ __forceinline__ raw load(const bf16_t* p, int nvalid)
+    {
+        raw r;
+        if (VEC) {  // nvalid is 0 or 8
+            r.w = make_uint4(0u, 0u, 0u, 0u);
+            if (nvalid == 8) r.w = *reinterpret_cast<const uint4*>(p);
+        } else {
+            uint32_t v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (j < nvalid) ? uint32_t(p[j]) : 0u;
+            r.w = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16),
+                             v[6] | (v[7] << 16));
+        }
+        return r;
+    }
+    static __device__ __forceinline__ void unpack(const raw& r, float (&v)[8])
+    {
+        v[0] = bf16_lo(r.w.x); v[1] = bf16_hi(r.w.x);
+        v[2] = bf16_lo(r.w.y); v[3] = bf16_hi(r.w.y);
+        v[4] = bf16_lo(r.w.z); v[5] = bf16_hi(r.w.z);
+        v[6] = bf16_lo(r.w.w); v[7] = bf16_hi(r.w.w);
+    }
+    template <bool VEC>
+    static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8], int nvalid)
+    {
+        if (VEC) {
+            if (nvalid == 8)
+                *reinterpret_cast<uint4*>(p) = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                                          pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < nvalid) p[j] = bf16_t(f32_to_bf16_bits(v[j]));
+        }
+    }
+};
+
+__device__ __forceinline__ float f4_get(const float4& v, int j)
+{
+    return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
+}
+
+// ---- wave-uniform fetch of B or C for one state over a group of GROUP_T steps ------------
+// The address depends only on the block, the wave index and loop counters, so the load
+// and the bf16 widening are done by the scalar unit and the values reach the vector ALU
+// as scalar operands.  Groups are kept small (4 steps: 8 or 16 bytes) so that two groups
+// of all 8 (state, B|C) rows fit the scalar register file and the next group can be in
+// flight while the current one is consumed.
+constexpr int GROUP_T = 4;
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(4))) const u32x2 const_u32x2;  // constant address space
+typedef __attribute__((address_space(4))) const u32x4 const_u32x4;
+
+template <typename T> struct bc_group;
+template <> struct bc_group<float> {
+    uint32_t w[4];
+    __device__ __forceinline__ float get(int j) const { return __uint_as_float(w[j]); }
+};
+template <> struct bc_group<bf16_t> {
+    uint32_t w[2];
+    __device__ __forceinline__ float get(int j) const { return (j & 1) ? bf16_hi(w[j >> 1]) : bf16_lo(w[j >> 1]); }
+};
+
+// p: start of the (b,n) row; t: first step of the group; L: row length.
+// MASKED: `state_ok` false (padding state) reads as zero.
+template <typename T, bool VEC, bool MASKED>
+__device__ __forceinline__ bc_group<T> load_bc(const T* __restrict__ p, int t, int L, bool state_ok)
+{
+    bc_group<T> g;
+    if (VEC) {
+        // Rows are 16-byte aligned and L is a multiple of 8, so a group is whole or lies
+        // entirely past the end; the latter is redirected to the last whole group (its
+        // values are never used: those steps run with dt = 0 and are not stored).  B and
+        // C are never written by the kernels, so reading them through the constant address
+        // space is sound; with the wave-uniform address it selects the scalar load path.
+        const int tc = min(t, L - GROUP_T);
+        if constexpr (sizeof(T) == 2) {
+            const u32x2 v = *(const_u32x2*)(p + tc);
+            g.w[0] = v.x; g.w[1] = v.y;
+        } else {
+            const u32x4 v = *(const_u32x4*)(p + tc);
+            g.w[0] = v.x; g.w[1] = v.y; g.w[2] = v.z; g.w[3] = v.w;
+        }
+        if (MASKED) {
+#pragma unroll
+            for (int i = 0; i < int(sizeof(g.w) / 4); ++i) g.w[i] = state_ok ? g.w[i] : 0u;
+        }
+    } else {
+        uint32_t e[GROUP_T];
+#pragma unroll
+        for (int j = 0; j < GROUP_T; ++j) {
+            const bool ok = (!MASKED || state_ok) && (t + j < L);
+            if constexpr (sizeof(T) == 2) e[j] = ok ? uint32_t(p[t + j]) : 0u;
+            else e[j] = ok ? __float_as_uint(p[t + j]) : 0u;
+        }
+        if constexpr (sizeof(T) == 2) { g.w[0] = e[0] | (e[1] << 16); g.w[1] = e[2] | (e[3] << 16); }
+        else { g.w[0] = e[0]; g.w[1] = e[1]; g.w[2] = e[2]; g.w[3] = e[3]; }
+    }
+    return g;
+}
+
+}  // namespace ss

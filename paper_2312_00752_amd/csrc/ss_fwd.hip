@@ -1,0 +1,290 @@
+// Forward selective scan (Algorithm 2 steps 5-6, fused as in Appendix D "Speed") and the
+// single-token recurrent step (Section 2, Eq. 2a/2b applied once).
+#include "ss_kernels.h"
+#include "ss_device.h"
+
+namespace ss {
+
+// One workgroup = 64 rows x 4 waves.  Per chunk of CHUNK_T steps:
+//   A. (pointwise view) load 64 rows x 32 steps of u, delta, z with 16-byte accesses, form
+//      dt = softplus(delta + bias) and dt*u, park them in LDS;
+//   B. (state view) wave w runs Eq. 2a/2b sequentially over the 32 steps for states
+//      4w..4w+3 of its 64 rows, B and C arriving as scalar operands, and writes its
+//      partial sum over those states of C*h to LDS;
+//   C. (pointwise view) add the 4 partial sums, the skip term and the gate, and store.
+// The state never leaves registers between chunks (Appendix D: the scan continues from
+// the previous chunk's state).  Steps past the end of the sequence use dt = 0, which is
+// the identity of the recurrence (abar = 1, input term 0).
+template <typename T, bool VEC, bool FULLN>
+__global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
+    __shared__ __attribute__((aligned(16))) float s_du[ROWS][TPAD];
+    __shared__ __attribute__((aligned(16))) float s_yp[NWAVES][ROWS][TPAD];
+
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, provably uniform
+    const int lane = tid & (WAVE - 1);
+    const int groups = (a.D + ROWS - 1) / ROWS;
+    const int b = blockIdx.x / groups;
+    const int d0 = (blockIdx.x % groups) * ROWS;
+    const int L = a.L, N = a.N;
+    const bool has_z = a.flags & F_HAS_Z, has_D = a.flags & F_HAS_D;
+    const bool softplus = a.flags & F_DELTA_SOFTPLUS;
+
+    // ---- pointwise view: thread -> (row pr, slice pq) -----------------------------------
+    const int pr = tid >> 2, pq = tid & 3;
+    const bool p_ok = d0 + pr < a.D;
+    const int pd = p_ok ? d0 + pr : a.D - 1;  // out-of-range rows shadow the last row; stores masked
+    const long prow = (long)b * a.D + pd;
+    const T* __restrict__ gu = static_cast<const T*>(a.u) + prow * L;
+    const T* __restrict__ gdl = static_cast<const T*>(a.delta) + prow * L;
+    const T* __restrict__ gz = static_cast<const T*>(a.z) + prow * L;  // not dereferenced without z
+    T* __restrict__ gout = static_cast<T*>(a.out) + prow * L;
+    const float bias = (a.flags & F_HAS_DELTA_BIAS) ? a.bias[pd] : 0.0f;
+    const float Dsk = has_D ? a.Dskip[pd] : 0.0f;
+
+    // ---- state view: lane -> row, wave -> states 4w..4w+3 -------------------------------
+    const bool s_ok = d0 + lane < a.D;
+    const int sd = s_ok ? d0 + lane : a.D - 1;
+    const long srow = (long)b * a.D + sd;
+    float A2[STATES_PER_LANE], h[STATES_PER_LANE];
+    const T* __restrict__ gB[STATES_PER_LANE];
+    const T* __restrict__ gC[STATES_PER_LANE];
+    bool n_ok[STATES_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < STATES_PER_LANE; ++k) {
+        const int n = w * STATES_PER_LANE + k;
+        n_ok[k] = n < N;
+        const int nc = n_ok[k] ? n : 0;
+        A2[k] = n_ok[k] ? a.A[(long)sd * N + nc] * LOG2E : 0.0f;
+        h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * N + nc] : 0.0f;
+        gB[k] = static_cast<const T*>(a.Bm) + ((long)b * N + nc) * L;
+        gC[k] = static_cast<const T*>(a.Cm) + ((long)b * N + nc) * L;
+    }
+
+    const int nchunks = (L + CHUNK_T - 1) / CHUNK_T;
+    typename io8<T>::raw ru, rd, rz;
+    auto issue_loads = [&](int c) {
+        const int t0 = c * CHUNK_T + pq * SLICE;
+        const int nv = min(max(L - t0, 0), SLICE);
+        ru = io8<T>::template load<VEC>(gu + t0, nv);
+        rd = io8<T>::template load<VEC>(gdl + t0, nv);
+        if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
+    };
+    issue_loads(0);
+
+    for (int c = 0; c < nchunks; ++c) {
+        float u8[SLICE], z8[SLICE], v8[SLICE];
+        const int tc = c * CHUNK_T;
+        const int t0 = tc + pq * SLICE;
+        const int nv = min(max(L - t0, 0), SLICE);
+        // ---- A: pointwise pre-processing --------------------------------------------
+        io8<T>::unpack(ru, u8);
+        io8<T>::unpack(rd, v8);
+        if (has_z) io8<T>::unpack(rz, z8);
+        {
+            float dt8[SLICE], du8[SLICE];
+#pragma unroll
+            for (int j = 0; j < SLICE; ++j) {
+                float x = v8[j] + bias, sp, sg;
+                if (softplus) softplus_sigmoid(x, sp, sg); else sp = x;
+                sp = (j < nv) ? sp : 0.0f;
+                dt8[j] = sp;
+                du8[j] = sp * u8[j];
+            }
+            float4* pd4 = reinterpret_cast<float4*>(&s_dt[pr][pq * SLICE]);
+            float4* pu4 = reinterpret_cast<float4*>(&s_du[pr][pq * SLICE]);
+            pd4[0] = make_float4(dt8[0], dt8[1], dt8[2], dt8[3]);
+            pd4[1] = make_float4(dt8[4], dt8[5], dt8[6], dt8[7]);
+            pu4[0] = make_float4(du8[0], du8[1], du8[2], du8[3]);
+            pu4[1] = make_float4(du8[4], du8[5], du8[6], du8[7]);
+        }
+        // checkpoint: the state entering this chunk (read back by the backward pass)
+        if (a.ckpt && s_ok) {
+            float4* ck = reinterpret_cast<float4*>(a.ckpt + (((long)c * a.B + b) * a.D + sd) * NPAD) + w;
+            *ck = make_float4(h[0], h[1], h[2], h[3]);
+        }
+        if (c + 1 < nchunks) issue_loads(c + 1);  // in flight during the scan below
+        __syncthreads();
+        // ---- B: sequential recurrence over the chunk ---------------------------------
+        constexpr int NG = CHUNK_T / GROUP_T;
+        bc_group<T> Bg[2][STATES_PER_LANE], Cg[2][STATES_PER_LANE];
+        auto fetch_bc = [&](int g, int slot) {
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k) {
+                Bg[slot][k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
+                Cg[slot][k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+            }
+        };
+        fetch_bc(0, 0);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int cur = g & 1;
+            if (g + 1 < NG) fetch_bc(g + 1, cur ^ 1);  // in flight while group g is consumed
+            const int tl = g * GROUP_T;  // step within the chunk
+            const float4 dt4 = *reinterpret_cast<const float4*>(&s_dt[lane][tl]);
+            const float4 du4 = *reinterpret_cast<const float4*>(&s_du[lane][tl]);
+            float yp[GROUP_T];
+#pragma unroll
+            for (int j = 0; j < GROUP_T; ++j) {
+                const float dt = f4_get(dt4, j), du = f4_get(du4, j);
+                float y = 0.0f;
+#pragma unroll
+                for (int k = 0; k < STATES_PER_LANE; ++k) {
+                    const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
+                    h[k] = fmaf(abar, h[k], du * Bg[cur][k].get(j));             // Eq. 2a
+                    y = fmaf(Cg[cur][k].get(j), h[k], y);                        // Eq. 2b
+                }
+                yp[j] = y;
+            }
+            *reinterpret_cast<float4*>(&s_yp[w][lane][tl]) = make_float4(yp[0], yp[1], yp[2], yp[3]);
+        }
+        __syncthreads();
+        // ---- C: pointwise post-processing --------------------------------------------
+        {
+            float y8[SLICE];
+#pragma unroll
+            for (int j = 0; j < SLICE; ++j) y8[j] = has_D ? Dsk * u8[j] : 0.0f;
+#pragma unroll
+            for (int ww = 0; ww < NWAVES; ++ww) {
+                const float4 p0 = *reinterpret_cast<const float4*>(&s_yp[ww][pr][pq * SLICE]);
+                const float4 p1 = *reinterpret_cast<const float4*>(&s_yp[ww][pr][pq * SLICE + 4]);
+                y8[0] += p0.x; y8[1] += p0.y; y8[2] += p0.z; y8[3] += p0.w;
+                y8[4] += p1.x; y8[5] += p1.y; y8[6] += p1.z; y8[7] += p1.w;
+            }
+            if (has_z) {
+#pragma unroll
+                for (int j = 0; j < SLICE; ++j) y8[j] *= z8[j] * sigmoid_fast(z8[j]);
+            }
+            const int nvs = p_ok ? nv : 0;
+            io8<T>::template store<VEC>(gout + t0, y8, nvs);
+        }
+        // no barrier needed here: the next phase A writes s_dt/s_du, which every wave has
+        // finished reading (barrier above), and s_yp is rewritten only after the next barrier
+    }
+
+    if (a.h_last && s_ok) {
+#pragma unroll
+        for (int k = 0; k < STATES_PER_LANE; ++k)
+            if (n_ok[k]) a.h_last[srow * N + w * STATES_PER_LANE + k] = h[k];
+    }
+}
+
+// Single-token step: the same lane layout (4 lanes per row, 4 states each); the state is
+// read and written once, in place, with 16-byte accesses when N == 16.
+template <typename T>
+__global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
+{
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long rowi = gid >> 2;
+    const int q = gid & 3;
+    const long rows = (long)a.B * a.D;
+    const bool row_ok = rowi < rows;
+    const long row = row_ok ? rowi : rows - 1;
+    const int b = row / a.D, d = row % a.D;
+    const int N = a.N;
+
+    const T* u_t = static_cast<const T*>(a.u_t);
+    const T* dl_t = static_cast<const T*>(a.delta_t);
+    const T* z_t = static_cast<const T*>(a.z_t);
+    const T* B_t = static_cast<const T*>(a.B_t);
+    const T* C_t = static_cast<const T*>(a.C_t);
+    auto ld = [](const T* p, long i) -> float {
+        if constexpr (sizeof(T) == 2) return bf16_to_f32(p[i]); else return p[i];
+    };
+    const float u = ld(u_t, row);
+    float x = ld(dl_t, row) + ((a.flags & F_HAS_DELTA_BIAS) ? a.bias[d] : 0.0f);
+    float dt = x, sg;
+    if (a.flags & F_DELTA_SOFTPLUS) softplus_sigmoid(x, dt, sg);
+    const float du = dt * u;
+
+    float hv[STATES_PER_LANE];
+    float* hp = a.h + row * N + q * STATES_PER_LANE;
+    const bool vec = (N == NPAD);
+    if (vec) {
+        const float4 t = *reinterpret_cast<const float4*>(hp);
+        hv[0] = t.x; hv[1] = t.y; hv[2] = t.z; hv[3] = t.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < STATES_PER_LANE; ++k)
+            hv[k] = (q * STATES_PER_LANE + k < N) ? hp[k] : 0.0f;
+    }
+    float y = 0.0f;
+#pragma unroll
+    for (int k = 0; k < STATES_PER_LANE; ++k) {
+        const int n = q * STATES_PER_LANE + k;
+        const bool ok = n < N;
+        const float A2 = ok ? a.A[(long)d * N + n] * LOG2E : 0.0f;
+        const float Bn = ok ? ld(B_t, (long)b * N + n) : 0.0f;
+        const float Cn = ok ? ld(C_t, (long)b * N + n) : 0.0f;
+        hv[k] = fmaf(exp2_fast(dt * A2), hv[k], du * Bn);
+        y = fmaf(Cn, hv[k], y);
+    }
+    if (row_ok) {
+        if (vec) {
+            *reinterpret_cast<float4*>(hp) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k)
+                if (q * STATES_PER_LANE + k < N) hp[k] = hv[k];
+        }
+    }
+    // sum over the 4 lanes of the row
+    y += __shfl_xor(y, 1);
+    y += __shfl_xor(y, 2);
+    if (a.flags & F_HAS_D) y = fmaf(a.Dskip[d], u, y);
+    if (a.flags & F_HAS_Z) {
+        const float z = ld(z_t, row);
+        y *= z * sigmoid_fast(z);
+    }
+    if (row_ok && q == 0) {
+        if constexpr (sizeof(T) == 2) static_cast<bf16_t*>(a.out_t)[row] = bf16_t(f32_to_bf16_bits(y));
+        else static_cast<float*>(a.out_t)[row] = y;
+    }
+}
+
+// h_last for an empty sequence: h0 or zero
+__global__ void copy_state_kernel(const float* __restrict__ src, float* __restrict__ dst, long n)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src ? src[i] : 0.0f;
+}
+
+int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)
+{
+    if (a.L == 0) {
+        if (a.h_last) {
+            const long n = (long)a.B * a.D * a.N;
+            copy_state_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(
+                (a.flags & F_HAS_H0) ? a.h0 : nullptr, a.h_last, n);
+        }
+        return hipGetLastError() == hipSuccess ? 0 : -1;
+    }
+    const int groups = (a.D + ROWS - 1) / ROWS;
+    const dim3 grid((unsigned)(a.B * groups)), block(THREADS);
+    const bool fulln = a.N == NPAD;
+#define SS_LAUNCH_FWD(T, VEC, FULLN) scan_fwd_kernel<T, VEC, FULLN><<<grid, block, 0, stream>>>(a)
+    if (io_dtype == 0) {
+        if (a.vec_ok && fulln) SS_LAUNCH_FWD(float, true, true);
+        else if (a.vec_ok) SS_LAUNCH_FWD(float, true, false);
+        else SS_LAUNCH_FWD(float, false, false);
+    } else {
+        if (a.vec_ok && fulln) SS_LAUNCH_FWD(bf16_t, true, true);
+        else if (a.vec_ok) SS_LAUNCH_FWD(bf16_t, true, false);
+        else SS_LAUNCH_FWD(bf16_t, false, false);
+    }
+#undef SS_LAUNCH_FWD
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
+{
+    const long lanes = (long)a.B * a.D * 4;
+    const dim3 grid((unsigned)((lanes + 255) / 256)), block(256);
+    if (io_dtype == 0) step_kernel<float><<<grid, block, 0, stream>>>(a);
+    else step_kernel<bf16_t><<<grid, block, 0, stream>>>(a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // namespace ss

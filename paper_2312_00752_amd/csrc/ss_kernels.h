@@ -1,0 +1,55 @@
+// Internal interface between the C-ABI entry points (ss_api.hip) and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ss_scan.h"
+
+namespace ss {
+
+enum : uint32_t {
+    F_DELTA_SOFTPLUS = SS_DELTA_SOFTPLUS,
+    F_HAS_DELTA_BIAS = SS_HAS_DELTA_BIAS,
+    F_HAS_D = SS_HAS_D,
+    F_HAS_Z = SS_HAS_Z,
+    F_HAS_H0 = SS_HAS_H0,
+};
+
+struct FwdArgs {
+    int B, D, L, N;
+    uint32_t flags;
+    int vec_ok;  // L % 8 == 0: every row starts 16-byte aligned and 8-step slices are whole or empty
+    const void *u, *delta, *z, *Bm, *Cm;
+    const float *A, *Dskip, *bias, *h0;
+    void* out;
+    float* h_last;  // may be null
+    float* ckpt;    // [chunk][B][D][16] state entering each chunk, or null
+};
+
+struct BwdArgs {
+    FwdArgs f;  // out / h_last unused; ckpt required
+    const void* dout;
+    const float* dh_last;
+    void *du, *ddelta, *dz;
+    float *dB, *dC;             // (B,N,L), zeroed before the scan kernel, atomically accumulated
+    float *dA_part;             // [B][D][16] per-batch partial sums
+    float *dD_part, *db_part;   // [B][D]
+    float* dh0;
+    float *dA, *dD, *dbias;     // final outputs of the reduction kernel
+};
+
+struct StepArgs {
+    int B, D, N;
+    uint32_t flags;
+    float* h;
+    const void *u_t, *delta_t, *z_t, *B_t, *C_t;
+    const float *A, *Dskip, *bias;
+    void* out_t;
+};
+
+// Each returns 0, or -1 if the runtime refused a launch.  io_dtype: 0 = float, 1 = bf16.
+int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream);
+int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream);
+int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream);
+
+}  // namespace ss

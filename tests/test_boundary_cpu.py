@@ -1,0 +1,147 @@
+"""Boundary checks that need no GPU: the library loads, exports every declared symbol,
+and rejects bad arguments on the host before any device call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2312_00752_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # a non-null, 4096-byte aligned address that is never dereferenced
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ss_scan.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(ss_[a-z_]+)\s*\(", hdr))
+    assert {"ss_scan_fwd", "ss_scan_bwd", "ss_step", "ss_workspace_bytes", "ss_strerror", "ss_version"} <= names
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert B.ss_version() >= 100
+    assert B.ss_strerror(0) == "success"
+    for code in range(-6, 0):
+        assert B.ss_strerror(code) not in ("", "success", "unknown error code")
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(B.FwdParams) == 6 * 4 + 13 * 8
+    assert ctypes.sizeof(B.BwdParams) == ctypes.sizeof(B.FwdParams) + 11 * 8
+    assert ctypes.sizeof(B.StepParams) == 5 * 4 + 4 + 10 * 8
+    assert B.SS_CHECKPOINT_STEPS == 32 and B.SS_MAX_DSTATE == 16
+
+
+def _good_fwd():
+    p = B.FwdParams()
+    p.batch, p.dim, p.seqlen, p.dstate = 2, 64, 128, 16
+    p.io_dtype = B.SS_BF16
+    for f in ("u", "delta", "Bmat", "Cmat", "A", "out"):
+        setattr(p, f, FAKE)
+    return p
+
+
+def _fwd(p):
+    return B.lib().ss_scan_fwd(ctypes.byref(p), None)
+
+
+def test_forward_rejections():
+    assert B.lib().ss_scan_fwd(None, None) == B.SS_ERR_NULL
+    for f in ("u", "delta", "Bmat", "Cmat", "A", "out"):
+        p = _good_fwd(); setattr(p, f, None)
+        assert _fwd(p) == B.SS_ERR_NULL, f
+    for f, v in (("batch", 0), ("dim", 0), ("dstate", 0), ("seqlen", -1), ("batch", -3)):
+        p = _good_fwd(); setattr(p, f, v)
+        assert _fwd(p) == B.SS_ERR_SHAPE, f
+    p = _good_fwd(); p.dstate = 17
+    assert _fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_fwd(); p.io_dtype = 2
+    assert _fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_fwd(); p.flags = 1 << 20
+    assert _fwd(p) == B.SS_ERR_UNSUPPORTED
+    for flag, f in ((B.SS_HAS_Z, "z"), (B.SS_HAS_D, "Dskip"), (B.SS_HAS_DELTA_BIAS, "delta_bias"),
+                    (B.SS_HAS_H0, "h0"), (B.SS_WRITE_H_LAST, "h_last")):
+        p = _good_fwd(); p.flags = flag
+        assert _fwd(p) == B.SS_ERR_NULL, f
+    p = _good_fwd(); p.u = FAKE + 8
+    assert _fwd(p) == B.SS_ERR_ALIGN
+    p = _good_fwd(); p.A = FAKE + 2
+    assert _fwd(p) == B.SS_ERR_ALIGN
+    # checkpoints requested without / with too small a workspace
+    p = _good_fwd(); p.flags = B.SS_SAVE_FOR_BWD
+    assert _fwd(p) == B.SS_ERR_WORKSPACE
+    need = B.ss_workspace_bytes(2, 64, 128, 16)
+    p.workspace = FAKE; p.workspace_bytes = need - 1
+    assert _fwd(p) == B.SS_ERR_WORKSPACE
+    p.workspace = FAKE + 128; p.workspace_bytes = need
+    assert _fwd(p) == B.SS_ERR_ALIGN
+
+
+def test_workspace_size_formula():
+    assert B.ss_workspace_bytes(2, 64, 128, 16, for_backward=False) == 0
+    need = B.ss_workspace_bytes(2, 64, 128, 16)
+    rows, chunks = 2 * 64, 128 // 32
+    assert need >= (chunks * rows * 16 + rows * 16 + 2 * rows) * 4
+    assert need % 256 == 0
+    assert B.ss_workspace_bytes(2, 64, 129, 16) > need          # a ragged tail adds a chunk
+    assert B.ss_workspace_bytes(1, 1, 0, 1) % 256 == 0
+
+
+def test_backward_rejections():
+    q = B.BwdParams()
+    q.fwd = _good_fwd()
+    q.fwd.out = None                      # not needed by the backward call
+    need = B.ss_workspace_bytes(2, 64, 128, 16)
+    q.fwd.workspace = FAKE; q.fwd.workspace_bytes = need
+    for f in ("dout", "du", "ddelta", "dB", "dC", "dA"):
+        setattr(q, f, FAKE)
+    bwd = lambda: B.lib().ss_scan_bwd(ctypes.byref(q), None)
+    for f in ("dout", "du", "ddelta", "dB", "dC", "dA"):
+        setattr(q, f, None)
+        assert bwd() == B.SS_ERR_NULL, f
+        setattr(q, f, FAKE)
+    q.fwd.flags = B.SS_HAS_Z; q.fwd.z = FAKE
+    assert bwd() == B.SS_ERR_NULL         # dz missing
+    q.dz = FAKE; q.fwd.flags |= B.SS_HAS_D; q.fwd.Dskip = FAKE
+    assert bwd() == B.SS_ERR_NULL         # dD missing
+    q.dD = FAKE; q.fwd.flags |= B.SS_HAS_DELTA_BIAS; q.fwd.delta_bias = FAKE
+    assert bwd() == B.SS_ERR_NULL         # ddelta_bias missing
+    q.ddelta_bias = FAKE; q.fwd.workspace_bytes = need - 256
+    assert bwd() == B.SS_ERR_WORKSPACE
+    q.fwd.workspace_bytes = need; q.du = FAKE + 4
+    assert bwd() == B.SS_ERR_ALIGN
+    assert B.lib().ss_scan_bwd(None, None) == B.SS_ERR_NULL
+
+
+def test_step_rejections():
+    def good():
+        p = B.StepParams()
+        p.batch, p.dim, p.dstate, p.io_dtype = 4, 32, 16, B.SS_F32
+        for f in ("h", "u_t", "delta_t", "B_t", "C_t", "A", "out_t"):
+            setattr(p, f, FAKE)
+        return p
+    step = lambda p: B.lib().ss_step(ctypes.byref(p), None)
+    assert B.lib().ss_step(None, None) == B.SS_ERR_NULL
+    for f in ("h", "u_t", "delta_t", "B_t", "C_t", "A", "out_t"):
+        p = good(); setattr(p, f, None)
+        assert step(p) == B.SS_ERR_NULL, f
+    p = good(); p.dstate = 0
+    assert step(p) == B.SS_ERR_SHAPE
+    p = good(); p.dstate = 64
+    assert step(p) == B.SS_ERR_UNSUPPORTED
+    p = good(); p.flags = B.SS_HAS_H0
+    assert step(p) == B.SS_ERR_UNSUPPORTED
+    p = good(); p.flags = B.SS_HAS_Z
+    assert step(p) == B.SS_ERR_NULL
+    p = good(); p.h = FAKE + 4
+    assert step(p) == B.SS_ERR_ALIGN
+
+
+def test_python_wrappers_refuse_cpu_tensors():
+    import torch
+    u = torch.zeros(1, 4, 8)
+    A = torch.zeros(4, 2)
+    Bm = torch.zeros(1, 2, 8)
+    with pytest.raises(ValueError):
+        B.ss_scan_fwd(u, u, A, Bm, Bm)
