@@ -50,7 +50,7 @@ extern "C" {
 #define SS_MAX_DSTATE 16
 /* Spacing, in time steps, of the state checkpoints the forward pass leaves for the
  * backward pass (Appendix D: states are recomputed, not stored). */
-#define SS_CHECKPOINT_STEPS 32
+#define SS_CHECKPOINT_STEPS 16
 
 typedef enum { SS_F32 = 0, SS_BF16 = 1 } ss_dtype;
 
@@ -92,9 +92,11 @@ typedef struct {
 
 /* Bytes of workspace a call with these sizes needs: for_backward == 0 for a plain
  * ss_scan_fwd, 1 for ss_scan_fwd with SS_SAVE_FOR_BWD and the ss_scan_bwd that follows
- * it.  Only batch, dim, seqlen, dstate are read.  The content is opaque; a forward call
- * with SS_SAVE_FOR_BWD fills it and the matching backward call must get the same,
- * untouched buffer.  256-byte alignment is required.  Returns 0 when none is needed. */
+ * it.  Only batch, dim, seqlen, dstate, io_dtype and the SS_HAS_Z flag are read.  The
+ * content is opaque (state checkpoints every SS_CHECKPOINT_STEPS steps, the pre-gate
+ * output when there is a gate, and per-batch partial sums of the backward pass); a
+ * forward call with SS_SAVE_FOR_BWD fills it and the matching backward call must get the
+ * same, untouched buffer.  256-byte alignment is required.  Returns 0 when none is needed. */
 size_t ss_workspace_bytes(const ss_fwd_params *p, int for_backward);
 
 /* Forward scan (Algorithm 2 steps 5-6 with the fusion of Appendix D).  Writes out, and

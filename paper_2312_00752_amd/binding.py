@@ -17,7 +17,7 @@ SS_HAS_H0, SS_WRITE_H_LAST, SS_SAVE_FOR_BWD = 16, 32, 64
 SS_OK, SS_ERR_NULL, SS_ERR_SHAPE, SS_ERR_UNSUPPORTED = 0, -1, -2, -3
 SS_ERR_ALIGN, SS_ERR_WORKSPACE, SS_ERR_LAUNCH = -4, -5, -6
 SS_MAX_DSTATE = 16
-SS_CHECKPOINT_STEPS = 32
+SS_CHECKPOINT_STEPS = 16
 
 _vp = ctypes.c_void_p
 
@@ -151,9 +151,12 @@ def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplu
     return p
 
 
-def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True):
+def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True, io_dtype=SS_F32, has_z=True):
+    """Workspace size; the defaults (float32 I/O, gate present) give an upper bound."""
     p = FwdParams()
     p.batch, p.dim, p.seqlen, p.dstate = batch, dim, seqlen, dstate
+    p.io_dtype = io_dtype
+    p.flags = SS_HAS_Z if has_z else 0
     return int(lib().ss_workspace_bytes(ctypes.byref(p), int(bool(for_backward))))
 
 

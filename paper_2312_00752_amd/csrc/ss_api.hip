@@ -13,18 +13,21 @@ constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Workspace layout (all float): [checkpoints nchunks*B*D*16][dA partials B*D*16]
-// [dD partials B*D][dbias partials B*D], each block 256-byte aligned.
+// Workspace layout, each block 256-byte aligned:
+// [float checkpoints nck*B*D*16][io pre-gate y B*D*L, only with a gate]
+// [float dA partials B*D*16][float dD partials B*D][float dbias partials B*D]
 struct WsLayout {
-    size_t ckpt_off, dA_off, dD_off, db_off, total;
+    size_t ckpt_off, y_off, dA_off, dD_off, db_off, total;
 };
-WsLayout ws_layout(int B, int D, int L)
+WsLayout ws_layout(const ss_fwd_params* p)
 {
-    const size_t nchunks = (size_t)(L + SS_CHECKPOINT_STEPS - 1) / SS_CHECKPOINT_STEPS;
-    const size_t rows = (size_t)B * D;
+    const size_t nck = ((size_t)p->seqlen + SS_CHECKPOINT_STEPS - 1) / SS_CHECKPOINT_STEPS;
+    const size_t rows = (size_t)p->batch * p->dim;
+    const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
     WsLayout w;
     w.ckpt_off = 0;
-    w.dA_off = round_up(nchunks * rows * 16 * sizeof(float), 256);
+    w.y_off = round_up(nck * rows * 16 * sizeof(float), 256);
+    w.dA_off = w.y_off + ((p->flags & SS_HAS_Z) ? round_up(rows * (size_t)p->seqlen * esz, 256) : 0);
     w.dD_off = w.dA_off + round_up(rows * 16 * sizeof(float), 256);
     w.db_off = w.dD_off + round_up(rows * sizeof(float), 256);
     w.total = w.db_off + round_up(rows * sizeof(float), 256);
@@ -54,7 +57,7 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd)
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
     if (for_bwd || (p->flags & SS_SAVE_FOR_BWD)) {
-        const size_t need = ws_layout(p->batch, p->dim, p->seqlen).total;
+        const size_t need = ws_layout(p).total;
         if (!p->workspace || p->workspace_bytes < need) return SS_ERR_WORKSPACE;
         if (!aligned(p->workspace, 256)) return SS_ERR_ALIGN;
     }
@@ -73,6 +76,7 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p)
     a.out = p->out;
     a.h_last = (p->flags & SS_WRITE_H_LAST) ? p->h_last : nullptr;
     a.ckpt = nullptr;
+    a.ysave = nullptr;
     return a;
 }
 
@@ -84,7 +88,7 @@ size_t ss_workspace_bytes(const ss_fwd_params* p, int for_backward)
 {
     if (!p || !for_backward) return 0;
     if (p->batch < 1 || p->dim < 1 || p->seqlen < 0) return 0;
-    return ws_layout(p->batch, p->dim, p->seqlen).total;
+    return ws_layout(p).total;
 }
 
 int ss_scan_fwd(const ss_fwd_params* p, void* stream)
@@ -92,9 +96,12 @@ int ss_scan_fwd(const ss_fwd_params* p, void* stream)
     const int rc = check_fwd(p, false);
     if (rc != SS_OK) return rc;
     ss::FwdArgs a = make_fwd_args(p);
-    if (p->flags & SS_SAVE_FOR_BWD)
-        a.ckpt = reinterpret_cast<float*>(static_cast<char*>(p->workspace) +
-                                          ws_layout(p->batch, p->dim, p->seqlen).ckpt_off);
+    if (p->flags & SS_SAVE_FOR_BWD) {
+        const WsLayout w = ws_layout(p);
+        char* ws = static_cast<char*>(p->workspace);
+        a.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
+        a.ysave = (p->flags & SS_HAS_Z) ? ws + w.y_off : nullptr;
+    }
     return ss::launch_fwd(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
 }
 
@@ -117,13 +124,14 @@ int ss_scan_bwd(const ss_bwd_params* p, void* stream)
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
 
-    const WsLayout w = ws_layout(f->batch, f->dim, f->seqlen);
+    const WsLayout w = ws_layout(f);
     char* ws = static_cast<char*>(f->workspace);
     ss::BwdArgs a{};
     a.f = make_fwd_args(f);
     a.f.out = nullptr;
     a.f.h_last = nullptr;
     a.f.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
+    a.f.ysave = (f->flags & SS_HAS_Z) ? ws + w.y_off : nullptr;
     a.dout = p->dout; a.dh_last = p->dh_last;
     a.du = p->du; a.ddelta = p->ddelta; a.dz = (f->flags & SS_HAS_Z) ? p->dz : nullptr;
     a.dB = p->dB; a.dC = p->dC;

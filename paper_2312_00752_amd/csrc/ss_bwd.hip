@@ -15,18 +15,20 @@
 
 namespace ss {
 
-constexpr int RED_PITCH = WAVE + 4;  // pitch (floats) of the per-wave cross-row reduction tile
+constexpr int BT = CKPT_T;                // steps per backward block (one checkpoint each)
+constexpr int BSL = BT * ROWS / THREADS;  // 4 steps per thread in the pointwise view
+constexpr int BPAD = BT + 4;              // LDS row pitch (floats) of (row, t) tiles
+constexpr int RED_PITCH = WAVE + 4;       // pitch (floats) of the per-wave cross-row reduction tile
 constexpr int RED_VALUES = GROUP_T * STATES_PER_LANE;  // 16 values per lane and group
 
 struct BwdSmem {
-    float dt[ROWS][TPAD];   // step size
-    float du[ROWS][TPAD];   // dt * u
-    float dy[ROWS][TPAD];   // gradient reaching y (after the gate)
-    float y[ROWS][TPAD];    // y before the gate: Dskip*u + sum over waves (only with z)
-    float dd[ROWS][TPAD];   // sum_n g abar h_prev A*log2(e)
-    float sb[ROWS][TPAD];   // sum_n g B
-    float red[NWAVES][RED_VALUES][RED_PITCH];  // cross-row reduction tile, private to a wave
-    float dbc[NWAVES][2][STATES_PER_LANE][CHUNK_T];  // this chunk's dB (0) / dC (1), private to a wave
+    float dt[ROWS][BPAD];           // step size
+    float du[ROWS][BPAD];           // dt * u
+    float dy[ROWS][BPAD];           // gradient reaching y (after the gate)
+    float pdd[NWAVES][ROWS][BPAD];  // per wave: sum over its states of g abar h_prev A*log2(e)
+    float psb[NWAVES][ROWS][BPAD];  // per wave: sum over its states of g B
+    float red[NWAVES][RED_VALUES][RED_PITCH];    // cross-row reduction tile, private to a wave
+    float dbc[NWAVES][2][STATES_PER_LANE][BT];   // this block's dB (0) / dC (1), private to a wave
 };
 
 // LDS traffic between lanes of ONE wave needs no barrier: a wave's LDS instructions
@@ -38,15 +40,19 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ void lds_add(float* p, float v)
+// x summed over lanes l, l^16, l^32, l^48 (result in every lane): two half/row swaps
+__device__ __forceinline__ float sum_over_lane_quarters(float x)
 {
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const auto c = __builtin_amdgcn_permlane16_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return __uint_as_float(c[0]) + __uint_as_float(c[1]);
 }
 
 // Sum each of this lane's RED_VALUES values (index = step j * 4 + state k) over the 64
-// lanes (rows) of the wave and add the totals to acc[k][j] (pitch CHUNK_T).  Lane l =
-// (quarter p = l/16, value v = l%16) adds up 16 rows of value v; the four quarters meet in
-// the LDS accumulator.
+// lanes (rows) of the wave and store the totals to acc[k][j] (pitch BT).  The values go
+// through a [value][row] LDS tile; lane l = (quarter p = l/16, value v = l%16) adds up 16
+// rows of value v and the four quarters are combined with lane swaps.
 __device__ __forceinline__ void reduce_over_rows(const float (&v)[RED_VALUES], float (*red)[RED_PITCH],
                                                  float* acc, int lane)
 {
@@ -56,21 +62,23 @@ __device__ __forceinline__ void reduce_over_rows(const float (&v)[RED_VALUES], f
     const int p = lane >> 4, vi = lane & 15;
     const float4* src = reinterpret_cast<const float4*>(&red[vi][16 * p]);
     const float4 a0 = src[0], a1 = src[1], a2 = src[2], a3 = src[3];
-    const float s = ((a0.x + a0.y) + (a0.z + a0.w)) + ((a1.x + a1.y) + (a1.z + a1.w)) +
-                    ((a2.x + a2.y) + (a2.z + a2.w)) + ((a3.x + a3.y) + (a3.z + a3.w));
-    lds_add(acc + (vi & 3) * CHUNK_T + (vi >> 2), s);
+    float s = ((a0.x + a0.y) + (a0.z + a0.w)) + ((a1.x + a1.y) + (a1.z + a1.w)) +
+              ((a2.x + a2.y) + (a2.z + a2.w)) + ((a3.x + a3.y) + (a3.z + a3.w));
+    s = sum_over_lane_quarters(s);
+    if (p == 0) acc[(vi & 3) * BT + (vi >> 2)] = s;
     wave_lds_fence();
 }
 
 // Same decomposition as the forward kernel (64 rows x 4 waves; wave w owns states
-// 4w..4w+3 of every row), walking the chunks from last to first.  Per chunk:
-//   A. (pointwise view) load u, delta, z, dout; form dt, dt*u, dy and park them in LDS;
-//   B1.(state view) recompute the chunk's states from the forward pass's checkpoint,
-//      keeping all 32 x 4 of them in registers; accumulate y (for dz) and dC;
-//   B2.(state view) run the adjoint recurrence backwards through the chunk, carrying
-//      abar*g into the next (earlier) chunk in registers; accumulate dA, dB and the two
-//      per-(b,d,t) sums over n that ddelta and du need;
-//   C. (pointwise view) finish du, ddelta, dz and store them.
+// 4w..4w+3 of every row), walking blocks of BT steps from last to first.  Per block:
+//   A. (pointwise view) load u, delta, z, dout and the saved pre-gate y; form dt, dt*u, dy
+//      and park them in LDS; dz is finished and stored here;
+//   B1.(state view) recompute the block's states from the forward pass's checkpoint,
+//      keeping states and decay factors (16 x 4 each) in registers; accumulate dC;
+//   B2.(state view) run the adjoint recurrence backwards through the block, carrying
+//      abar*g into the next (earlier) block in registers; accumulate dA and dB, and write
+//      this wave's share of the two per-(b,d,t) sums over n that ddelta and du need;
+//   C. (pointwise view) add the four waves' shares, finish du and ddelta, and store them.
 template <typename T, bool VEC, bool FULLN>
 __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 {
@@ -88,7 +96,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     const bool has_z = f.flags & F_HAS_Z, has_D = f.flags & F_HAS_D;
     const bool softplus = f.flags & F_DELTA_SOFTPLUS;
 
-    // ---- pointwise view ------------------------------------------------------------------
+    // ---- pointwise view: thread -> (row pr, 4-step slice pq) -----------------------------
     const int pr = tid >> 2, pq = tid & 3;
     const bool p_ok = d0 + pr < f.D;
     const int pd = p_ok ? d0 + pr : f.D - 1;
@@ -96,6 +104,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     const T* __restrict__ gu = static_cast<const T*>(f.u) + prow * L;
     const T* __restrict__ gdl = static_cast<const T*>(f.delta) + prow * L;
     const T* __restrict__ gz = static_cast<const T*>(f.z) + prow * L;
+    const T* __restrict__ gy = static_cast<const T*>(f.ysave) + prow * L;
     const T* __restrict__ gdo = static_cast<const T*>(a.dout) + prow * L;
     T* __restrict__ gdu = static_cast<T*>(a.du) + prow * L;
     T* __restrict__ gdd = static_cast<T*>(a.ddelta) + prow * L;
@@ -104,7 +113,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     const float Dsk = has_D ? f.Dskip[pd] : 0.0f;
     float dD_acc = 0.0f, db_acc = 0.0f;
 
-    // ---- state view ------------------------------------------------------------------------
+    // ---- state view: lane -> row, wave -> states 4w..4w+3 --------------------------------
     const bool s_ok = d0 + lane < f.D;
     const int sd = s_ok ? d0 + lane : f.D - 1;
     const long srow = (long)b * f.D + sd;
@@ -126,87 +135,76 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     float* const dbc = &sm.dbc[w][0][0][0];
     float (*const red)[RED_PITCH] = sm.red[w];
 
-    const int nchunks = (L + CHUNK_T - 1) / CHUNK_T;
-    typename io8<T>::raw ru, rd, rz, ro;
-    auto issue_loads = [&](int c) {
-        const int t0 = c * CHUNK_T + pq * SLICE;
-        const int nv = p_ok ? min(max(L - t0, 0), SLICE) : 0;  // rows past D contribute nothing
-        ru = io8<T>::template load<VEC>(gu + t0, nv);
-        rd = io8<T>::template load<VEC>(gdl + t0, nv);
-        ro = io8<T>::template load<VEC>(gdo + t0, nv);
-        if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
+    const int nblocks = (L + BT - 1) / BT;
+    typename io4<T>::raw ru, rd, rz, ro, ry;
+    auto issue_loads = [&](int blk) {
+        const int t0 = blk * BT + pq * BSL;
+        const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;  // rows past D contribute nothing
+        ru = io4<T>::template load<VEC>(gu + t0, nv);
+        rd = io4<T>::template load<VEC>(gdl + t0, nv);
+        ro = io4<T>::template load<VEC>(gdo + t0, nv);
+        if (has_z) {
+            rz = io4<T>::template load<VEC>(gz + t0, nv);
+            ry = io4<T>::template load<VEC>(gy + t0, nv);
+        }
     };
-    issue_loads(nchunks - 1);
+    issue_loads(nblocks - 1);
 
-    for (int c = nchunks - 1; c >= 0; --c) {
-        const int tc = c * CHUNK_T;
-        const int t0 = tc + pq * SLICE;
-        const int nv = p_ok ? min(max(L - t0, 0), SLICE) : 0;
-        // the state entering this chunk, left by the forward pass
-        const float4 hck4 = *(reinterpret_cast<const float4*>(f.ckpt + (((long)c * f.B + b) * f.D + sd) * NPAD) + w);
+    for (int blk = nblocks - 1; blk >= 0; --blk) {
+        const int tc = blk * BT;
+        const int t0 = tc + pq * BSL;
+        const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;
+        // the state entering this block, left by the forward pass
+        const float4 hck4 = *(reinterpret_cast<const float4*>(f.ckpt + (((long)blk * f.B + b) * f.D + sd) * NPAD) + w);
 
         // ---- A: pointwise pre-processing ---------------------------------------------------
-        float u8[SLICE], sg8[SLICE], zf8[SLICE];  // u, d softplus, dout * d(gate)/dz
+        float u4[BSL], sg4[BSL];  // u and d softplus(x)/dx, needed again in C
         {
-            float v8[SLICE], z8[SLICE], o8[SLICE];
-            io8<T>::unpack(ru, u8);
-            io8<T>::unpack(rd, v8);
-            io8<T>::unpack(ro, o8);
-            if (has_z) io8<T>::unpack(rz, z8);
-            float dt8[SLICE], du8[SLICE], dy8[SLICE], y8[SLICE];
+            float v4[BSL], o4[BSL], dt4[BSL], du4[BSL], dy4[BSL];
+            io4<T>::unpack(ru, u4);
+            io4<T>::unpack(rd, v4);
+            io4<T>::unpack(ro, o4);
 #pragma unroll
-            for (int j = 0; j < SLICE; ++j) {
-                float x = v8[j] + bias, sp, sg;
+            for (int j = 0; j < BSL; ++j) {
+                float x = v4[j] + bias, sp, sg;
                 if (softplus) softplus_sigmoid(x, sp, sg); else { sp = x; sg = 1.0f; }
                 sp = (j < nv) ? sp : 0.0f;
-                dt8[j] = sp;
-                sg8[j] = sg;
-                du8[j] = sp * u8[j];
-                float dy = o8[j];
-                if (has_z) {
-                    const float s = sigmoid_fast(z8[j]);
-                    zf8[j] = dy * s * fmaf(z8[j], 1.0f - s, 1.0f);  // dout * d[z sigmoid(z)]/dz
-                    dy *= z8[j] * s;
-                }
-                dy8[j] = dy;
-                y8[j] = Dsk * u8[j];
+                dt4[j] = sp;
+                sg4[j] = sg;
+                du4[j] = sp * u4[j];
+                dy4[j] = o4[j];
             }
-            auto st8 = [&](float (*tile)[TPAD], const float (&v)[SLICE]) {
-                float4* p4 = reinterpret_cast<float4*>(&tile[pr][pq * SLICE]);
-                p4[0] = make_float4(v[0], v[1], v[2], v[3]);
-                p4[1] = make_float4(v[4], v[5], v[6], v[7]);
-            };
-            st8(sm.dt, dt8);
-            st8(sm.du, du8);
-            st8(sm.dy, dy8);
-            if (has_z) st8(sm.y, y8);
-            const float zero8[SLICE] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            st8(sm.dd, zero8);
-            st8(sm.sb, zero8);
+            if (has_z) {
+                float z4[BSL], y4[BSL], dz4[BSL];
+                io4<T>::unpack(rz, z4);
+                io4<T>::unpack(ry, y4);
+#pragma unroll
+                for (int j = 0; j < BSL; ++j) {
+                    const float s = sigmoid_fast(z4[j]);
+                    dz4[j] = o4[j] * y4[j] * s * fmaf(z4[j], 1.0f - s, 1.0f);  // dout y d[z sigmoid(z)]/dz
+                    dy4[j] = o4[j] * z4[j] * s;
+                }
+                io4<T>::template store<VEC>(gdz + t0, dz4, nv);
+            }
+            *reinterpret_cast<float4*>(&sm.dt[pr][pq * BSL]) = make_float4(dt4[0], dt4[1], dt4[2], dt4[3]);
+            *reinterpret_cast<float4*>(&sm.du[pr][pq * BSL]) = make_float4(du4[0], du4[1], du4[2], du4[3]);
+            *reinterpret_cast<float4*>(&sm.dy[pr][pq * BSL]) = make_float4(dy4[0], dy4[1], dy4[2], dy4[3]);
         }
-        dbc[lane] = 0.0f; dbc[lane + 64] = 0.0f; dbc[lane + 128] = 0.0f; dbc[lane + 192] = 0.0f;
-        if (c > 0) issue_loads(c - 1);  // in flight during the sweeps below
+        if (blk > 0) issue_loads(blk - 1);  // in flight during the sweeps below
         __syncthreads();
 
-        // ---- B1: recompute the states of the chunk -----------------------------------------
-        constexpr int NG = CHUNK_T / GROUP_T;
-        float hs[CHUNK_T][STATES_PER_LANE];
+        // ---- B1: recompute the states of the block -----------------------------------------
+        constexpr int NG = BT / GROUP_T;
+        float hs[BT][STATES_PER_LANE], as[BT][STATES_PER_LANE];
         const float hck[STATES_PER_LANE] = {hck4.x, hck4.y, hck4.z, hck4.w};
         {
             float h[STATES_PER_LANE] = {hck[0], hck[1], hck[2], hck[3]};
-            bc_group<T> Bg[2][STATES_PER_LANE], Cg[2][STATES_PER_LANE];
-            auto fetch_bc = [&](int g, int slot) {
-#pragma unroll
-                for (int k = 0; k < STATES_PER_LANE; ++k) {
-                    Bg[slot][k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
-                    Cg[slot][k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
-                }
-            };
-            fetch_bc(0, 0);
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                const int cur = g & 1;
-                if (g + 1 < NG) fetch_bc(g + 1, cur ^ 1);
+                bc_group<T> Bg[STATES_PER_LANE];
+#pragma unroll
+                for (int k = 0; k < STATES_PER_LANE; ++k)
+                    Bg[k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
                 const int tl = g * GROUP_T;
                 const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[lane][tl]);
                 const float4 du4 = *reinterpret_cast<const float4*>(&sm.du[lane][tl]);
@@ -215,69 +213,60 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 #pragma unroll
                 for (int j = 0; j < GROUP_T; ++j) {
                     const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
-                    float y = 0.0f;
 #pragma unroll
                     for (int k = 0; k < STATES_PER_LANE; ++k) {
                         const float abar = exp2_fast(dt * A2[k]);
-                        h[k] = fmaf(abar, h[k], du * Bg[cur][k].get(j));
+                        h[k] = fmaf(abar, h[k], du * Bg[k].get(j));
+                        as[tl + j][k] = abar;
                         hs[tl + j][k] = h[k];
-                        if (has_z) y = fmaf(Cg[cur][k].get(j), h[k], y);
                         dCv[j * STATES_PER_LANE + k] = dy * h[k];
                     }
-                    if (has_z) lds_add(&sm.y[lane][tl + j], y);
                 }
-                reduce_over_rows(dCv, red, dbc + STATES_PER_LANE * CHUNK_T + tl, lane);
+                reduce_over_rows(dCv, red, dbc + STATES_PER_LANE * BT + tl, lane);
             }
         }
-        // ---- B2: adjoint recurrence, last step of the chunk first --------------------------
-        {
-            bc_group<T> Bg[2][STATES_PER_LANE], Cg[2][STATES_PER_LANE];
-            auto fetch_bc = [&](int g, int slot) {
+        // ---- B2: adjoint recurrence, last step of the block first --------------------------
+#pragma unroll
+        for (int g = NG - 1; g >= 0; --g) {
+            bc_group<T> Bg[STATES_PER_LANE], Cg[STATES_PER_LANE];
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k) {
+                Bg[k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
+                Cg[k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+            }
+            const int tl = g * GROUP_T;
+            const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[lane][tl]);
+            const float4 du4 = *reinterpret_cast<const float4*>(&sm.du[lane][tl]);
+            const float4 dy4 = *reinterpret_cast<const float4*>(&sm.dy[lane][tl]);
+            float dBv[RED_VALUES], dd[GROUP_T], sb[GROUP_T];
+#pragma unroll
+            for (int j = GROUP_T - 1; j >= 0; --j) {
+                const int t = tl + j;
+                const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
+                dd[j] = 0.0f;
+                sb[j] = 0.0f;
 #pragma unroll
                 for (int k = 0; k < STATES_PER_LANE; ++k) {
-                    Bg[slot][k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
-                    Cg[slot][k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+                    const float gk = fmaf(Cg[k].get(j), dy, ag[k]);   // gradient reaching h_t
+                    ag[k] = as[t][k] * gk;                             // flows on to h_{t-1}
+                    const float hprev = (t > 0) ? hs[t > 0 ? t - 1 : 0][k] : hck[k];
+                    const float gh = ag[k] * hprev;                    // g abar h_{t-1}
+                    dA[k] = fmaf(gh, dt, dA[k]);
+                    dd[j] = fmaf(gh, A2[k], dd[j]);
+                    sb[j] = fmaf(gk, Bg[k].get(j), sb[j]);
+                    dBv[j * STATES_PER_LANE + k] = gk * du;
                 }
-            };
-            fetch_bc(NG - 1, (NG - 1) & 1);
-#pragma unroll
-            for (int g = NG - 1; g >= 0; --g) {
-                const int cur = g & 1;
-                if (g > 0) fetch_bc(g - 1, cur ^ 1);
-                const int tl = g * GROUP_T;
-                const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[lane][tl]);
-                const float4 du4 = *reinterpret_cast<const float4*>(&sm.du[lane][tl]);
-                const float4 dy4 = *reinterpret_cast<const float4*>(&sm.dy[lane][tl]);
-                float dBv[RED_VALUES];
-#pragma unroll
-                for (int j = GROUP_T - 1; j >= 0; --j) {
-                    const int t = tl + j;
-                    const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
-                    float dd = 0.0f, sb = 0.0f;
-#pragma unroll
-                    for (int k = 0; k < STATES_PER_LANE; ++k) {
-                        const float abar = exp2_fast(dt * A2[k]);
-                        const float gk = fmaf(Cg[cur][k].get(j), dy, ag[k]);   // gradient reaching h_t
-                        ag[k] = abar * gk;                                      // flows on to h_{t-1}
-                        const float hprev = (t > 0) ? hs[t > 0 ? t - 1 : 0][k] : hck[k];
-                        const float gh = ag[k] * hprev;                         // g abar h_{t-1}
-                        dA[k] = fmaf(gh, dt, dA[k]);
-                        dd = fmaf(gh, A2[k], dd);
-                        sb = fmaf(gk, Bg[cur][k].get(j), sb);
-                        dBv[j * STATES_PER_LANE + k] = gk * du;
-                    }
-                    lds_add(&sm.dd[lane][t], dd);
-                    lds_add(&sm.sb[lane][t], sb);
-                }
-                reduce_over_rows(dBv, red, dbc + tl, lane);
             }
+            *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
+            *reinterpret_cast<float4*>(&sm.psb[w][lane][tl]) = make_float4(sb[0], sb[1], sb[2], sb[3]);
+            reduce_over_rows(dBv, red, dbc + tl, lane);
         }
-        // ---- flush this wave's dB/dC of the chunk to global memory -------------------------
+        // ---- flush this wave's dB/dC of the block to global memory -------------------------
         wave_lds_fence();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2 * STATES_PER_LANE * BT / WAVE; ++i) {
             const int idx = i * WAVE + lane;
-            const int which = idx >> 7, k = (idx >> 5) & 3, t = idx & (CHUNK_T - 1);
+            const int which = idx / (STATES_PER_LANE * BT), k = (idx / BT) % STATES_PER_LANE, t = idx % BT;
             const int n = w * STATES_PER_LANE + k;
             if (n < N && tc + t < L) {
                 float* dst = (which ? a.dC : a.dB) + ((long)b * N + n) * L + tc + t;
@@ -288,33 +277,31 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 
         // ---- C: pointwise post-processing ---------------------------------------------------
         {
-            auto ld8 = [&](float (*tile)[TPAD], float (&v)[SLICE]) {
-                const float4* p4 = reinterpret_cast<const float4*>(&tile[pr][pq * SLICE]);
-                const float4 x = p4[0], y = p4[1];
-                v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-                v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
-            };
-            float dt8[SLICE], dy8[SLICE], dd8[SLICE], sb8[SLICE], y8[SLICE];
-            ld8(sm.dt, dt8);
-            ld8(sm.dy, dy8);
-            ld8(sm.dd, dd8);
-            ld8(sm.sb, sb8);
-            if (has_z) ld8(sm.y, y8);
-            float du8[SLICE], dl8[SLICE], dz8[SLICE];
+            const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[pr][pq * BSL]);
+            const float4 dy4 = *reinterpret_cast<const float4*>(&sm.dy[pr][pq * BSL]);
+            float dd4[BSL] = {0.f, 0.f, 0.f, 0.f}, sb4[BSL] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < SLICE; ++j) {
-                const float ddt = fmaf(u8[j], sb8[j], LN2 * dd8[j]);
-                du8[j] = fmaf(dt8[j], sb8[j], Dsk * dy8[j]);
-                dl8[j] = ddt * sg8[j];
-                if (has_z) dz8[j] = zf8[j] * y8[j];
-                dD_acc = fmaf(dy8[j], u8[j], dD_acc);
-                db_acc += (j < nv) ? dl8[j] : 0.0f;
+            for (int ww = 0; ww < NWAVES; ++ww) {
+                const float4 x = *reinterpret_cast<const float4*>(&sm.pdd[ww][pr][pq * BSL]);
+                const float4 y = *reinterpret_cast<const float4*>(&sm.psb[ww][pr][pq * BSL]);
+                dd4[0] += x.x; dd4[1] += x.y; dd4[2] += x.z; dd4[3] += x.w;
+                sb4[0] += y.x; sb4[1] += y.y; sb4[2] += y.z; sb4[3] += y.w;
             }
-            io8<T>::template store<VEC>(gdu + t0, du8, nv);
-            io8<T>::template store<VEC>(gdd + t0, dl8, nv);
-            if (has_z) io8<T>::template store<VEC>(gdz + t0, dz8, nv);
+            float du4[BSL], dl4[BSL];
+#pragma unroll
+            for (int j = 0; j < BSL; ++j) {
+                const float dt = f4_get(dt4, j), dy = f4_get(dy4, j);
+                const float ddt = fmaf(u4[j], sb4[j], LN2 * dd4[j]);
+                du4[j] = fmaf(dt, sb4[j], Dsk * dy);
+                dl4[j] = ddt * sg4[j];
+                dD_acc = fmaf(dy, u4[j], dD_acc);
+                db_acc += (j < nv) ? dl4[j] : 0.0f;
+            }
+            io4<T>::template store<VEC>(gdu + t0, du4, nv);
+            io4<T>::template store<VEC>(gdd + t0, dl4, nv);
         }
-        // the next phase A rewrites only this thread's own tile slices before its barrier
+        // the next phase A rewrites only this thread's own slices of dt/du/dy; the share
+        // tiles are rewritten only after the next barrier
     }
 
     // ---- per-row results --------------------------------------------------------------------

@@ -22,7 +22,8 @@ constexpr int NWAVES = 4;                              // covers N <= 16
 constexpr int ROWS = WAVE;                             // rows per workgroup
 constexpr int THREADS = NWAVES * WAVE;                 // 256
 constexpr int NPAD = STATES_PER_LANE * NWAVES;         // 16
-constexpr int CHUNK_T = 32;                            // == SS_CHECKPOINT_STEPS
+constexpr int CHUNK_T = 32;                            // steps per forward chunk
+constexpr int CKPT_T = 16;                             // == SS_CHECKPOINT_STEPS
 constexpr int SLICE = CHUNK_T * ROWS / THREADS;        // 8 steps per thread in the pointwise view
 constexpr int SLICES = CHUNK_T / SLICE;                // 4 threads per row in the pointwise view
 constexpr int TPAD = CHUNK_T + 4;                      // LDS row pitch (floats) of (row, t) tiles
@@ -154,6 +155,77 @@ template <> struct io8<bf16_t> {
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j)
+                if (j < nvalid) p[j] = bf16_t(f32_to_bf16_bits(v[j]));
+        }
+    }
+};
+
+// ---- 4 consecutive io elements <-> 4 floats (same VEC contract: whole or empty) ----------
+template <typename T> struct io4;
+
+template <> struct io4<float> {
+    struct raw { float4 a; };
+    template <bool VEC>
+    static __device__ __forceinline__ raw load(const float* p, int nvalid)
+    {
+        raw r;
+        if (VEC) {
+            r.a = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (nvalid == 4) r.a = *reinterpret_cast<const float4*>(p);
+        } else {
+            r.a = make_float4(0 < nvalid ? p[0] : 0.f, 1 < nvalid ? p[1] : 0.f, 2 < nvalid ? p[2] : 0.f,
+                              3 < nvalid ? p[3] : 0.f);
+        }
+        return r;
+    }
+    static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
+    {
+        v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
+    }
+    template <bool VEC>
+    static __device__ __forceinline__ void store(float* p, const float (&v)[4], int nvalid)
+    {
+        if (VEC) {
+            if (nvalid == 4) *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (j < nvalid) p[j] = v[j];
+        }
+    }
+};
+
+template <> struct io4<bf16_t> {
+    struct raw { uint2 w; };
+    template <bool VEC>
+    static __device__ __forceinline__ raw load(const bf16_t* p, int nvalid)
+    {
+        raw r;
+        if (VEC) {
+            r.w = make_uint2(0u, 0u);
+            if (nvalid == 4) r.w = *reinterpret_cast<const uint2*>(p);
+        } else {
+            uint32_t v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (j < nvalid) ? uint32_t(p[j]) : 0u;
+            r.w = make_uint2(v[0] | (v[1] << 16), v[2] | (v[3] << 16));
+        }
+        return r;
+    }
+    static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
+    {
+        v[0] = bf16_lo(r.w.x); v[1] = bf16_hi(r.w.x);
+        v[2] = bf16_lo(r.w.y); v[3] = bf16_hi(r.w.y);
+    }
+    template <bool VEC>
+    static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[4], int nvalid)
+    {
+        if (VEC) {
+            if (nvalid == 4)
+                *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
                 if (j < nvalid) p[j] = bf16_t(f32_to_bf16_bits(v[j]));
         }
     }

@@ -100,11 +100,14 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             pu4[0] = make_float4(du8[0], du8[1], du8[2], du8[3]);
             pu4[1] = make_float4(du8[4], du8[5], du8[6], du8[7]);
         }
-        // checkpoint: the state entering this chunk (read back by the backward pass)
-        if (a.ckpt && s_ok) {
-            float4* ck = reinterpret_cast<float4*>(a.ckpt + (((long)c * a.B + b) * a.D + sd) * NPAD) + w;
-            *ck = make_float4(h[0], h[1], h[2], h[3]);
-        }
+        // checkpoint: the state entering every CKPT_T-step block (read back by the backward pass)
+        auto save_ckpt = [&](int block) {
+            if (a.ckpt && s_ok && block * CKPT_T < L) {
+                float4* ck = reinterpret_cast<float4*>(a.ckpt + (((long)block * a.B + b) * a.D + sd) * NPAD) + w;
+                *ck = make_float4(h[0], h[1], h[2], h[3]);
+            }
+        };
+        save_ckpt(c * (CHUNK_T / CKPT_T));
         if (c + 1 < nchunks) issue_loads(c + 1);  // in flight during the scan below
         __syncthreads();
         // ---- B: sequential recurrence over the chunk ---------------------------------
@@ -123,6 +126,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             const int cur = g & 1;
             if (g + 1 < NG) fetch_bc(g + 1, cur ^ 1);  // in flight while group g is consumed
             const int tl = g * GROUP_T;  // step within the chunk
+            if (g > 0 && tl % CKPT_T == 0) save_ckpt((tc + tl) / CKPT_T);
             const float4 dt4 = *reinterpret_cast<const float4*>(&s_dt[lane][tl]);
             const float4 du4 = *reinterpret_cast<const float4*>(&s_du[lane][tl]);
             float yp[GROUP_T];
@@ -153,11 +157,13 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 y8[0] += p0.x; y8[1] += p0.y; y8[2] += p0.z; y8[3] += p0.w;
                 y8[4] += p1.x; y8[5] += p1.y; y8[6] += p1.z; y8[7] += p1.w;
             }
+            const int nvs = p_ok ? nv : 0;
             if (has_z) {
+                if (a.ysave)  // y before the gate, for the backward pass's dz
+                    io8<T>::template store<VEC>(static_cast<T*>(a.ysave) + prow * L + t0, y8, nvs);
 #pragma unroll
                 for (int j = 0; j < SLICE; ++j) y8[j] *= z8[j] * sigmoid_fast(z8[j]);
             }
-            const int nvs = p_ok ? nv : 0;
             io8<T>::template store<VEC>(gout + t0, y8, nvs);
         }
         // no barrier needed here: the next phase A writes s_dt/s_du, which every wave has

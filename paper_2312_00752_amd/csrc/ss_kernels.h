@@ -23,7 +23,8 @@ struct FwdArgs {
     const float *A, *Dskip, *bias, *h0;
     void* out;
     float* h_last;  // may be null
-    float* ckpt;    // [chunk][B][D][16] state entering each chunk, or null
+    float* ckpt;    // [checkpoint][B][D][16]: state entering every 16-step block, or null
+    void* ysave;    // (B,D,L) io dtype: y before the gate, kept for the backward pass, or null
 };
 
 struct BwdArgs {

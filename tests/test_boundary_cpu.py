@@ -30,7 +30,7 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.FwdParams) == 6 * 4 + 13 * 8
     assert ctypes.sizeof(B.BwdParams) == ctypes.sizeof(B.FwdParams) + 11 * 8
     assert ctypes.sizeof(B.StepParams) == 5 * 4 + 4 + 10 * 8
-    assert B.SS_CHECKPOINT_STEPS == 32 and B.SS_MAX_DSTATE == 16
+    assert B.SS_CHECKPOINT_STEPS == 16 and B.SS_MAX_DSTATE == 16
 
 
 def _good_fwd():
@@ -71,7 +71,7 @@ def test_forward_rejections():
     # checkpoints requested without / with too small a workspace
     p = _good_fwd(); p.flags = B.SS_SAVE_FOR_BWD
     assert _fwd(p) == B.SS_ERR_WORKSPACE
-    need = B.ss_workspace_bytes(2, 64, 128, 16)
+    need = B.ss_workspace_bytes(2, 64, 128, 16, io_dtype=B.SS_BF16, has_z=False)
     p.workspace = FAKE; p.workspace_bytes = need - 1
     assert _fwd(p) == B.SS_ERR_WORKSPACE
     p.workspace = FAKE + 128; p.workspace_bytes = need
@@ -81,8 +81,10 @@ def test_forward_rejections():
 def test_workspace_size_formula():
     assert B.ss_workspace_bytes(2, 64, 128, 16, for_backward=False) == 0
     need = B.ss_workspace_bytes(2, 64, 128, 16)
-    rows, chunks = 2 * 64, 128 // 32
-    assert need >= (chunks * rows * 16 + rows * 16 + 2 * rows) * 4
+    rows, chunks = 2 * 64, 128 // B.SS_CHECKPOINT_STEPS
+    assert need >= (chunks * rows * 16 + rows * 128 + rows * 16 + 2 * rows) * 4
+    assert B.ss_workspace_bytes(2, 64, 128, 16, io_dtype=B.SS_BF16) == need - rows * 128 * 2
+    assert B.ss_workspace_bytes(2, 64, 128, 16, has_z=False) == need - rows * 128 * 4
     assert need % 256 == 0
     assert B.ss_workspace_bytes(2, 64, 129, 16) > need          # a ragged tail adds a chunk
     assert B.ss_workspace_bytes(1, 1, 0, 1) % 256 == 0
@@ -92,7 +94,7 @@ def test_backward_rejections():
     q = B.BwdParams()
     q.fwd = _good_fwd()
     q.fwd.out = None                      # not needed by the backward call
-    need = B.ss_workspace_bytes(2, 64, 128, 16)
+    need = B.ss_workspace_bytes(2, 64, 128, 16)   # upper bound over dtypes and flags
     q.fwd.workspace = FAKE; q.fwd.workspace_bytes = need
     for f in ("dout", "du", "ddelta", "dB", "dC", "dA"):
         setattr(q, f, FAKE)
