@@ -109,9 +109,10 @@ def test_backward_rejections():
     assert bwd() == B.SS_ERR_NULL         # dD missing
     q.dD = FAKE; q.fwd.flags |= B.SS_HAS_DELTA_BIAS; q.fwd.delta_bias = FAKE
     assert bwd() == B.SS_ERR_NULL         # ddelta_bias missing
-    q.ddelta_bias = FAKE; q.fwd.workspace_bytes = need - 256
+    exact = B.ss_workspace_bytes(2, 64, 128, 16, io_dtype=B.SS_BF16, has_z=True)
+    q.ddelta_bias = FAKE; q.fwd.workspace_bytes = exact - 256
     assert bwd() == B.SS_ERR_WORKSPACE
-    q.fwd.workspace_bytes = need; q.du = FAKE + 4
+    q.fwd.workspace_bytes = exact; q.du = FAKE + 4
     assert bwd() == B.SS_ERR_ALIGN
     assert B.lib().ss_scan_bwd(None, None) == B.SS_ERR_NULL
 
