@@ -41,17 +41,15 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(uint32_t(v) << 16); }
 
-// float -> bf16, round to nearest even (NaN stays NaN)
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
-{
-    uint32_t x = __float_as_uint(f);
-    uint32_t r = (x + 0x7fffu + ((x >> 16) & 1u)) >> 16;
-    return (f != f) ? 0x7fc0u : r;
-}
+// float -> bf16 with the hardware converter of gfx950 (round to nearest even, NaN kept)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));  // v_cvt_pk_bf16_f32
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xffffu; }
 
 // softplus(r) = log(1 + e^r) and sigmoid(r), sharing one exponential.
 // For e^r below 2^-12 the series e - e^2/2 replaces log(1+e), which would lose the
