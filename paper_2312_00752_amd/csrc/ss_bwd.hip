@@ -136,19 +136,27 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     float (*const red)[RED_PITCH] = sm.red[w];
 
     const int nblocks = (L + BT - 1) / BT;
-    typename io4<T>::raw ru, rd, rz, ro, ry;
-    auto issue_loads = [&](int blk) {
-        const int t0 = blk * BT + pq * BSL;
-        const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;  // rows past D contribute nothing
-        ru = io4<T>::template load<VEC>(gu + t0, nv);
-        rd = io4<T>::template load<VEC>(gdl + t0, nv);
-        ro = io4<T>::template load<VEC>(gdo + t0, nv);
-        if (has_z) {
-            rz = io4<T>::template load<VEC>(gz + t0, nv);
-            ry = io4<T>::template load<VEC>(gy + t0, nv);
+    // Loads are issued for 64 bytes of a row at a time (an aligned pair of bf16 blocks, one
+    // float block), so that neighbouring pieces of a cache line are requested together; more
+    // blocks per group would not fit the register budget.  slot = block index mod LG.
+    constexpr int LG = 64 / (BT * (int)sizeof(T));
+    typename io4<T>::raw ru[LG], rd[LG], rz[LG], ro[LG], ry[LG];
+    auto issue_group = [&](int grp) {
+#pragma unroll
+        for (int s = 0; s < LG; ++s) {
+            const int blk = grp * LG + s;
+            const int t0 = blk * BT + pq * BSL;
+            const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;  // rows past D contribute nothing
+            ru[s] = io4<T>::template load<VEC>(gu + t0, nv);
+            rd[s] = io4<T>::template load<VEC>(gdl + t0, nv);
+            ro[s] = io4<T>::template load<VEC>(gdo + t0, nv);
+            if (has_z) {
+                rz[s] = io4<T>::template load<VEC>(gz + t0, nv);
+                ry[s] = io4<T>::template load<VEC>(gy + t0, nv);
+            }
         }
     };
-    issue_loads(nblocks - 1);
+    issue_group((nblocks - 1) / LG);
 
     for (int blk = nblocks - 1; blk >= 0; --blk) {
         const int tc = blk * BT;
@@ -161,9 +169,15 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         float u4[BSL], sg4[BSL];  // u and d softplus(x)/dx, needed again in C
         {
             float v4[BSL], o4[BSL], dt4[BSL], du4[BSL], dy4[BSL];
-            io4<T>::unpack(ru, u4);
-            io4<T>::unpack(rd, v4);
-            io4<T>::unpack(ro, o4);
+            float z4[BSL], y4[BSL];
+            const int slot = blk & (LG - 1);  // uniform
+#pragma unroll
+            for (int s = 0; s < LG; ++s) {  // unrolled so the register arrays stay statically indexed
+                if (slot == s) {
+                    io4<T>::unpack(ru[s], u4); io4<T>::unpack(rd[s], v4); io4<T>::unpack(ro[s], o4);
+                    if (has_z) { io4<T>::unpack(rz[s], z4); io4<T>::unpack(ry[s], y4); }
+                }
+            }
 #pragma unroll
             for (int j = 0; j < BSL; ++j) {
                 float x = v4[j] + bias, sp, sg;
@@ -175,9 +189,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                 dy4[j] = o4[j];
             }
             if (has_z) {
-                float z4[BSL], y4[BSL], dz4[BSL];
-                io4<T>::unpack(rz, z4);
-                io4<T>::unpack(ry, y4);
+                float dz4[BSL];
 #pragma unroll
                 for (int j = 0; j < BSL; ++j) {
                     const float s = sigmoid_fast(z4[j]);
@@ -190,7 +202,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
             *reinterpret_cast<float4*>(&sm.du[pr][pq * BSL]) = make_float4(du4[0], du4[1], du4[2], du4[3]);
             *reinterpret_cast<float4*>(&sm.dy[pr][pq * BSL]) = make_float4(dy4[0], dy4[1], dy4[2], dy4[3]);
         }
-        if (blk > 0) issue_loads(blk - 1);  // in flight during the sweeps below
+        if ((blk & (LG - 1)) == 0 && blk > 0) issue_group(blk / LG - 1);  // in flight during the sweeps below
         __syncthreads();
 
         // ---- B1: recompute the states of the block -----------------------------------------
