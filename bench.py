@@ -62,6 +62,59 @@ def cpu_baseline(w, sample_dim):
                       % (sample_dim, nb, nl)}
 
 
+def decode_bench(dev, tokens=512):
+    """Single-token recurrent steps (batch 64, D 4096, N 16, bf16 I/O): stream launches and
+    the same launches replayed from a HIP graph."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    from paper_2312_00752_amd import workloads as wl
+    nb, nd, nn = wl.STEP_CONFIG[:3]
+    s = wl.make_step_inputs(nb, nd, nn, 8, io="bf16", seed=wl.STEP_CONFIG[5])
+    bf, f32 = torch.bfloat16, torch.float32
+    g = {k: torch.from_numpy(s[k]).to(dev).to(bf) for k in ("u", "delta", "z", "B", "C")}
+    A, Dk, bias = (torch.from_numpy(s[k]).to(dev) for k in ("A", "Dskip", "delta_bias"))
+    h = torch.zeros(nb, nd, nn, device=dev, dtype=f32)
+    out = torch.empty(nb, nd, device=dev, dtype=bf)
+
+    def step(t):
+        i = t % 8
+        B.ss_step(h, g["u"][i], g["delta"][i], A, g["B"][i], g["C"][i], Dskip=Dk, z_t=g["z"][i],
+                  delta_bias=bias, delta_softplus=True, out_t=out)
+
+    for t in range(16):
+        step(t)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in range(tokens):
+        step(t)
+    e1.record()
+    torch.cuda.synchronize()
+    us_stream = e0.elapsed_time(e1) * 1e3 / tokens
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for t in range(64):
+                step(t)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(tokens // 64):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us_graph = e0.elapsed_time(e1) * 1e3 / tokens
+    state_bytes = 2 * nb * nd * nn * 4 + nb * nd * 2 * 4 + 2 * nb * nn * 2
+    return {"workload": "ss_step batch %d, D %d, N %d, bf16 I/O" % (nb, nd, nn),
+            "us_per_token_stream": us_stream, "us_per_token_graph": us_graph,
+            "bytes_per_token": state_bytes,
+            "GBs_graph": state_bytes / (us_graph * 1e-6) / 1e9,
+            "frac_of_hbm_peak_graph": state_bytes / (us_graph * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +122,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mamba1p4b_layer_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the single-token step timing")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB streaming kernel (torch.neg; reference dispatch for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -160,6 +214,8 @@ def main():
                    "fwd_bwd_frac_of_hbm_peak": (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                    "fwd_traffic": traffic.get("scan_fwd_kernel_hbm_bytes")},
     }
+    if not args.no_decode:
+        res["decode"] = decode_bench(dev)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, sample_dim=nd)
     print(json.dumps(res))

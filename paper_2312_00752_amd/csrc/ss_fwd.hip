@@ -177,9 +177,10 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     }
 }
 
-// Single-token step: the same lane layout (4 lanes per row, 4 states each); the state is
-// read and written once, in place, with 16-byte accesses when N == 16.
-template <typename T>
+// Single-token step: 4 lanes per row, 4 states each; the state is read and written once,
+// in place.  With N == 16 every per-state operand (state, A, B_t, C_t) is one aligned
+// 16- or 8-byte access per lane.
+template <typename T, bool FULLN>
 __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
 {
     const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -199,36 +200,50 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     auto ld = [](const T* p, long i) -> float {
         if constexpr (sizeof(T) == 2) return bf16_to_f32(p[i]); else return p[i];
     };
+    float hv[STATES_PER_LANE], Av[STATES_PER_LANE], Bv[STATES_PER_LANE], Cv[STATES_PER_LANE];
+    float* hp = a.h + row * N + q * STATES_PER_LANE;
+    if (FULLN) {
+        const float4 h4 = *reinterpret_cast<const float4*>(hp);
+        const float4 A4 = *reinterpret_cast<const float4*>(a.A + (long)d * NPAD + q * STATES_PER_LANE);
+        hv[0] = h4.x; hv[1] = h4.y; hv[2] = h4.z; hv[3] = h4.w;
+        Av[0] = A4.x; Av[1] = A4.y; Av[2] = A4.z; Av[3] = A4.w;
+        const long bo = (long)b * NPAD + q * STATES_PER_LANE;
+        if constexpr (sizeof(T) == 2) {
+            const uint2 Bw = *reinterpret_cast<const uint2*>(B_t + bo);
+            const uint2 Cw = *reinterpret_cast<const uint2*>(C_t + bo);
+            Bv[0] = bf16_lo(Bw.x); Bv[1] = bf16_hi(Bw.x); Bv[2] = bf16_lo(Bw.y); Bv[3] = bf16_hi(Bw.y);
+            Cv[0] = bf16_lo(Cw.x); Cv[1] = bf16_hi(Cw.x); Cv[2] = bf16_lo(Cw.y); Cv[3] = bf16_hi(Cw.y);
+        } else {
+            const float4 B4 = *reinterpret_cast<const float4*>(B_t + bo);
+            const float4 C4 = *reinterpret_cast<const float4*>(C_t + bo);
+            Bv[0] = B4.x; Bv[1] = B4.y; Bv[2] = B4.z; Bv[3] = B4.w;
+            Cv[0] = C4.x; Cv[1] = C4.y; Cv[2] = C4.z; Cv[3] = C4.w;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < STATES_PER_LANE; ++k) {
+            const int n = q * STATES_PER_LANE + k;
+            const bool ok = n < N;
+            hv[k] = ok ? hp[k] : 0.0f;
+            Av[k] = ok ? a.A[(long)d * N + n] : 0.0f;
+            Bv[k] = ok ? ld(B_t, (long)b * N + n) : 0.0f;
+            Cv[k] = ok ? ld(C_t, (long)b * N + n) : 0.0f;
+        }
+    }
     const float u = ld(u_t, row);
     float x = ld(dl_t, row) + ((a.flags & F_HAS_DELTA_BIAS) ? a.bias[d] : 0.0f);
     float dt = x, sg;
     if (a.flags & F_DELTA_SOFTPLUS) softplus_sigmoid(x, dt, sg);
-    const float du = dt * u;
+    const float du = dt * u, dt2 = dt * LOG2E;
 
-    float hv[STATES_PER_LANE];
-    float* hp = a.h + row * N + q * STATES_PER_LANE;
-    const bool vec = (N == NPAD);
-    if (vec) {
-        const float4 t = *reinterpret_cast<const float4*>(hp);
-        hv[0] = t.x; hv[1] = t.y; hv[2] = t.z; hv[3] = t.w;
-    } else {
-#pragma unroll
-        for (int k = 0; k < STATES_PER_LANE; ++k)
-            hv[k] = (q * STATES_PER_LANE + k < N) ? hp[k] : 0.0f;
-    }
     float y = 0.0f;
 #pragma unroll
     for (int k = 0; k < STATES_PER_LANE; ++k) {
-        const int n = q * STATES_PER_LANE + k;
-        const bool ok = n < N;
-        const float A2 = ok ? a.A[(long)d * N + n] * LOG2E : 0.0f;
-        const float Bn = ok ? ld(B_t, (long)b * N + n) : 0.0f;
-        const float Cn = ok ? ld(C_t, (long)b * N + n) : 0.0f;
-        hv[k] = fmaf(exp2_fast(dt * A2), hv[k], du * Bn);
-        y = fmaf(Cn, hv[k], y);
+        hv[k] = fmaf(exp2_fast(dt2 * Av[k]), hv[k], du * Bv[k]);   // Eq. 4 and Eq. 2a
+        y = fmaf(Cv[k], hv[k], y);                                  // Eq. 2b
     }
     if (row_ok) {
-        if (vec) {
+        if (FULLN) {
             *reinterpret_cast<float4*>(hp) = make_float4(hv[0], hv[1], hv[2], hv[3]);
         } else {
 #pragma unroll
@@ -288,8 +303,19 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
 {
     const long lanes = (long)a.B * a.D * 4;
     const dim3 grid((unsigned)((lanes + 255) / 256)), block(256);
-    if (io_dtype == 0) step_kernel<float><<<grid, block, 0, stream>>>(a);
-    else step_kernel<bf16_t><<<grid, block, 0, stream>>>(a);
+    // the vector path also needs B_t / C_t rows aligned to 8 (bf16) or 16 (float) bytes,
+    // which N == 16 and the element-aligned base pointers checked by the caller give only
+    // when the bases themselves are that aligned
+    const size_t va = io_dtype == 0 ? 16 : 8;
+    const bool vec = a.N == NPAD && reinterpret_cast<uintptr_t>(a.B_t) % va == 0 &&
+                     reinterpret_cast<uintptr_t>(a.C_t) % va == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
+    if (io_dtype == 0) {
+        if (vec) step_kernel<float, true><<<grid, block, 0, stream>>>(a);
+        else step_kernel<float, false><<<grid, block, 0, stream>>>(a);
+    } else {
+        if (vec) step_kernel<bf16_t, true><<<grid, block, 0, stream>>>(a);
+        else step_kernel<bf16_t, false><<<grid, block, 0, stream>>>(a);
+    }
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
