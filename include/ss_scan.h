@@ -94,9 +94,14 @@ typedef struct {
  * ss_scan_fwd, 1 for ss_scan_fwd with SS_SAVE_FOR_BWD and the ss_scan_bwd that follows
  * it.  Only batch, dim, seqlen, dstate, io_dtype and the SS_HAS_Z flag are read.  The
  * content is opaque (state checkpoints every SS_CHECKPOINT_STEPS steps, the pre-gate
- * output when there is a gate, and per-batch partial sums of the backward pass); a
- * forward call with SS_SAVE_FOR_BWD fills it and the matching backward call must get the
- * same, untouched buffer.  256-byte alignment is required.  Returns 0 when none is needed. */
+ * output when there is a gate, per-segment carries when a long sequence with few rows is
+ * split across workgroups, and partial sums of the backward pass); a forward call with
+ * SS_SAVE_FOR_BWD fills it and the matching backward call must get the same, untouched
+ * buffer.  256-byte alignment is required.  Returns 0 when none is needed.
+ * A plain forward call (for_backward == 0) never requires a workspace: the size returned
+ * for it (non-zero only for few rows and a long sequence) is scratch that, if lent, lets
+ * the library split the sequence across workgroups; without it the call is correct but
+ * runs one workgroup per 64 rows. */
 size_t ss_workspace_bytes(const ss_fwd_params *p, int for_backward);
 
 /* Forward scan (Algorithm 2 steps 5-6 with the fusion of Appendix D).  Writes out, and

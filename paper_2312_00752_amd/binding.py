@@ -162,11 +162,13 @@ def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True, io_dtype=S
 
 def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0=None,
                 delta_softplus=False, out=None, h_last=None, return_last_state=False,
-                workspace=None, stream=None):
+                workspace=None, save_for_bwd=True, stream=None):
     """Enqueue the forward scan.  Returns (out, h_last or None).
 
-    ``workspace`` (a uint8 CUDA tensor of at least ``ss_workspace_bytes(...)`` bytes)
-    makes the call leave the checkpoints that ``ss_scan_bwd`` needs."""
+    ``workspace`` is a uint8 CUDA tensor of at least ``ss_workspace_bytes(...)`` bytes.  With
+    ``save_for_bwd`` (the default when a workspace is given) the call leaves what
+    ``ss_scan_bwd`` needs in it; without, the workspace only serves as scratch that lets
+    a long sequence with few rows be split across workgroups."""
     import torch
     p = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus)
     if out is None:
@@ -180,7 +182,8 @@ def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0
     if workspace is not None:
         p.workspace = _ptr(workspace, torch.uint8, None, "workspace")
         p.workspace_bytes = workspace.numel()
-        p.flags |= SS_SAVE_FOR_BWD
+        if save_for_bwd:
+            p.flags |= SS_SAVE_FOR_BWD
     rc = lib().ss_scan_fwd(ctypes.byref(p), _stream(stream))
     if rc != SS_OK:
         raise SsError(rc)

@@ -13,24 +13,56 @@ constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Workspace layout, each block 256-byte aligned:
-// [float checkpoints nck*B*D*16][io pre-gate y B*D*L, only with a gate]
-// [float dA partials B*D*16][float dD partials B*D][float dbias partials B*D]
-struct WsLayout {
-    size_t ckpt_off, y_off, dA_off, dD_off, db_off, total;
+// Split of the sequence across workgroups.  The scan kernels run one workgroup per 64 rows
+// of a batch entry; when that gives fewer workgroups than the chip has compute units and
+// the sequence is long, L is cut into segments (multiples of 32 steps) that are scanned
+// concurrently and stitched with a carry pass (Appendix D: the scan continues from the
+// state the previous chunk ended in; here the chunks run in parallel from aggregates).
+struct SegPlan {
+    int nseg, seg_len;
 };
-WsLayout ws_layout(const ss_fwd_params* p)
+SegPlan plan_segments(int B, int D, int L)
+{
+    const long wgs = (long)B * ((D + 63) / 64);
+    SegPlan s{1, (L + 31) / 32 * 32};
+    if (s.seg_len == 0) s.seg_len = 32;
+    if (wgs >= 256 || L < 2048) return s;
+    long want = (512 + wgs - 1) / wgs;                 // about two workgroups per compute unit
+    want = want < L / 512 ? want : L / 512;            // segments of at least 512 steps
+    if (want < 2) return s;
+    s.seg_len = (int)(((L + want - 1) / want + 31) / 32 * 32);
+    s.nseg = (L + s.seg_len - 1) / s.seg_len;
+    return s;
+}
+
+// Workspace layouts, each block 256-byte aligned.
+//   forward only:  [float seg_h nseg*B*D*16][float seg_sumdt nseg*B*D]        (only when split)
+//   with backward: [float checkpoints nck*B*D*16][io pre-gate y B*D*L, only with a gate]
+//                  [seg_h][seg_sumdt][float seg_g nseg*B*D*16]                 (only when split)
+//                  [float dA partials nseg*B*D*16][float dD partials nseg*B*D][float dbias partials nseg*B*D]
+struct WsLayout {
+    size_t ckpt_off, y_off, segh_off, segdt_off, segg_off, dA_off, dD_off, db_off, total;
+    SegPlan plan;
+};
+WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
 {
     const size_t nck = ((size_t)p->seqlen + SS_CHECKPOINT_STEPS - 1) / SS_CHECKPOINT_STEPS;
     const size_t rows = (size_t)p->batch * p->dim;
     const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
-    WsLayout w;
-    w.ckpt_off = 0;
-    w.y_off = round_up(nck * rows * 16 * sizeof(float), 256);
-    w.dA_off = w.y_off + ((p->flags & SS_HAS_Z) ? round_up(rows * (size_t)p->seqlen * esz, 256) : 0);
-    w.dD_off = w.dA_off + round_up(rows * 16 * sizeof(float), 256);
-    w.db_off = w.dD_off + round_up(rows * sizeof(float), 256);
-    w.total = w.db_off + round_up(rows * sizeof(float), 256);
+    WsLayout w{};
+    w.plan = plan_segments(p->batch, p->dim, p->seqlen);
+    const size_t ns = (size_t)w.plan.nseg, split = ns > 1 ? 1 : 0;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += round_up(bytes, 256); return at; };
+    w.ckpt_off = take(for_bwd ? nck * rows * 16 * sizeof(float) : 0);
+    w.y_off = take(for_bwd && (p->flags & SS_HAS_Z) ? rows * (size_t)p->seqlen * esz : 0);
+    w.segh_off = take(split * ns * rows * 16 * sizeof(float));
+    w.segdt_off = take(split * ns * rows * sizeof(float));
+    w.segg_off = take(for_bwd ? split * ns * rows * 16 * sizeof(float) : 0);
+    w.dA_off = take(for_bwd ? ns * rows * 16 * sizeof(float) : 0);
+    w.dD_off = take(for_bwd ? ns * rows * sizeof(float) : 0);
+    w.db_off = take(for_bwd ? ns * rows * sizeof(float) : 0);
+    w.total = off;
     return w;
 }
 
@@ -57,7 +89,7 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd)
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
     if (for_bwd || (p->flags & SS_SAVE_FOR_BWD)) {
-        const size_t need = ws_layout(p).total;
+        const size_t need = ws_layout(p, true).total;
         if (!p->workspace || p->workspace_bytes < need) return SS_ERR_WORKSPACE;
         if (!aligned(p->workspace, 256)) return SS_ERR_ALIGN;
     }
@@ -77,6 +109,10 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p)
     a.h_last = (p->flags & SS_WRITE_H_LAST) ? p->h_last : nullptr;
     a.ckpt = nullptr;
     a.ysave = nullptr;
+    a.nseg = 1;
+    a.seg_len = (p->seqlen + 31) / 32 * 32 + 32;
+    a.seg_h = nullptr;
+    a.seg_sumdt = nullptr;
     return a;
 }
 
@@ -86,9 +122,8 @@ extern "C" {
 
 size_t ss_workspace_bytes(const ss_fwd_params* p, int for_backward)
 {
-    if (!p || !for_backward) return 0;
-    if (p->batch < 1 || p->dim < 1 || p->seqlen < 0) return 0;
-    return ws_layout(p).total;
+    if (!p || p->batch < 1 || p->dim < 1 || p->seqlen < 0) return 0;
+    return ws_layout(p, for_backward != 0).total;
 }
 
 int ss_scan_fwd(const ss_fwd_params* p, void* stream)
@@ -96,11 +131,24 @@ int ss_scan_fwd(const ss_fwd_params* p, void* stream)
     const int rc = check_fwd(p, false);
     if (rc != SS_OK) return rc;
     ss::FwdArgs a = make_fwd_args(p);
+    char* ws = static_cast<char*>(p->workspace);
     if (p->flags & SS_SAVE_FOR_BWD) {
-        const WsLayout w = ws_layout(p);
-        char* ws = static_cast<char*>(p->workspace);
+        const WsLayout w = ws_layout(p, true);
         a.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
         a.ysave = (p->flags & SS_HAS_Z) ? ws + w.y_off : nullptr;
+        if (w.plan.nseg > 1) {
+            a.nseg = w.plan.nseg; a.seg_len = w.plan.seg_len;
+            a.seg_h = reinterpret_cast<float*>(ws + w.segh_off);
+            a.seg_sumdt = reinterpret_cast<float*>(ws + w.segdt_off);
+        }
+    } else {
+        // a plain forward call splits the sequence only if the caller lent the scratch for it
+        const WsLayout w = ws_layout(p, false);
+        if (w.plan.nseg > 1 && ws && p->workspace_bytes >= w.total && aligned(ws, 256)) {
+            a.nseg = w.plan.nseg; a.seg_len = w.plan.seg_len;
+            a.seg_h = reinterpret_cast<float*>(ws + w.segh_off);
+            a.seg_sumdt = reinterpret_cast<float*>(ws + w.segdt_off);
+        }
     }
     return ss::launch_fwd(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
 }
@@ -124,7 +172,7 @@ int ss_scan_bwd(const ss_bwd_params* p, void* stream)
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
 
-    const WsLayout w = ws_layout(f);
+    const WsLayout w = ws_layout(f, true);
     char* ws = static_cast<char*>(f->workspace);
     ss::BwdArgs a{};
     a.f = make_fwd_args(f);
@@ -132,6 +180,12 @@ int ss_scan_bwd(const ss_bwd_params* p, void* stream)
     a.f.h_last = nullptr;
     a.f.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
     a.f.ysave = (f->flags & SS_HAS_Z) ? ws + w.y_off : nullptr;
+    if (w.plan.nseg > 1) {
+        a.f.nseg = w.plan.nseg; a.f.seg_len = w.plan.seg_len;
+        a.f.seg_h = reinterpret_cast<float*>(ws + w.segh_off);
+        a.f.seg_sumdt = reinterpret_cast<float*>(ws + w.segdt_off);
+        a.seg_g = reinterpret_cast<float*>(ws + w.segg_off);
+    }
     a.dout = p->dout; a.dh_last = p->dh_last;
     a.du = p->du; a.ddelta = p->ddelta; a.dz = (f->flags & SS_HAS_Z) ? p->dz : nullptr;
     a.dB = p->dB; a.dC = p->dC;

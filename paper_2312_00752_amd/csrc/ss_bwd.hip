@@ -95,6 +95,10 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     const int L = f.L, N = f.N;
     const bool has_z = f.flags & F_HAS_Z, has_D = f.flags & F_HAS_D;
     const bool softplus = f.flags & F_DELTA_SOFTPLUS;
+    const int seg = blockIdx.y;  // segment of the sequence (see scan_fwd_kernel)
+    const int blk_begin = seg * (f.seg_len / BT);
+    const int blk_end = min((L + BT - 1) / BT, (seg + 1) * (f.seg_len / BT));
+    const long seg_rows = (long)seg * f.B * f.D;
 
     // ---- pointwise view: thread -> (row pr, 4-step slice pq) -----------------------------
     const int pr = tid >> 2, pq = tid & 3;
@@ -127,7 +131,8 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
         A2[k] = n_ok[k] ? f.A[(long)sd * N + nc] * LOG2E : 0.0f;
-        ag[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;  // abar_L g_L := dh_last
+        if (seg == f.nseg - 1) ag[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;  // abar_L g_L := dh_last
+        else ag[k] = a.seg_g[(seg_rows + srow) * NPAD + w * STATES_PER_LANE + k];
         dA[k] = 0.0f;
         gB[k] = static_cast<const T*>(f.Bm) + ((long)b * N + nc) * L;
         gC[k] = static_cast<const T*>(f.Cm) + ((long)b * N + nc) * L;
@@ -135,7 +140,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     float* const dbc = &sm.dbc[w][0][0][0];
     float (*const red)[RED_PITCH] = sm.red[w];
 
-    const int nblocks = (L + BT - 1) / BT;
+    const int nblocks = blk_end;
     // Loads are issued for 64 bytes of a row at a time (an aligned pair of bf16 blocks, one
     // float block), so that neighbouring pieces of a cache line are requested together; more
     // blocks per group would not fit the register budget.  slot = block index mod LG.
@@ -158,7 +163,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     };
     issue_group((nblocks - 1) / LG);
 
-    for (int blk = nblocks - 1; blk >= 0; --blk) {
+    for (int blk = nblocks - 1; blk >= blk_begin; --blk) {
         const int tc = blk * BT;
         const int t0 = tc + pq * BSL;
         const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;
@@ -202,7 +207,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
             *reinterpret_cast<float4*>(&sm.du[pr][pq * BSL]) = make_float4(du4[0], du4[1], du4[2], du4[3]);
             *reinterpret_cast<float4*>(&sm.dy[pr][pq * BSL]) = make_float4(dy4[0], dy4[1], dy4[2], dy4[3]);
         }
-        if ((blk & (LG - 1)) == 0 && blk > 0) issue_group(blk / LG - 1);  // in flight during the sweeps below
+        if ((blk & (LG - 1)) == 0 && blk > blk_begin) issue_group(blk / LG - 1);  // in flight during the sweeps below
         __syncthreads();
 
         // ---- B1: recompute the states of the block -----------------------------------------
@@ -318,9 +323,9 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 
     // ---- per-row results --------------------------------------------------------------------
     if (s_ok) {
-        float4* pa = reinterpret_cast<float4*>(a.dA_part + srow * NPAD) + w;
+        float4* pa = reinterpret_cast<float4*>(a.dA_part + (seg_rows + srow) * NPAD) + w;
         *pa = make_float4(dA[0], dA[1], dA[2], dA[3]);
-        if (a.dh0) {
+        if (a.dh0 && seg == 0) {
 #pragma unroll
             for (int k = 0; k < STATES_PER_LANE; ++k)
                 if (n_ok[k]) a.dh0[srow * N + w * STATES_PER_LANE + k] = ag[k];
@@ -331,8 +336,134 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     db_acc += __shfl_xor(db_acc, 1);
     db_acc += __shfl_xor(db_acc, 2);
     if (p_ok && pq == 0) {
-        a.dD_part[prow] = dD_acc;
-        a.db_part[prow] = db_acc;
+        a.dD_part[seg_rows + prow] = dD_acc;
+        a.db_part[seg_rows + prow] = db_acc;
+    }
+}
+
+// Adjoint aggregate of a segment, for a sequence split across workgroups: runs only the
+// adjoint recurrence g = C dy + abar+ g+ over the segment, from a zero carry (last segment:
+// from dh_last), and leaves the carry abar g at the segment's first step in seg_g.  Needs
+// no states, so it is the forward kernel's loop structure walked backwards: 32-step chunks,
+// dt and dy staged through LDS, C on the scalar path.
+template <typename T, bool VEC, bool FULLN>
+__global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
+    __shared__ __attribute__((aligned(16))) float s_dy[ROWS][TPAD];
+    const FwdArgs& f = a.f;
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & (WAVE - 1);
+    const int groups = (f.D + ROWS - 1) / ROWS;
+    const int b = blockIdx.x / groups;
+    const int d0 = (blockIdx.x % groups) * ROWS;
+    const int L = f.L, N = f.N;
+    const bool has_z = f.flags & F_HAS_Z, softplus = f.flags & F_DELTA_SOFTPLUS;
+    const int seg = blockIdx.y + 1;  // segment 0 passes nothing on
+    const int c_begin = seg * (f.seg_len / CHUNK_T);
+    const int c_end = min((L + CHUNK_T - 1) / CHUNK_T, (seg + 1) * (f.seg_len / CHUNK_T));
+
+    const int pr = tid >> 2, pq = tid & 3;
+    const bool p_ok = d0 + pr < f.D;
+    const int pd = p_ok ? d0 + pr : f.D - 1;
+    const long prow = (long)b * f.D + pd;
+    const T* __restrict__ gdl = static_cast<const T*>(f.delta) + prow * L;
+    const T* __restrict__ gz = static_cast<const T*>(f.z) + prow * L;
+    const T* __restrict__ gdo = static_cast<const T*>(a.dout) + prow * L;
+    const float bias = (f.flags & F_HAS_DELTA_BIAS) ? f.bias[pd] : 0.0f;
+
+    const bool s_ok = d0 + lane < f.D;
+    const int sd = s_ok ? d0 + lane : f.D - 1;
+    const long srow = (long)b * f.D + sd;
+    float A2[STATES_PER_LANE], ag[STATES_PER_LANE];
+    const T* __restrict__ gC[STATES_PER_LANE];
+    bool n_ok[STATES_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < STATES_PER_LANE; ++k) {
+        const int n = w * STATES_PER_LANE + k;
+        n_ok[k] = n < N;
+        const int nc = n_ok[k] ? n : 0;
+        A2[k] = n_ok[k] ? f.A[(long)sd * N + nc] * LOG2E : 0.0f;
+        ag[k] = (seg == f.nseg - 1 && n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;
+        gC[k] = static_cast<const T*>(f.Cm) + ((long)b * N + nc) * L;
+    }
+    typename io8<T>::raw rd, rz, ro;
+    auto issue_loads = [&](int c) {
+        const int t0 = c * CHUNK_T + pq * SLICE;
+        const int nv = p_ok ? min(max(L - t0, 0), SLICE) : 0;
+        rd = io8<T>::template load<VEC>(gdl + t0, nv);
+        ro = io8<T>::template load<VEC>(gdo + t0, nv);
+        if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
+    };
+    issue_loads(c_end - 1);
+    for (int c = c_end - 1; c >= c_begin; --c) {
+        const int tc = c * CHUNK_T;
+        const int nv = p_ok ? min(max(L - (tc + pq * SLICE), 0), SLICE) : 0;
+        {
+            float v8[SLICE], o8[SLICE], z8[SLICE], dt8[SLICE];
+            io8<T>::unpack(rd, v8);
+            io8<T>::unpack(ro, o8);
+            if (has_z) io8<T>::unpack(rz, z8);
+#pragma unroll
+            for (int j = 0; j < SLICE; ++j) {
+                float x = v8[j] + bias, sp, sg;
+                if (softplus) softplus_sigmoid(x, sp, sg); else sp = x;
+                dt8[j] = (j < nv) ? sp : 0.0f;
+                if (has_z) o8[j] *= z8[j] * sigmoid_fast(z8[j]);
+            }
+            float4* pd4 = reinterpret_cast<float4*>(&s_dt[pr][pq * SLICE]);
+            float4* py4 = reinterpret_cast<float4*>(&s_dy[pr][pq * SLICE]);
+            pd4[0] = make_float4(dt8[0], dt8[1], dt8[2], dt8[3]);
+            pd4[1] = make_float4(dt8[4], dt8[5], dt8[6], dt8[7]);
+            py4[0] = make_float4(o8[0], o8[1], o8[2], o8[3]);
+            py4[1] = make_float4(o8[4], o8[5], o8[6], o8[7]);
+        }
+        if (c > c_begin) issue_loads(c - 1);
+        __syncthreads();
+        constexpr int NG = CHUNK_T / GROUP_T;
+#pragma unroll
+        for (int g = NG - 1; g >= 0; --g) {
+            bc_group<T> Cg[STATES_PER_LANE];
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k)
+                Cg[k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+            const float4 dt4 = *reinterpret_cast<const float4*>(&s_dt[lane][g * GROUP_T]);
+            const float4 dy4 = *reinterpret_cast<const float4*>(&s_dy[lane][g * GROUP_T]);
+#pragma unroll
+            for (int j = GROUP_T - 1; j >= 0; --j) {
+                const float dt = f4_get(dt4, j), dy = f4_get(dy4, j);
+#pragma unroll
+                for (int k = 0; k < STATES_PER_LANE; ++k)
+                    ag[k] = exp2_fast(dt * A2[k]) * fmaf(Cg[k].get(j), dy, ag[k]);
+            }
+        }
+        __syncthreads();
+    }
+    if (s_ok) {
+        float4* dst = reinterpret_cast<float4*>(a.seg_g + ((long)seg * f.B * f.D + srow) * NPAD) + w;
+        *dst = make_float4(ag[0], ag[1], ag[2], ag[3]);
+    }
+}
+
+// Turns the segments' local adjoint carries into incoming ones, in place, walking the
+// segments backwards: in[nseg-2] = loc[nseg-1];  in[s-1] = exp(A * sum_dt[s]) * in[s] + loc[s].
+__global__ void carry_bwd_kernel(const BwdArgs a)
+{
+    const FwdArgs& f = a.f;
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long rows = (long)f.B * f.D;
+    if (i >= rows * NPAD) return;
+    const long row = i / NPAD;
+    const int n = i % NPAD, d = row % f.D;
+    const float A2 = n < f.N ? f.A[(long)d * f.N + n] * LOG2E : 0.0f;
+    float carry = a.seg_g[(long)(f.nseg - 1) * rows * NPAD + i];  // loc of the last segment (includes dh_last)
+    for (int s = f.nseg - 2; s >= 0; --s) {
+        float* slot = a.seg_g + (long)s * rows * NPAD + i;
+        const float loc = *slot;  // segment 0 has no aggregate: its value is not used
+        *slot = carry;            // carry entering segment s from the right
+        if (s == 0) break;
+        carry = fmaf(exp2_fast(A2 * f.seg_sumdt[(long)s * rows + row]), carry, loc);
     }
 }
 
@@ -352,7 +483,7 @@ __global__ void finalize_kernel(const BwdArgs a, int have_partials)
     if (d >= a.f.D) return;
     float sA = 0.0f, sD = 0.0f, sb = 0.0f;
     if (have_partials) {
-        for (int b = 0; b < a.f.B; ++b) {
+        for (int b = 0; b < a.f.B * a.f.nseg; ++b) {  // per segment and batch entry
             const long row = (long)b * a.f.D + d;
             sA += a.dA_part[row * NPAD + n];
             if (n == 0) { sD += a.dD_part[row]; sb += a.db_part[row]; }
@@ -382,7 +513,12 @@ static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
             return -1;
         configured = true;
     }
-    kern<<<grid, dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
+    if (a.f.nseg > 1) {
+        adjoint_agg_kernel<T, VEC, FULLN><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
+        const long n = (long)a.f.B * a.f.D * NPAD;
+        carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    }
+    kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

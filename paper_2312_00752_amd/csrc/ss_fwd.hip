@@ -15,7 +15,12 @@ namespace ss {
 // The state never leaves registers between chunks (Appendix D: the scan continues from
 // the previous chunk's state).  Steps past the end of the sequence use dt = 0, which is
 // the identity of the recurrence (abar = 1, input term 0).
-template <typename T, bool VEC, bool FULLN>
+//
+// When the sequence is split into segments (blockIdx.y), the kernel runs twice: first with
+// AGG = true on every segment but the last, from the zero state (segment 0: from h0),
+// producing only the segment's end state and the sum of its step sizes; then, after
+// carry_fwd_kernel has turned those into each segment's incoming state, with AGG = false.
+template <typename T, bool VEC, bool FULLN, bool AGG>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -29,8 +34,11 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     const int b = blockIdx.x / groups;
     const int d0 = (blockIdx.x % groups) * ROWS;
     const int L = a.L, N = a.N;
-    const bool has_z = a.flags & F_HAS_Z, has_D = a.flags & F_HAS_D;
+    const bool has_z = !AGG && (a.flags & F_HAS_Z), has_D = !AGG && (a.flags & F_HAS_D);
     const bool softplus = a.flags & F_DELTA_SOFTPLUS;
+    const int seg = blockIdx.y;
+    const int c_begin = seg * (a.seg_len / CHUNK_T);
+    const int c_end = min((L + CHUNK_T - 1) / CHUNK_T, (seg + 1) * (a.seg_len / CHUNK_T));
 
     // ---- pointwise view: thread -> (row pr, slice pq) -----------------------------------
     const int pr = tid >> 2, pq = tid & 3;
@@ -58,12 +66,13 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
         A2[k] = n_ok[k] ? a.A[(long)sd * N + nc] * LOG2E : 0.0f;
-        h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * N + nc] : 0.0f;
+        if (seg == 0) h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * N + nc] : 0.0f;
+        else h[k] = AGG ? 0.0f : a.seg_h[((long)seg * a.B * a.D + srow) * NPAD + w * STATES_PER_LANE + k];
         gB[k] = static_cast<const T*>(a.Bm) + ((long)b * N + nc) * L;
         gC[k] = static_cast<const T*>(a.Cm) + ((long)b * N + nc) * L;
     }
+    float sum_dt = 0.0f;  // AGG: this thread's share of the segment's sum of step sizes
 
-    const int nchunks = (L + CHUNK_T - 1) / CHUNK_T;
     typename io8<T>::raw ru, rd, rz;
     auto issue_loads = [&](int c) {
         const int t0 = c * CHUNK_T + pq * SLICE;
@@ -72,9 +81,9 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         rd = io8<T>::template load<VEC>(gdl + t0, nv);
         if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
     };
-    issue_loads(0);
+    issue_loads(c_begin);
 
-    for (int c = 0; c < nchunks; ++c) {
+    for (int c = c_begin; c < c_end; ++c) {
         float u8[SLICE], z8[SLICE], v8[SLICE];
         const int tc = c * CHUNK_T;
         const int t0 = tc + pq * SLICE;
@@ -92,6 +101,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 sp = (j < nv) ? sp : 0.0f;
                 dt8[j] = sp;
                 du8[j] = sp * u8[j];
+                if (AGG) sum_dt += sp;
             }
             float4* pd4 = reinterpret_cast<float4*>(&s_dt[pr][pq * SLICE]);
             float4* pu4 = reinterpret_cast<float4*>(&s_du[pr][pq * SLICE]);
@@ -102,13 +112,13 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         }
         // checkpoint: the state entering every CKPT_T-step block (read back by the backward pass)
         auto save_ckpt = [&](int block) {
-            if (a.ckpt && s_ok && block * CKPT_T < L) {
+            if (!AGG && a.ckpt && s_ok && block * CKPT_T < L) {
                 float4* ck = reinterpret_cast<float4*>(a.ckpt + (((long)block * a.B + b) * a.D + sd) * NPAD) + w;
                 *ck = make_float4(h[0], h[1], h[2], h[3]);
             }
         };
         save_ckpt(c * (CHUNK_T / CKPT_T));
-        if (c + 1 < nchunks) issue_loads(c + 1);  // in flight during the scan below
+        if (c + 1 < c_end) issue_loads(c + 1);  // in flight during the scan below
         __syncthreads();
         // ---- B: sequential recurrence over the chunk ---------------------------------
         constexpr int NG = CHUNK_T / GROUP_T;
@@ -138,15 +148,16 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 for (int k = 0; k < STATES_PER_LANE; ++k) {
                     const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
                     h[k] = fmaf(abar, h[k], du * Bg[cur][k].get(j));             // Eq. 2a
-                    y = fmaf(Cg[cur][k].get(j), h[k], y);                        // Eq. 2b
+                    if (!AGG) y = fmaf(Cg[cur][k].get(j), h[k], y);              // Eq. 2b
                 }
                 yp[j] = y;
             }
-            *reinterpret_cast<float4*>(&s_yp[w][lane][tl]) = make_float4(yp[0], yp[1], yp[2], yp[3]);
+            if (!AGG)
+                *reinterpret_cast<float4*>(&s_yp[w][lane][tl]) = make_float4(yp[0], yp[1], yp[2], yp[3]);
         }
         __syncthreads();
         // ---- C: pointwise post-processing --------------------------------------------
-        {
+        if (!AGG) {
             float y8[SLICE];
 #pragma unroll
             for (int j = 0; j < SLICE; ++j) y8[j] = has_D ? Dsk * u8[j] : 0.0f;
@@ -170,12 +181,41 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         // finished reading (barrier above), and s_yp is rewritten only after the next barrier
     }
 
-    if (a.h_last && s_ok) {
+    if (AGG) {
+        if (s_ok) {
+            float4* dst = reinterpret_cast<float4*>(a.seg_h + ((long)seg * a.B * a.D + srow) * NPAD) + w;
+            *dst = make_float4(h[0], h[1], h[2], h[3]);
+        }
+        sum_dt += __shfl_xor(sum_dt, 1);
+        sum_dt += __shfl_xor(sum_dt, 2);
+        if (p_ok && pq == 0) a.seg_sumdt[(long)seg * a.B * a.D + prow] = sum_dt;
+    } else if (a.h_last && s_ok && seg == a.nseg - 1) {
 #pragma unroll
         for (int k = 0; k < STATES_PER_LANE; ++k)
             if (n_ok[k]) a.h_last[srow * N + w * STATES_PER_LANE + k] = h[k];
     }
 }
+
+// Turns the segments' local end states into incoming states, in place:
+// in[1] = loc[0];  in[s+1] = exp(A * sum_dt[s]) * in[s] + loc[s]   (one thread per (b,d,n)).
+__global__ void carry_fwd_kernel(const FwdArgs a)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long rows = (long)a.B * a.D;
+    if (i >= rows * NPAD) return;
+    const long row = i / NPAD;
+    const int n = i % NPAD, d = row % a.D;
+    const float A2 = n < a.N ? a.A[(long)d * a.N + n] * LOG2E : 0.0f;
+    float carry = a.seg_h[i];  // loc[0]: already includes h0
+    for (int s = 1; s < a.nseg; ++s) {
+        float* slot = a.seg_h + (long)s * rows * NPAD + i;
+        const float loc = *slot;  // read before it is overwritten
+        *slot = carry;            // incoming state of segment s
+        if (s == a.nseg - 1) break;  // the last segment has no aggregate
+        carry = fmaf(exp2_fast(A2 * a.seg_sumdt[(long)s * rows + row]), carry, loc);
+    }
+}
+
 
 // Single-token step: 4 lanes per row, 4 states each; the state is read and written once,
 // in place.  With N == 16 every per-state operand (state, A, B_t, C_t) is one aligned
@@ -272,6 +312,19 @@ __global__ void copy_state_kernel(const float* __restrict__ src, float* __restri
     if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
+template <typename T, bool VEC, bool FULLN>
+static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
+{
+    const int groups = (a.D + ROWS - 1) / ROWS;
+    const dim3 block(THREADS);
+    if (a.nseg > 1) {
+        scan_fwd_kernel<T, VEC, FULLN, true><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
+        const long n = (long)a.B * a.D * NPAD;
+        carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    }
+    scan_fwd_kernel<T, VEC, FULLN, false><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+}
+
 int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)
 {
     if (a.L == 0) {
@@ -282,20 +335,16 @@ int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)
         }
         return hipGetLastError() == hipSuccess ? 0 : -1;
     }
-    const int groups = (a.D + ROWS - 1) / ROWS;
-    const dim3 grid((unsigned)(a.B * groups)), block(THREADS);
     const bool fulln = a.N == NPAD;
-#define SS_LAUNCH_FWD(T, VEC, FULLN) scan_fwd_kernel<T, VEC, FULLN><<<grid, block, 0, stream>>>(a)
     if (io_dtype == 0) {
-        if (a.vec_ok && fulln) SS_LAUNCH_FWD(float, true, true);
-        else if (a.vec_ok) SS_LAUNCH_FWD(float, true, false);
-        else SS_LAUNCH_FWD(float, false, false);
+        if (a.vec_ok && fulln) launch_fwd_t<float, true, true>(a, stream);
+        else if (a.vec_ok) launch_fwd_t<float, true, false>(a, stream);
+        else launch_fwd_t<float, false, false>(a, stream);
     } else {
-        if (a.vec_ok && fulln) SS_LAUNCH_FWD(bf16_t, true, true);
-        else if (a.vec_ok) SS_LAUNCH_FWD(bf16_t, true, false);
-        else SS_LAUNCH_FWD(bf16_t, false, false);
+        if (a.vec_ok && fulln) launch_fwd_t<bf16_t, true, true>(a, stream);
+        else if (a.vec_ok) launch_fwd_t<bf16_t, true, false>(a, stream);
+        else launch_fwd_t<bf16_t, false, false>(a, stream);
     }
-#undef SS_LAUNCH_FWD
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -25,6 +25,11 @@ struct FwdArgs {
     float* h_last;  // may be null
     float* ckpt;    // [checkpoint][B][D][16]: state entering every 16-step block, or null
     void* ysave;    // (B,D,L) io dtype: y before the gate, kept for the backward pass, or null
+    // Split of the sequence across workgroups (few rows, long L).  Segment s covers steps
+    // [s*seg_len, min(L, (s+1)*seg_len)); seg_len is a multiple of 32.  nseg == 1: no split.
+    int seg_len, nseg;
+    float* seg_h;      // [nseg][B][D][16]: local end state of a segment, then its incoming state
+    float* seg_sumdt;  // [nseg][B][D]: sum of the step sizes of a segment
 };
 
 struct BwdArgs {
@@ -33,8 +38,9 @@ struct BwdArgs {
     const float* dh_last;
     void *du, *ddelta, *dz;
     float *dB, *dC;             // (B,N,L), zeroed before the scan kernel, atomically accumulated
-    float *dA_part;             // [B][D][16] per-batch partial sums
-    float *dD_part, *db_part;   // [B][D]
+    float *dA_part;             // [nseg][B][D][16] partial sums per segment and batch entry
+    float *dD_part, *db_part;   // [nseg][B][D]
+    float* seg_g;               // [nseg][B][D][16]: adjoint carry of a segment (local, then incoming)
     float* dh0;
     float *dA, *dD, *dbias;     // final outputs of the reduction kernel
 };
