@@ -31,6 +31,9 @@ SegPlan plan_segments(int B, int D, int L)
     want = want < L / 512 ? want : L / 512;            // segments of at least 512 steps
     if (want < 2) return s;
     s.seg_len = (int)(((L + want - 1) / want + 31) / 32 * 32);
+    // A segment length that is a large power of two makes every workgroup walk the memory
+    // channels in lockstep (all segment starts alias); an odd multiple of 32 steps staggers them.
+    if (s.seg_len % 256 == 0) s.seg_len += 160;
     s.nseg = (L + s.seg_len - 1) / s.seg_len;
     return s;
 }

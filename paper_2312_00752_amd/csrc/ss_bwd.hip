@@ -162,9 +162,12 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         }
     };
     issue_group((nblocks - 1) / LG);
+    float touched = touch_bc<T>(f.Bm, f.Cm, b, N, L, w, lane, (nblocks - 1) * BT);
 
     for (int blk = nblocks - 1; blk >= blk_begin; --blk) {
         const int tc = blk * BT;
+        consume_touch(touched);
+        touched = touch_bc<T>(f.Bm, f.Cm, b, N, L, w, lane, (blk - 1) * BT);
         const int t0 = tc + pq * BSL;
         const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;
         // the state entering this block, left by the forward pass
@@ -397,8 +400,11 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
         if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
     };
     issue_loads(c_end - 1);
+    float touched = touch_bc<T>(f.Cm, f.Cm, b, N, L, w, lane, (c_end - 1) * CHUNK_T);
     for (int c = c_end - 1; c >= c_begin; --c) {
         const int tc = c * CHUNK_T;
+        consume_touch(touched);
+        touched = touch_bc<T>(f.Cm, f.Cm, b, N, L, w, lane, (c - 1) * CHUNK_T);
         const int nv = p_ok ? min(max(L - (tc + pq * SLICE), 0), SLICE) : 0;
         {
             float v8[SLICE], o8[SLICE], z8[SLICE], dt8[SLICE];
@@ -458,12 +464,24 @@ __global__ void carry_bwd_kernel(const BwdArgs a)
     const int n = i % NPAD, d = row % f.D;
     const float A2 = n < f.N ? f.A[(long)d * f.N + n] * LOG2E : 0.0f;
     float carry = a.seg_g[(long)(f.nseg - 1) * rows * NPAD + i];  // loc of the last segment (includes dh_last)
-    for (int s = f.nseg - 2; s >= 0; --s) {
-        float* slot = a.seg_g + (long)s * rows * NPAD + i;
-        const float loc = *slot;  // segment 0 has no aggregate: its value is not used
-        *slot = carry;            // carry entering segment s from the right
-        if (s == 0) break;
-        carry = fmaf(exp2_fast(A2 * f.seg_sumdt[(long)s * rows + row]), carry, loc);
+    // as in carry_fwd_kernel: loads of a batch of segments first, then the serial chain
+    constexpr int CARRY_BATCH = 16;
+    for (int s0 = f.nseg - 2; s0 >= 0; s0 -= CARRY_BATCH) {
+        float loc[CARRY_BATCH], sdt[CARRY_BATCH];
+#pragma unroll
+        for (int j = 0; j < CARRY_BATCH; ++j) {
+            const int s = s0 - j;
+            loc[j] = s >= 1 ? a.seg_g[(long)s * rows * NPAD + i] : 0.0f;   // segment 0 has no aggregate
+            sdt[j] = s >= 1 ? f.seg_sumdt[(long)s * rows + row] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < CARRY_BATCH; ++j) {
+            const int s = s0 - j;
+            if (s >= 0) {
+                a.seg_g[(long)s * rows * NPAD + i] = carry;  // carry entering segment s from the right
+                carry = fmaf(exp2_fast(A2 * sdt[j]), carry, loc[j]);
+            }
+        }
     }
 }
 
@@ -483,6 +501,7 @@ __global__ void finalize_kernel(const BwdArgs a, int have_partials)
     if (d >= a.f.D) return;
     float sA = 0.0f, sD = 0.0f, sb = 0.0f;
     if (have_partials) {
+#pragma unroll 8
         for (int b = 0; b < a.f.B * a.f.nseg; ++b) {  // per segment and batch entry
             const long row = (long)b * a.f.D + d;
             sA += a.dA_part[row * NPAD + n];

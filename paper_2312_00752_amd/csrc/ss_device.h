@@ -294,4 +294,23 @@ __device__ __forceinline__ bc_group<T> load_bc(const T* __restrict__ p, int t, i
     return g;
 }
 
+// The scalar loads above are issued only one group (4 steps) ahead, which hides an L2 hit
+// but not a trip to HBM.  When B and C are not already L2-resident (one batch entry, long
+// sequence), the wave therefore touches the lines it will need one chunk later with
+// ordinary vector loads: lanes 0..3 one element of each of its B rows, lanes 4..7 of its C
+// rows, at step t.  The value is only handed to `consume_touch` an iteration later.
+template <typename T>
+__device__ __forceinline__ float touch_bc(const void* Bm, const void* Cm, int b, int N, int L, int w,
+                                           int lane, int t)
+{
+    float v = 0.0f;
+    if (lane < 2 * STATES_PER_LANE && t >= 0 && t < L) {
+        const int n = min(w * STATES_PER_LANE + (lane & 3), N - 1);
+        const T* p = static_cast<const T*>(lane < STATES_PER_LANE ? Bm : Cm) + ((long)b * N + n) * L + t;
+        if constexpr (sizeof(T) == 2) v = bf16_to_f32(*p); else v = *p;
+    }
+    return v;
+}
+__device__ __forceinline__ void consume_touch(float v) { asm volatile("" ::"v"(v)); }
+
 }  // namespace ss

@@ -82,9 +82,12 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
     };
     issue_loads(c_begin);
+    float touched = touch_bc<T>(a.Bm, a.Cm, b, N, L, w, lane, c_begin * CHUNK_T);
 
     for (int c = c_begin; c < c_end; ++c) {
         float u8[SLICE], z8[SLICE], v8[SLICE];
+        consume_touch(touched);
+        touched = touch_bc<T>(a.Bm, a.Cm, b, N, L, w, lane, (c + 1) * CHUNK_T);
         const int tc = c * CHUNK_T;
         const int t0 = tc + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);
@@ -207,15 +210,27 @@ __global__ void carry_fwd_kernel(const FwdArgs a)
     const int n = i % NPAD, d = row % a.D;
     const float A2 = n < a.N ? a.A[(long)d * a.N + n] * LOG2E : 0.0f;
     float carry = a.seg_h[i];  // loc[0]: already includes h0
-    for (int s = 1; s < a.nseg; ++s) {
-        float* slot = a.seg_h + (long)s * rows * NPAD + i;
-        const float loc = *slot;  // read before it is overwritten
-        *slot = carry;            // incoming state of segment s
-        if (s == a.nseg - 1) break;  // the last segment has no aggregate
-        carry = fmaf(exp2_fast(A2 * a.seg_sumdt[(long)s * rows + row]), carry, loc);
+    // Segments are taken CARRY_BATCH at a time: their loads do not depend on the carry, so
+    // they are issued together and only the multiply-adds form the serial chain.
+    constexpr int CARRY_BATCH = 16;
+    for (int s0 = 1; s0 < a.nseg; s0 += CARRY_BATCH) {
+        float loc[CARRY_BATCH], sdt[CARRY_BATCH];
+#pragma unroll
+        for (int j = 0; j < CARRY_BATCH; ++j) {
+            const int s = s0 + j;
+            loc[j] = s < a.nseg - 1 ? a.seg_h[(long)s * rows * NPAD + i] : 0.0f;   // the last segment has no aggregate
+            sdt[j] = s < a.nseg - 1 ? a.seg_sumdt[(long)s * rows + row] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < CARRY_BATCH; ++j) {
+            const int s = s0 + j;
+            if (s < a.nseg) {
+                a.seg_h[(long)s * rows * NPAD + i] = carry;  // incoming state of segment s
+                carry = fmaf(exp2_fast(A2 * sdt[j]), carry, loc[j]);
+            }
+        }
     }
 }
-
 
 // Single-token step: 4 lanes per row, 4 states each; the state is read and written once,
 // in place.  With N == 16 every per-state operand (state, A, B_t, C_t) is one aligned

@@ -89,7 +89,7 @@ def test_workspace_size_formula():
     assert B.ss_workspace_bytes(2, 64, 129, 16) > need          # a ragged tail adds a chunk
     assert B.ss_workspace_bytes(1, 1, 0, 1) % 256 == 0
     # few rows and a long sequence: scratch for splitting L across workgroups, also for a plain forward
-    assert B.ss_workspace_bytes(1, 256, 1 << 20, 16, for_backward=False) >= 128 * 256 * 17 * 4
+    assert B.ss_workspace_bytes(1, 256, 1 << 20, 16, for_backward=False) >= 100 * 256 * 17 * 4
     assert B.ss_workspace_bytes(8, 4096, 2048, 16, for_backward=False) == 0      # enough rows: never split
     assert B.ss_workspace_bytes(1, 256, 1024, 16, for_backward=False) == 0       # too short to split
 
