@@ -49,16 +49,20 @@ __device__ __forceinline__ float sum_over_lane_quarters(float x)
     return __uint_as_float(c[0]) + __uint_as_float(c[1]);
 }
 
-// Sum each of this lane's RED_VALUES values (index = step j * 4 + state k) over the 64
-// lanes (rows) of the wave and store the totals to acc[k][j] (pitch BT).  The values go
-// through a [value][row] LDS tile; lane l = (quarter p = l/16, value v = l%16) adds up 16
-// rows of value v and the four quarters are combined with lane swaps.
-__device__ __forceinline__ void reduce_over_rows(const float (&v)[RED_VALUES], float (*red)[RED_PITCH],
-                                                 float* acc, int lane)
+// Sum over the 64 lanes (rows) of a wave of each of a lane's RED_VALUES values (index =
+// step j * 4 + state k), in two halves so that the LDS round trip of one group of steps
+// overlaps the arithmetic of the next: reduce_put parks the values in a [value][row] LDS
+// tile; reduce_take, called one group later, has lane l = (quarter p = l/16, value v = l%16)
+// add up 16 rows of value v, combines the four quarters with lane swaps and stores the
+// totals to acc[k][j] (pitch BT).
+__device__ __forceinline__ void reduce_put(const float (&v)[RED_VALUES], float (*red)[RED_PITCH], int lane)
 {
 #pragma unroll
     for (int i = 0; i < RED_VALUES; ++i) red[i][lane] = v[i];
     wave_lds_fence();
+}
+__device__ __forceinline__ void reduce_take(float (*red)[RED_PITCH], float* acc, int lane)
+{
     const int p = lane >> 4, vi = lane & 15;
     const float4* src = reinterpret_cast<const float4*>(&red[vi][16 * p]);
     const float4 a0 = src[0], a1 = src[1], a2 = src[2], a3 = src[3];
@@ -242,8 +246,10 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                         dCv[j * STATES_PER_LANE + k] = dy * h[k];
                     }
                 }
-                reduce_over_rows(dCv, red, dbc + STATES_PER_LANE * BT + tl, lane);
+                if (g > 0) reduce_take(red, dbc + STATES_PER_LANE * BT + tl - GROUP_T, lane);  // previous group
+                reduce_put(dCv, red, lane);
             }
+            reduce_take(red, dbc + STATES_PER_LANE * BT + (NG - 1) * GROUP_T, lane);
         }
         // ---- B2: adjoint recurrence, last step of the block first --------------------------
 #pragma unroll
@@ -279,8 +285,10 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
             }
             *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
             *reinterpret_cast<float4*>(&sm.psb[w][lane][tl]) = make_float4(sb[0], sb[1], sb[2], sb[3]);
-            reduce_over_rows(dBv, red, dbc + tl, lane);
+            if (g < NG - 1) reduce_take(red, dbc + tl + GROUP_T, lane);  // previous (later) group
+            reduce_put(dBv, red, lane);
         }
+        reduce_take(red, dbc, lane);
         // ---- flush this wave's dB/dC of the block to global memory -------------------------
         wave_lds_fence();
 #pragma unroll
