@@ -9,7 +9,10 @@
  *     r_t      = delta[b,d,t] (+ delta_bias[d])
  *     dt_t     = softplus(r_t)            if SS_DELTA_SOFTPLUS, else r_t   (Section 3.2, tau_Delta)
  *     abar_t,n = exp(dt_t * A[d,n])                                        (Eq. 4)
- *     h_t,n    = abar_t,n * h_{t-1,n} + dt_t * Bmat[b,n,t] * u[b,d,t]      (Eq. 2a, first-order B-bar)
+ *     h_t,n    = abar_t,n * h_{t-1,n} + phi_t,n * Bmat[b,n,t] * u[b,d,t]   (Eq. 2a)
+ *                phi_t,n = dt_t                          (default: first-order B-bar)
+ *                phi_t,n = (abar_t,n - 1) / A[d,n]       (SS_EXACT_ZOH_B: the B-bar of Eq. 4;
+ *                                                         dt_t where A[d,n] == 0)
  *     y_t      = sum_n Cmat[b,n,t] * h_t,n (+ Dskip[d] * u[b,d,t])         (Eq. 2b)
  *     out_t    = y_t * z_t * sigmoid(z_t) if SS_HAS_Z, else y_t            (Section 3.4 gate)
  *
@@ -61,7 +64,8 @@ enum {
     SS_HAS_Z          = 8u,  /* z is given: multiplicative SiLU gate                       */
     SS_HAS_H0         = 16u, /* h0 is given (else the scan starts from the zero state)     */
     SS_WRITE_H_LAST   = 32u, /* h_last is written                                          */
-    SS_SAVE_FOR_BWD   = 64u  /* forward: leave state checkpoints in `workspace`            */
+    SS_SAVE_FOR_BWD   = 64u, /* forward: leave state checkpoints in `workspace`            */
+    SS_EXACT_ZOH_B    = 128u /* exact zero-order-hold B-bar of Eq. 4 instead of dt * B     */
 };
 
 enum {
@@ -130,7 +134,7 @@ typedef struct {
     int32_t batch, dim, dstate;       /* B, D, N                                           */
     int32_t io_dtype;                 /* of u_t, delta_t, z_t, B_t, C_t, out_t             */
     uint32_t flags;                   /* SS_DELTA_SOFTPLUS, SS_HAS_DELTA_BIAS, SS_HAS_D,
-                                         SS_HAS_Z                                          */
+                                         SS_HAS_Z, SS_EXACT_ZOH_B                          */
     float *h;                         /* (B,D,N) float32 state, updated IN PLACE           */
     const void *u_t, *delta_t, *z_t;  /* (B,D)                                             */
     const void *B_t, *C_t;            /* (B,N)                                             */

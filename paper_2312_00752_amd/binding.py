@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_PKG, "libss_scan.so")
 
 SS_F32, SS_BF16 = 0, 1
 SS_DELTA_SOFTPLUS, SS_HAS_DELTA_BIAS, SS_HAS_D, SS_HAS_Z = 1, 2, 4, 8
-SS_HAS_H0, SS_WRITE_H_LAST, SS_SAVE_FOR_BWD = 16, 32, 64
+SS_HAS_H0, SS_WRITE_H_LAST, SS_SAVE_FOR_BWD, SS_EXACT_ZOH_B = 16, 32, 64, 128
 SS_OK, SS_ERR_NULL, SS_ERR_SHAPE, SS_ERR_UNSUPPORTED = 0, -1, -2, -3
 SS_ERR_ALIGN, SS_ERR_WORKSPACE, SS_ERR_LAUNCH = -4, -5, -6
 SS_MAX_DSTATE = 16
@@ -118,7 +118,7 @@ def _stream(stream):
     return stream.cuda_stream
 
 
-def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus):
+def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh=False):
     import torch
     f32 = torch.float32
     nb, nd, nl = u.shape
@@ -147,6 +147,8 @@ def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplu
         flags |= SS_HAS_H0
     if delta_softplus:
         flags |= SS_DELTA_SOFTPLUS
+    if exact_zoh:
+        flags |= SS_EXACT_ZOH_B
     p.flags = flags
     return p
 
@@ -162,7 +164,7 @@ def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True, io_dtype=S
 
 def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0=None,
                 delta_softplus=False, out=None, h_last=None, return_last_state=False,
-                workspace=None, save_for_bwd=True, stream=None):
+                workspace=None, save_for_bwd=True, exact_zoh=False, stream=None):
     """Enqueue the forward scan.  Returns (out, h_last or None).
 
     ``workspace`` is a uint8 CUDA tensor of at least ``ss_workspace_bytes(...)`` bytes.  With
@@ -170,7 +172,7 @@ def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0
     ``ss_scan_bwd`` needs in it; without, the workspace only serves as scratch that lets
     a long sequence with few rows be split across workgroups."""
     import torch
-    p = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus)
+    p = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh)
     if out is None:
         out = torch.empty_like(u)
     p.out = _ptr(out, u.dtype, u.shape, "out")
@@ -191,7 +193,7 @@ def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0
 
 
 def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, delta_bias=None,
-                h0=None, delta_softplus=False, dh_last=None, want_dh0=False, stream=None):
+                h0=None, delta_softplus=False, dh_last=None, want_dh0=False, exact_zoh=False, stream=None):
     """Enqueue the backward scan after a forward call that filled ``workspace``.
 
     Returns a dict with du, ddelta, dz, dB, dC, dA, dD, ddelta_bias, dh0 (None where the
@@ -199,7 +201,7 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
     import torch
     f32 = torch.float32
     q = BwdParams()
-    q.fwd = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus)
+    q.fwd = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh)
     nb, nd, nl, nn = q.fwd.batch, q.fwd.dim, q.fwd.seqlen, q.fwd.dstate
     q.fwd.workspace = _ptr(workspace, torch.uint8, None, "workspace")
     q.fwd.workspace_bytes = workspace.numel()
@@ -223,7 +225,7 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
 
 
 def ss_step(h, u_t, delta_t, A, B_t, C_t, Dskip=None, z_t=None, delta_bias=None,
-            delta_softplus=False, out_t=None, stream=None):
+            delta_softplus=False, out_t=None, exact_zoh=False, stream=None):
     """Enqueue one recurrent step; ``h`` (B,D,N) float32 is updated in place.  Returns out_t."""
     import torch
     f32 = torch.float32
@@ -232,7 +234,7 @@ def ss_step(h, u_t, delta_t, A, B_t, C_t, Dskip=None, z_t=None, delta_bias=None,
     p = StepParams()
     p.batch, p.dim, p.dstate = nb, nd, nn
     p.io_dtype = _io_code(u_t)
-    flags = SS_DELTA_SOFTPLUS if delta_softplus else 0
+    flags = (SS_DELTA_SOFTPLUS if delta_softplus else 0) | (SS_EXACT_ZOH_B if exact_zoh else 0)
     p.h = _ptr(h, f32, (nb, nd, nn), "h")
     p.u_t = _ptr(u_t, io, (nb, nd), "u_t")
     p.delta_t = _ptr(delta_t, io, (nb, nd), "delta_t")

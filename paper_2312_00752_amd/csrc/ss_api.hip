@@ -7,8 +7,8 @@
 namespace {
 
 constexpr uint32_t kFwdFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z |
-                               SS_HAS_H0 | SS_WRITE_H_LAST | SS_SAVE_FOR_BWD;
-constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z;
+                               SS_HAS_H0 | SS_WRITE_H_LAST | SS_SAVE_FOR_BWD | SS_EXACT_ZOH_B;
+constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z | SS_EXACT_ZOH_B;
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -83,7 +83,11 @@ __device__ __forceinline__ void reduce_take(float (*red)[RED_PITCH], float* acc,
 //      abar*g into the next (earlier) block in registers; accumulate dA and dB, and write
 //      this wave's share of the two per-(b,d,t) sums over n that ddelta and du need;
 //   C. (pointwise view) add the four waves' shares, finish du and ddelta, and store them.
-template <typename T, bool VEC, bool FULLN>
+// ZOH selects the exact zero-order-hold B-bar of Eq. 4.  With phi = (abar - 1)/A and
+// q = g B u the formulas above become  ddt = sum_n abar (g h_prev A + q),
+// dA_n += g abar h_prev dt + q dphi/dA,  du = sum_n g phi B + Dskip dy,  dB = sum_d g phi u;
+// the LDS tile that otherwise carries dt*u then carries u.
+template <typename T, bool VEC, bool FULLN, bool ZOH>
 __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -125,7 +129,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     const bool s_ok = d0 + lane < f.D;
     const int sd = s_ok ? d0 + lane : f.D - 1;
     const long srow = (long)b * f.D + sd;
-    float A2[STATES_PER_LANE], ag[STATES_PER_LANE], dA[STATES_PER_LANE];
+    float A2[STATES_PER_LANE], An[STATES_PER_LANE], invA[STATES_PER_LANE], ag[STATES_PER_LANE], dA[STATES_PER_LANE];
     const T* __restrict__ gB[STATES_PER_LANE];
     const T* __restrict__ gC[STATES_PER_LANE];
     bool n_ok[STATES_PER_LANE];
@@ -134,7 +138,9 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         const int n = w * STATES_PER_LANE + k;
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
-        A2[k] = n_ok[k] ? f.A[(long)sd * N + nc] * LOG2E : 0.0f;
+        An[k] = n_ok[k] ? f.A[(long)sd * N + nc] : 0.0f;
+        A2[k] = An[k] * LOG2E;
+        invA[k] = An[k] != 0.0f ? 1.0f / An[k] : 0.0f;
         if (seg == f.nseg - 1) ag[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;  // abar_L g_L := dh_last
         else ag[k] = a.seg_g[(seg_rows + srow) * NPAD + w * STATES_PER_LANE + k];
         dA[k] = 0.0f;
@@ -197,7 +203,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                 sp = (j < nv) ? sp : 0.0f;
                 dt4[j] = sp;
                 sg4[j] = sg;
-                du4[j] = sp * u4[j];
+                du4[j] = ZOH ? u4[j] : sp * u4[j];
                 dy4[j] = o4[j];
             }
             if (has_z) {
@@ -240,7 +246,9 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 #pragma unroll
                     for (int k = 0; k < STATES_PER_LANE; ++k) {
                         const float abar = exp2_fast(dt * A2[k]);
-                        h[k] = fmaf(abar, h[k], du * Bg[k].get(j));
+                        float bu = du * Bg[k].get(j);
+                        if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
+                        h[k] = fmaf(abar, h[k], bu);
                         as[tl + j][k] = abar;
                         hs[tl + j][k] = h[k];
                         dCv[j * STATES_PER_LANE + k] = dy * h[k];
@@ -277,10 +285,19 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                     ag[k] = as[t][k] * gk;                             // flows on to h_{t-1}
                     const float hprev = (t > 0) ? hs[t > 0 ? t - 1 : 0][k] : hck[k];
                     const float gh = ag[k] * hprev;                    // g abar h_{t-1}
-                    dA[k] = fmaf(gh, dt, dA[k]);
-                    dd[j] = fmaf(gh, A2[k], dd[j]);
-                    sb[j] = fmaf(gk, Bg[k].get(j), sb[j]);
-                    dBv[j * STATES_PER_LANE + k] = gk * du;
+                    if (ZOH) {
+                        const zoh_terms z = zoh_phi(dt, An[k], invA[k], as[t][k], true);
+                        const float gB = gk * Bg[k].get(j), q = gB * du;   // du holds u here
+                        dA[k] = fmaf(gh, dt, fmaf(q, z.dphi_dA, dA[k]));
+                        dd[j] = fmaf(gh, An[k], fmaf(q, as[t][k], dd[j]));
+                        sb[j] = fmaf(gB, z.phi, sb[j]);
+                        dBv[j * STATES_PER_LANE + k] = gk * z.phi * du;
+                    } else {
+                        dA[k] = fmaf(gh, dt, dA[k]);
+                        dd[j] = fmaf(gh, A2[k], dd[j]);
+                        sb[j] = fmaf(gk, Bg[k].get(j), sb[j]);
+                        dBv[j * STATES_PER_LANE + k] = gk * du;
+                    }
                 }
             }
             *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
@@ -319,8 +336,8 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 #pragma unroll
             for (int j = 0; j < BSL; ++j) {
                 const float dt = f4_get(dt4, j), dy = f4_get(dy4, j);
-                const float ddt = fmaf(u4[j], sb4[j], LN2 * dd4[j]);
-                du4[j] = fmaf(dt, sb4[j], Dsk * dy);
+                const float ddt = ZOH ? dd4[j] : fmaf(u4[j], sb4[j], LN2 * dd4[j]);
+                du4[j] = ZOH ? fmaf(Dsk, dy, sb4[j]) : fmaf(dt, sb4[j], Dsk * dy);
                 dl4[j] = ddt * sg4[j];
                 dD_acc = fmaf(dy, u4[j], dD_acc);
                 db_acc += (j < nv) ? dl4[j] : 0.0f;
@@ -529,11 +546,11 @@ __global__ void copy_dh_kernel(const float* __restrict__ src, float* __restrict_
     if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
-template <typename T, bool VEC, bool FULLN>
+template <typename T, bool VEC, bool FULLN, bool ZOH>
 static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
     static bool configured = false;  // raising the dynamic LDS limit is needed once per kernel
-    auto kern = scan_bwd_kernel<T, VEC, FULLN>;
+    auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH>;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)sizeof(BwdSmem)) != hipSuccess)
@@ -567,14 +584,22 @@ int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream)
     const dim3 grid((unsigned)(f.B * groups));
     const bool fulln = f.N == NPAD;
     int rc;
-    if (io_dtype == 0) {
-        if (f.vec_ok && fulln) rc = launch_scan_bwd<float, true, true>(a, grid, stream);
-        else if (f.vec_ok) rc = launch_scan_bwd<float, true, false>(a, grid, stream);
-        else rc = launch_scan_bwd<float, false, false>(a, grid, stream);
+    if (f.flags & F_EXACT_ZOH_B) {  // the variant is built for the fastest and the most general shape only
+        if (io_dtype == 0) {
+            if (f.vec_ok && fulln) rc = launch_scan_bwd<float, true, true, true>(a, grid, stream);
+            else rc = launch_scan_bwd<float, false, false, true>(a, grid, stream);
+        } else {
+            if (f.vec_ok && fulln) rc = launch_scan_bwd<bf16_t, true, true, true>(a, grid, stream);
+            else rc = launch_scan_bwd<bf16_t, false, false, true>(a, grid, stream);
+        }
+    } else if (io_dtype == 0) {
+        if (f.vec_ok && fulln) rc = launch_scan_bwd<float, true, true, false>(a, grid, stream);
+        else if (f.vec_ok) rc = launch_scan_bwd<float, true, false, false>(a, grid, stream);
+        else rc = launch_scan_bwd<float, false, false, false>(a, grid, stream);
     } else {
-        if (f.vec_ok && fulln) rc = launch_scan_bwd<bf16_t, true, true>(a, grid, stream);
-        else if (f.vec_ok) rc = launch_scan_bwd<bf16_t, true, false>(a, grid, stream);
-        else rc = launch_scan_bwd<bf16_t, false, false>(a, grid, stream);
+        if (f.vec_ok && fulln) rc = launch_scan_bwd<bf16_t, true, true, false>(a, grid, stream);
+        else if (f.vec_ok) rc = launch_scan_bwd<bf16_t, true, false, false>(a, grid, stream);
+        else rc = launch_scan_bwd<bf16_t, false, false, false>(a, grid, stream);
     }
     if (rc != 0) return rc;
     finalize_kernel<<<dim3(fin_blocks), dim3(256), 0, stream>>>(a, 1);

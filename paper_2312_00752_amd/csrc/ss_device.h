@@ -65,6 +65,30 @@ __device__ __forceinline__ void softplus_sigmoid(float r, float& sp, float& sg)
     float inv = rcp_fast(one_e);          // 1/(1+e^r)
     sg = (r > 20.0f) ? 1.0f : e * inv;    // e^r/(1+e^r); avoids inf*0 for huge r
 }
+// Exact zero-order hold (Eq. 4): phi(dt, A) = (exp(dt A) - 1) / A multiplies B u in the
+// state update (dt itself where A == 0), and d phi / d A = (x e^x - (e^x - 1)) / A^2 with
+// x = dt A (dt^2 / 2 where A == 0).  Both differences cancel for small x, where the Taylor
+// series is used instead (|x| < 1/8: truncation error below 1e-8 relative).
+struct zoh_terms { float phi, dphi_dA; };
+__device__ __forceinline__ zoh_terms zoh_phi(float dt, float A, float invA, float abar, bool want_dA)
+{
+    const float x = dt * A;
+    const bool small = fabsf(x) < 0.125f;
+    const float em1_series = x * fmaf(x, fmaf(x, fmaf(x, fmaf(x, 1.0f / 120.0f, 1.0f / 24.0f), 1.0f / 6.0f), 0.5f), 1.0f);
+    const float em1 = small ? em1_series : abar - 1.0f;
+    zoh_terms r;
+    r.phi = (A == 0.0f) ? dt : em1 * invA;
+    r.dphi_dA = 0.0f;
+    if (want_dA) {
+        // x e^x - (e^x - 1) = sum_{k>=2} (k-1)/k! x^k
+        const float x2 = x * x;
+        const float num_series = x2 * fmaf(x, fmaf(x, fmaf(x, fmaf(x, 1.0f / 144.0f, 1.0f / 30.0f), 0.125f), 1.0f / 3.0f), 0.5f);
+        const float num = small ? num_series : fmaf(x, abar, -em1);
+        r.dphi_dA = (A == 0.0f) ? 0.5f * dt * dt : num * invA * invA;
+    }
+    return r;
+}
+
 __device__ __forceinline__ float sigmoid_fast(float z)
 {
     return rcp_fast(1.0f + exp2_fast(-z * LOG2E));

@@ -20,7 +20,9 @@ namespace ss {
 // AGG = true on every segment but the last, from the zero state (segment 0: from h0),
 // producing only the segment's end state and the sum of its step sizes; then, after
 // carry_fwd_kernel has turned those into each segment's incoming state, with AGG = false.
-template <typename T, bool VEC, bool FULLN, bool AGG>
+// ZOH selects the exact zero-order-hold B-bar of Eq. 4: the LDS tile that otherwise carries
+// dt*u then carries u, and each state multiplies it by phi(dt, A) = (abar - 1) / A.
+template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -56,7 +58,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     const bool s_ok = d0 + lane < a.D;
     const int sd = s_ok ? d0 + lane : a.D - 1;
     const long srow = (long)b * a.D + sd;
-    float A2[STATES_PER_LANE], h[STATES_PER_LANE];
+    float A2[STATES_PER_LANE], An[STATES_PER_LANE], invA[STATES_PER_LANE], h[STATES_PER_LANE];
     const T* __restrict__ gB[STATES_PER_LANE];
     const T* __restrict__ gC[STATES_PER_LANE];
     bool n_ok[STATES_PER_LANE];
@@ -65,7 +67,9 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         const int n = w * STATES_PER_LANE + k;
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
-        A2[k] = n_ok[k] ? a.A[(long)sd * N + nc] * LOG2E : 0.0f;
+        An[k] = n_ok[k] ? a.A[(long)sd * N + nc] : 0.0f;
+        A2[k] = An[k] * LOG2E;
+        invA[k] = An[k] != 0.0f ? 1.0f / An[k] : 0.0f;
         if (seg == 0) h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * N + nc] : 0.0f;
         else h[k] = AGG ? 0.0f : a.seg_h[((long)seg * a.B * a.D + srow) * NPAD + w * STATES_PER_LANE + k];
         gB[k] = static_cast<const T*>(a.Bm) + ((long)b * N + nc) * L;
@@ -103,7 +107,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 if (softplus) softplus_sigmoid(x, sp, sg); else sp = x;
                 sp = (j < nv) ? sp : 0.0f;
                 dt8[j] = sp;
-                du8[j] = sp * u8[j];
+                du8[j] = ZOH ? u8[j] : sp * u8[j];
                 if (AGG) sum_dt += sp;
             }
             float4* pd4 = reinterpret_cast<float4*>(&s_dt[pr][pq * SLICE]);
@@ -150,7 +154,9 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 #pragma unroll
                 for (int k = 0; k < STATES_PER_LANE; ++k) {
                     const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
-                    h[k] = fmaf(abar, h[k], du * Bg[cur][k].get(j));             // Eq. 2a
+                    float bu = du * Bg[cur][k].get(j);
+                    if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
+                    h[k] = fmaf(abar, h[k], bu);                                 // Eq. 2a
                     if (!AGG) y = fmaf(Cg[cur][k].get(j), h[k], y);              // Eq. 2b
                 }
                 yp[j] = y;
@@ -235,7 +241,7 @@ __global__ void carry_fwd_kernel(const FwdArgs a)
 // Single-token step: 4 lanes per row, 4 states each; the state is read and written once,
 // in place.  With N == 16 every per-state operand (state, A, B_t, C_t) is one aligned
 // 16- or 8-byte access per lane.
-template <typename T, bool FULLN>
+template <typename T, bool FULLN, bool ZOH>
 __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
 {
     const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -289,12 +295,15 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     float x = ld(dl_t, row) + ((a.flags & F_HAS_DELTA_BIAS) ? a.bias[d] : 0.0f);
     float dt = x, sg;
     if (a.flags & F_DELTA_SOFTPLUS) softplus_sigmoid(x, dt, sg);
-    const float du = dt * u, dt2 = dt * LOG2E;
+    const float du = ZOH ? u : dt * u, dt2 = dt * LOG2E;
 
     float y = 0.0f;
 #pragma unroll
     for (int k = 0; k < STATES_PER_LANE; ++k) {
-        hv[k] = fmaf(exp2_fast(dt2 * Av[k]), hv[k], du * Bv[k]);   // Eq. 4 and Eq. 2a
+        const float abar = exp2_fast(dt2 * Av[k]);                  // Eq. 4
+        float bu = du * Bv[k];
+        if (ZOH) bu *= zoh_phi(dt, Av[k], Av[k] != 0.0f ? 1.0f / Av[k] : 0.0f, abar, false).phi;
+        hv[k] = fmaf(abar, hv[k], bu);                              // Eq. 2a
         y = fmaf(Cv[k], hv[k], y);                                  // Eq. 2b
     }
     if (row_ok) {
@@ -327,17 +336,17 @@ __global__ void copy_state_kernel(const float* __restrict__ src, float* __restri
     if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
-template <typename T, bool VEC, bool FULLN>
+template <typename T, bool VEC, bool FULLN, bool ZOH>
 static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
 {
     const int groups = (a.D + ROWS - 1) / ROWS;
     const dim3 block(THREADS);
     if (a.nseg > 1) {
-        scan_fwd_kernel<T, VEC, FULLN, true><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
+        scan_fwd_kernel<T, VEC, FULLN, true, ZOH><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
         const long n = (long)a.B * a.D * NPAD;
         carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
     }
-    scan_fwd_kernel<T, VEC, FULLN, false><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+    scan_fwd_kernel<T, VEC, FULLN, false, ZOH><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
 }
 
 int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)
@@ -351,14 +360,22 @@ int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)
         return hipGetLastError() == hipSuccess ? 0 : -1;
     }
     const bool fulln = a.N == NPAD;
-    if (io_dtype == 0) {
-        if (a.vec_ok && fulln) launch_fwd_t<float, true, true>(a, stream);
-        else if (a.vec_ok) launch_fwd_t<float, true, false>(a, stream);
-        else launch_fwd_t<float, false, false>(a, stream);
+    if (a.flags & F_EXACT_ZOH_B) {  // the variant is built for the fastest and the most general shape only
+        if (io_dtype == 0) {
+            if (a.vec_ok && fulln) launch_fwd_t<float, true, true, true>(a, stream);
+            else launch_fwd_t<float, false, false, true>(a, stream);
+        } else {
+            if (a.vec_ok && fulln) launch_fwd_t<bf16_t, true, true, true>(a, stream);
+            else launch_fwd_t<bf16_t, false, false, true>(a, stream);
+        }
+    } else if (io_dtype == 0) {
+        if (a.vec_ok && fulln) launch_fwd_t<float, true, true, false>(a, stream);
+        else if (a.vec_ok) launch_fwd_t<float, true, false, false>(a, stream);
+        else launch_fwd_t<float, false, false, false>(a, stream);
     } else {
-        if (a.vec_ok && fulln) launch_fwd_t<bf16_t, true, true>(a, stream);
-        else if (a.vec_ok) launch_fwd_t<bf16_t, true, false>(a, stream);
-        else launch_fwd_t<bf16_t, false, false>(a, stream);
+        if (a.vec_ok && fulln) launch_fwd_t<bf16_t, true, true, false>(a, stream);
+        else if (a.vec_ok) launch_fwd_t<bf16_t, true, false, false>(a, stream);
+        else launch_fwd_t<bf16_t, false, false, false>(a, stream);
     }
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -373,13 +390,16 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
     const size_t va = io_dtype == 0 ? 16 : 8;
     const bool vec = a.N == NPAD && reinterpret_cast<uintptr_t>(a.B_t) % va == 0 &&
                      reinterpret_cast<uintptr_t>(a.C_t) % va == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
+    const bool zoh = a.flags & F_EXACT_ZOH_B;
+#define SS_LAUNCH_STEP(T, V, Z) step_kernel<T, V, Z><<<grid, block, 0, stream>>>(a)
     if (io_dtype == 0) {
-        if (vec) step_kernel<float, true><<<grid, block, 0, stream>>>(a);
-        else step_kernel<float, false><<<grid, block, 0, stream>>>(a);
+        if (vec) { if (zoh) SS_LAUNCH_STEP(float, true, true); else SS_LAUNCH_STEP(float, true, false); }
+        else { if (zoh) SS_LAUNCH_STEP(float, false, true); else SS_LAUNCH_STEP(float, false, false); }
     } else {
-        if (vec) step_kernel<bf16_t, true><<<grid, block, 0, stream>>>(a);
-        else step_kernel<bf16_t, false><<<grid, block, 0, stream>>>(a);
+        if (vec) { if (zoh) SS_LAUNCH_STEP(bf16_t, true, true); else SS_LAUNCH_STEP(bf16_t, true, false); }
+        else { if (zoh) SS_LAUNCH_STEP(bf16_t, false, true); else SS_LAUNCH_STEP(bf16_t, false, false); }
     }
+#undef SS_LAUNCH_STEP
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

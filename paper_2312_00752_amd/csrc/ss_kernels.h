@@ -13,6 +13,7 @@ enum : uint32_t {
     F_HAS_D = SS_HAS_D,
     F_HAS_Z = SS_HAS_Z,
     F_HAS_H0 = SS_HAS_H0,
+    F_EXACT_ZOH_B = SS_EXACT_ZOH_B,
 };
 
 struct FwdArgs {
