@@ -17,8 +17,13 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-FP32_VALU_PEAK_TFLOPS = 157.3  # MI355X vector fp32, published (packed); context only
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+# Un-packed fp32 vector issue peak: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz lane-ops/s (an FMA
+# counts once; the published 157.3 TFLOP/s counts it twice and assumes packed FP32).
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# VALU instructions (an exponential counted as two issue slots) per token*channel*state,
+# counted in the ISA of the bf16 kernels: forward 7.3 + 1, backward 18.7 + 1.
+VALU_SLOTS_FWD, VALU_SLOTS_BWD = 8.3, 19.7
 
 
 def algorithmic_bytes(batch, seqlen, dim, dstate, esz, has_z=True):
@@ -115,6 +120,54 @@ def decode_bench(dev, tokens=512):
             "frac_of_hbm_peak_graph": state_bytes / (us_graph * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
 
+def paper_sweep(dev):
+    """The shape of the paper's own scan benchmark (Section 4.5 / Appendix E.5: batch 1,
+    D 1024, N 16, bf16 inputs, L = 2^9 .. 2^19), forward only and forward+backward."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    nb, nd, nn = 1, 1024, 16
+    bf = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(6)
+    rows = []
+    for e in range(9, 20):
+        nl = 1 << e
+        mk = lambda *shape: torch.randn(*shape, device=dev, generator=gen).to(bf)
+        u, dl, z, do = mk(nb, nd, nl), mk(nb, nd, nl), mk(nb, nd, nl), mk(nb, nd, nl)
+        Bm, Cm = mk(nb, nn, nl), mk(nb, nn, nl)
+        A = -torch.arange(1, nn + 1, device=dev, dtype=torch.float32).repeat(nd, 1).contiguous()
+        Dk = torch.randn(nd, device=dev, generator=gen)
+        bias = torch.full((nd,), -4.0, device=dev)
+        out = torch.empty_like(u)
+        ws = torch.empty(max(256, B.ss_workspace_bytes(nb, nd, nl, nn, io_dtype=B.SS_BF16)), dtype=torch.uint8, device=dev)
+        ws0 = torch.empty(max(256, B.ss_workspace_bytes(nb, nd, nl, nn, for_backward=False, io_dtype=B.SS_BF16)),
+                          dtype=torch.uint8, device=dev)
+        kw = dict(Dskip=Dk, z=z, delta_bias=bias, delta_softplus=True)
+        fi = lambda: B.ss_scan_fwd(u, dl, A, Bm, Cm, out=out, workspace=ws0, save_for_bwd=False, **kw)
+        fs = lambda: B.ss_scan_fwd(u, dl, A, Bm, Cm, out=out, workspace=ws, **kw)
+        bw = lambda: B.ss_scan_bwd(do, u, dl, A, Bm, Cm, ws, **kw)
+        for _ in range(2):
+            fi(); fs(); bw()
+        torch.cuda.synchronize()
+        it = 10
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        ev[0].record()
+        for _ in range(it):
+            fi()
+        ev[1].record()
+        for _ in range(it):
+            fs()
+        ev[2].record()
+        for _ in range(it):
+            bw()
+        ev[3].record()
+        torch.cuda.synchronize()
+        rows.append({"L": nl, "fwd_us": ev[0].elapsed_time(ev[1]) * 1e3 / it,
+                     "fwd_save_us": ev[1].elapsed_time(ev[2]) * 1e3 / it,
+                     "bwd_us": ev[2].elapsed_time(ev[3]) * 1e3 / it})
+    return {"workload": "batch 1, D 1024, N 16, bf16 I/O", "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +176,8 @@ def main():
     ap.add_argument("--workload", default="mamba1p4b_layer_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the single-token step timing")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="also time the shape of the paper's own scan benchmark over L = 2^9..2^19")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB streaming kernel (torch.neg; reference dispatch for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -213,9 +268,18 @@ def main():
                    "fwd_bwd_algorithmic_GBs": (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9,
                    "fwd_bwd_frac_of_hbm_peak": (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                    "fwd_traffic": traffic.get("scan_fwd_kernel_hbm_bytes")},
+        # The scan kernels are bound by vector-ALU issue, not by HBM: lane-ops issued per
+        # second against the chip's un-packed fp32 issue peak.
+        "alu": {"bound": "alu", "kernel": "scan_bwd_kernel",
+                "achieved": tc * nn * VALU_SLOTS_BWD / (bwd_ms * 1e-3) / 1e12,
+                "peak": VALU_PEAK_LANE_OPS / 1e12, "unit": "T lane-ops/s",
+                "frac": tc * nn * VALU_SLOTS_BWD / (bwd_ms * 1e-3) / VALU_PEAK_LANE_OPS,
+                "fwd_frac": tc * nn * VALU_SLOTS_FWD / (fwd_ms * 1e-3) / VALU_PEAK_LANE_OPS},
     }
     if not args.no_decode:
         res["decode"] = decode_bench(dev)
+    if args.paper_sweep:
+        res["paper_sweep"] = paper_sweep(dev)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, sample_dim=nd)
     print(json.dumps(res))
