@@ -300,3 +300,23 @@ def test_threads_do_not_change_result():
     a = _full(p, nthreads=1)
     b = _full(p, nthreads=4)
     np.testing.assert_array_equal(a["out"], b["out"])
+
+
+def test_oracle_matches_its_stored_fixture():
+    """Regression guard: the oracle still produces the numbers stored by
+    tests/golden/make_oracle_fixture.py (its own earlier output, not an independent pin)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("make_oracle_fixture", os.path.join(GOLDEN, "make_oracle_fixture.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    w = mod.case()
+    now = {False: mod.compute(w, False), True: mod.compute(w, True)}
+    seen = 0
+    for line in open(os.path.join(GOLDEN, "oracle_tiny_case.txt")):
+        if line.startswith("#"):
+            continue
+        name, mode, *vals = line.split()
+        got = np.asarray(now[mode == "zoh"][name]).reshape(-1)
+        np.testing.assert_allclose(got, np.array(vals, dtype=np.float64), rtol=1e-13, atol=1e-15, err_msg=name + " " + mode)
+        seen += 1
+    assert seen == 20
