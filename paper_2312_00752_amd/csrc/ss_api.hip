@@ -26,7 +26,7 @@ SegPlan plan_segments(int B, int D, int L)
     const long wgs = (long)B * ((D + 63) / 64);
     SegPlan s{1, (L + 31) / 32 * 32};
     if (s.seg_len == 0) s.seg_len = 32;
-    if (wgs >= 256 || L < 2048) return s;
+    if (wgs > 256 || L < 2048) return s;               // more than one workgroup per compute unit already
     long want = (512 + wgs - 1) / wgs;                 // about two workgroups per compute unit
     want = want < L / 512 ? want : L / 512;            // segments of at least 512 steps
     if (want < 2) return s;

@@ -91,6 +91,7 @@ def test_workspace_size_formula():
     # few rows and a long sequence: scratch for splitting L across workgroups, also for a plain forward
     assert B.ss_workspace_bytes(1, 256, 1 << 20, 16, for_backward=False) >= 100 * 256 * 17 * 4
     assert B.ss_workspace_bytes(8, 4096, 2048, 16, for_backward=False) == 0      # enough rows: never split
+    assert B.ss_workspace_bytes(8, 2048, 2048, 16, for_backward=False) > 0       # one row tile per compute unit: split in two
     assert B.ss_workspace_bytes(1, 256, 1024, 16, for_backward=False) == 0       # too short to split
 
 
