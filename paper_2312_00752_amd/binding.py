@@ -1,4 +1,4 @@
-"""Thin ctypes binding of the C-ABI library declared in ``include/ss_scan.h``.
+"""Thin ctypes binding of the C-ABI library declared in ``include/ss_scan.h`` and ``include/ss_conv.h``.
 
 Argument marshalling only: every step of the path runs in the library's HIP kernels.
 PyTorch appears here solely as the owner of device memory and streams.  The library must
@@ -43,6 +43,25 @@ class StepParams(ctypes.Structure):
                 ("A", _vp), ("Dskip", _vp), ("delta_bias", _vp), ("out_t", _vp)]
 
 
+class ConvParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("seqlen", ctypes.c_int32),
+                ("width", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("x", _vp), ("w", _vp), ("bias", _vp), ("state_in", _vp), ("out", _vp), ("state_out", _vp)]
+
+
+class ConvBwdParams(ctypes.Structure):
+    _fields_ = [("fwd", ConvParams), ("dout", _vp), ("dx", _vp), ("dw", _vp), ("dbias", _vp)]
+
+
+class ConvStepParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("width", ctypes.c_int32),
+                ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("state", _vp), ("x_t", _vp), ("w", _vp), ("bias", _vp), ("out_t", _vp)]
+
+
+SS_CONV_SILU, SS_CONV_HAS_BIAS, SS_CONV_HAS_STATE, SS_CONV_WRITE_STATE = 1, 2, 4, 8
+SS_CONV_MAX_WIDTH = 4
+
 _lib = None
 
 
@@ -62,6 +81,12 @@ def lib():
         l.ss_scan_bwd.argtypes = [ctypes.POINTER(BwdParams), _vp]
         l.ss_step.restype = ctypes.c_int
         l.ss_step.argtypes = [ctypes.POINTER(StepParams), _vp]
+        l.ss_conv_fwd.restype = ctypes.c_int
+        l.ss_conv_fwd.argtypes = [ctypes.POINTER(ConvParams), _vp]
+        l.ss_conv_bwd.restype = ctypes.c_int
+        l.ss_conv_bwd.argtypes = [ctypes.POINTER(ConvBwdParams), _vp]
+        l.ss_conv_step.restype = ctypes.c_int
+        l.ss_conv_step.argtypes = [ctypes.POINTER(ConvStepParams), _vp]
         l.ss_strerror.restype = ctypes.c_char_p
         l.ss_strerror.argtypes = [ctypes.c_int]
         l.ss_version.restype = ctypes.c_int
@@ -255,6 +280,85 @@ def ss_step(h, u_t, delta_t, A, B_t, C_t, Dskip=None, z_t=None, delta_bias=None,
         out_t = torch.empty_like(u_t)
     p.out_t = _ptr(out_t, io, (nb, nd), "out_t")
     rc = lib().ss_step(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return out_t
+
+
+# ---------------------------------------------------------------- short causal convolution
+def _conv_params(x, w, bias, state_in, silu):
+    import torch
+    f32 = torch.float32
+    nb, nd, nl = x.shape
+    width = w.shape[1]
+    p = ConvParams()
+    p.batch, p.dim, p.seqlen, p.width = nb, nd, nl, width
+    p.io_dtype = _io_code(x)
+    flags = SS_CONV_SILU if silu else 0
+    p.x = _ptr(x, None, (nb, nd, nl), "x")
+    p.w = _ptr(w, f32, (nd, width), "w")
+    if bias is not None:
+        p.bias = _ptr(bias, f32, (nd,), "bias")
+        flags |= SS_CONV_HAS_BIAS
+    if state_in is not None:
+        p.state_in = _ptr(state_in, x.dtype, (nb, nd, width - 1), "state_in")
+        flags |= SS_CONV_HAS_STATE
+    p.flags = flags
+    return p
+
+
+def ss_conv_fwd(x, w, bias=None, state_in=None, silu=True, out=None, return_state=False, stream=None):
+    """Enqueue the causal convolution (+ SiLU).  Returns (out, state_out or None)."""
+    import torch
+    p = _conv_params(x, w, bias, state_in, silu)
+    if out is None:
+        out = torch.empty_like(x)
+    p.out = _ptr(out, x.dtype, x.shape, "out")
+    state_out = None
+    if return_state:
+        state_out = torch.empty((p.batch, p.dim, p.width - 1), dtype=x.dtype, device=x.device)
+        p.state_out = _ptr(state_out, None, None, "state_out")
+        p.flags |= SS_CONV_WRITE_STATE
+    rc = lib().ss_conv_fwd(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return out, state_out
+
+
+def ss_conv_bwd(dout, x, w, bias=None, state_in=None, silu=True, stream=None):
+    """Enqueue the backward convolution.  Returns dict(dx, dw, dbias)."""
+    import torch
+    q = ConvBwdParams()
+    q.fwd = _conv_params(x, w, bias, state_in, silu)
+    g = {"dx": torch.empty_like(x), "dw": torch.empty_like(w),
+         "dbias": torch.empty_like(bias) if bias is not None else None}
+    q.dout = _ptr(dout, x.dtype, x.shape, "dout")
+    q.dx = _ptr(g["dx"], None, None, "dx")
+    q.dw = _ptr(g["dw"], None, None, "dw")
+    q.dbias = _ptr(g["dbias"], None, None, "dbias")
+    rc = lib().ss_conv_bwd(ctypes.byref(q), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return g
+
+
+def ss_conv_step(state, x_t, w, bias=None, silu=True, out_t=None, stream=None):
+    """Enqueue one token of the convolution; ``state`` (B,D,W-1) is updated in place."""
+    import torch
+    nb, nd = x_t.shape
+    width = w.shape[1]
+    p = ConvStepParams()
+    p.batch, p.dim, p.width = nb, nd, width
+    p.io_dtype = _io_code(x_t)
+    p.flags = (SS_CONV_SILU if silu else 0) | (SS_CONV_HAS_BIAS if bias is not None else 0)
+    p.state = _ptr(state, x_t.dtype, (nb, nd, width - 1), "state")
+    p.x_t = _ptr(x_t, None, (nb, nd), "x_t")
+    p.w = _ptr(w, torch.float32, (nd, width), "w")
+    p.bias = _ptr(bias, torch.float32, (nd,), "bias")
+    if out_t is None:
+        out_t = torch.empty_like(x_t)
+    p.out_t = _ptr(out_t, x_t.dtype, (nb, nd), "out_t")
+    rc = lib().ss_conv_step(ctypes.byref(p), _stream(stream))
     if rc != SS_OK:
         raise SsError(rc)
     return out_t

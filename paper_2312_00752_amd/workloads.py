@@ -14,6 +14,14 @@ Recipe (numpy ``default_rng(seed)``; draw order u, z, delta_raw, bias, B, C, Dsk
            plus N(0, 0.02^2) noise
 Tensors of a bf16 workload are rounded to bf16 once (round-to-nearest-even) and handed
 out as float32 arrays holding exactly those values.
+
+Layer recipe (``make_layer_inputs``; the block of Section 3.4 around the scan; draw order x, z,
+conv_w, conv_b, W_x, W_dt, dt_bias, Dskip, dout):
+  x, z, Dskip, dout ~ N(0,1)          (x, z stand for the two halves of the input projection)
+  conv_w, conv_b ~ U[-W^-1/2, W^-1/2]  (width W = 4)
+  W_x  (R+2N, D) ~ U[-D^-1/2, D^-1/2]  rows: Delta rank-R part, B, C   (Section 3.2, 3.6)
+  W_dt (D, R)    ~ U[-R^-1/2, R^-1/2]  with R = ceil(D / 32)  (D/2 is the model width, R = width/16)
+  dt_bias, A as above.
 """
 import numpy as np
 
@@ -122,3 +130,47 @@ def make_step_inputs(batch, dim, dstate, tokens, io="bf16", seed=5):
     return {"u": u, "delta": delta, "z": z, "A": A, "B": Bm, "C": Cm, "Dskip": Dskip,
             "delta_bias": bias, "io": io, "shape": (batch, dim, dstate, tokens),
             "delta_softplus": True}
+
+
+def make_conv_inputs(batch, dim, seqlen, width=4, io="bf16", seed=0):
+    """Inputs of the short convolution: x, dout (B,D,L), state_in (B,D,W-1), w (D,W), bias (D)."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((batch, dim, seqlen), dtype=np.float32)
+    dout = rng.standard_normal((batch, dim, seqlen), dtype=np.float32)
+    state_in = rng.standard_normal((batch, dim, width - 1), dtype=np.float32)
+    k = 1.0 / np.sqrt(width)
+    w = rng.uniform(-k, k, size=(dim, width)).astype(np.float32)
+    bias = rng.uniform(-k, k, size=dim).astype(np.float32)
+    if io == "bf16":
+        x, dout, state_in = round_to_bf16(x), round_to_bf16(dout), round_to_bf16(state_in)
+    return {"x": x, "dout": dout, "state_in": state_in, "w": w, "bias": bias, "io": io,
+            "shape": (batch, dim, seqlen, width)}
+
+
+def layer_rank(dim):
+    """Rank R of the Delta projection for an inner width ``dim`` (model width / 16, Section 3.6)."""
+    return (dim + 31) // 32
+
+
+def make_layer_inputs(batch, seqlen, dim, dstate=16, io="bf16", seed=0, width=4, rank=None):
+    """Inputs of the selective SSM layer (see the module docstring for the recipe)."""
+    rng = np.random.default_rng(seed)
+    R = rank or layer_rank(dim)
+    x = rng.standard_normal((batch, dim, seqlen), dtype=np.float32)
+    z = rng.standard_normal((batch, dim, seqlen), dtype=np.float32)
+    k = 1.0 / np.sqrt(width)
+    conv_w = rng.uniform(-k, k, size=(dim, width)).astype(np.float32)
+    conv_b = rng.uniform(-k, k, size=dim).astype(np.float32)
+    k = 1.0 / np.sqrt(dim)
+    W_x = rng.uniform(-k, k, size=(R + 2 * dstate, dim)).astype(np.float32)
+    k = 1.0 / np.sqrt(R)
+    W_dt = rng.uniform(-k, k, size=(dim, R)).astype(np.float32)
+    dt_bias = _inv_softplus(rng.uniform(1e-3, 1e-1, size=dim)).astype(np.float32)
+    Dskip = rng.standard_normal(dim, dtype=np.float32)
+    dout = rng.standard_normal((batch, dim, seqlen), dtype=np.float32)
+    A = -np.broadcast_to(np.arange(1, dstate + 1, dtype=np.float32), (dim, dstate)).copy()
+    if io == "bf16":
+        x, z, dout, W_x, W_dt = (round_to_bf16(a) for a in (x, z, dout, W_x, W_dt))
+    return {"x": x, "z": z, "conv_w": conv_w, "conv_b": conv_b, "W_x": W_x, "W_dt": W_dt,
+            "dt_bias": dt_bias, "A": A, "Dskip": Dskip, "dout": dout, "io": io,
+            "shape": (batch, seqlen, dim, dstate, R, width)}

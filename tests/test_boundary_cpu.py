@@ -13,10 +13,13 @@ FAKE = 0x7F0000001000  # a non-null, 4096-byte aligned address that is never der
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "ss_scan.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(ss_[a-z_]+)\s*\(", hdr))
-    assert {"ss_scan_fwd", "ss_scan_bwd", "ss_step", "ss_workspace_bytes", "ss_strerror", "ss_version"} <= names
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        hdr = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, fn)).read(), flags=re.S)
+        names |= set(re.findall(r"\b(ss_[a-z_]+)\s*\(", hdr))
+    assert {"ss_scan_fwd", "ss_scan_bwd", "ss_step", "ss_workspace_bytes", "ss_strerror", "ss_version",
+            "ss_conv_fwd", "ss_conv_bwd", "ss_conv_step"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -153,3 +156,52 @@ def test_python_wrappers_refuse_cpu_tensors():
     Bm = torch.zeros(1, 2, 8)
     with pytest.raises(ValueError):
         B.ss_scan_fwd(u, u, A, Bm, Bm)
+
+
+# ---------------------------------------------------------------- short convolution
+def _good_conv():
+    p = B.ConvParams()
+    p.batch, p.dim, p.seqlen, p.width = 2, 64, 128, 4
+    p.io_dtype = B.SS_BF16
+    p.flags = B.SS_CONV_SILU | B.SS_CONV_HAS_BIAS
+    for f in ("x", "w", "bias", "out"):
+        setattr(p, f, FAKE)
+    return p
+
+
+def test_conv_struct_layout_and_rejections():
+    assert ctypes.sizeof(B.ConvParams) == 6 * 4 + 6 * 8
+    assert ctypes.sizeof(B.ConvBwdParams) == ctypes.sizeof(B.ConvParams) + 4 * 8
+    assert ctypes.sizeof(B.ConvStepParams) == 5 * 4 + 4 + 5 * 8
+    fwd = lambda p: B.lib().ss_conv_fwd(ctypes.byref(p), None)
+    assert B.lib().ss_conv_fwd(None, None) == B.SS_ERR_NULL
+    for f in ("x", "w", "bias", "out"):
+        p = _good_conv(); setattr(p, f, None)
+        assert fwd(p) == B.SS_ERR_NULL, f
+    for f, v in (("batch", 0), ("dim", 0), ("seqlen", -1), ("width", 0)):
+        p = _good_conv(); setattr(p, f, v)
+        assert fwd(p) == B.SS_ERR_SHAPE, f
+    p = _good_conv(); p.width = 5
+    assert fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_conv(); p.flags = 16
+    assert fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_conv(); p.io_dtype = 7
+    assert fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_conv(); p.x = FAKE + 8
+    assert fwd(p) == B.SS_ERR_ALIGN
+    p = _good_conv(); p.flags |= B.SS_CONV_HAS_STATE
+    assert fwd(p) == B.SS_ERR_NULL
+    p = _good_conv(); p.flags |= B.SS_CONV_WRITE_STATE
+    assert fwd(p) == B.SS_ERR_NULL
+    q = B.ConvBwdParams(); q.fwd = _good_conv()
+    bwd = lambda q: B.lib().ss_conv_bwd(ctypes.byref(q), None)
+    assert bwd(q) == B.SS_ERR_NULL           # dw missing
+    q.dw = FAKE
+    assert bwd(q) == B.SS_ERR_NULL           # dbias missing although a bias is given
+    q.dbias = FAKE
+    assert bwd(q) == B.SS_ERR_NULL           # dout / dx missing
+    s = B.ConvStepParams()
+    s.batch, s.dim, s.width, s.io_dtype = 2, 8, 4, B.SS_F32
+    assert B.lib().ss_conv_step(ctypes.byref(s), None) == B.SS_ERR_NULL
+    s.width = 9
+    assert B.lib().ss_conv_step(ctypes.byref(s), None) == B.SS_ERR_UNSUPPORTED
