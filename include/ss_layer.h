@@ -1,0 +1,83 @@
+/*
+ * ss_layer.h -- C ABI of the selective SSM layer: the steps either side of the scan.
+ *
+ * Algorithm 2 of arXiv 2312.00752 with the selection functions of Section 3.2 (s_B, s_C
+ * linear in the input, Delta through softplus), the low-rank Delta projection of Section 3.6
+ * and the convolution / activation / gate of the block in Section 3.4 (Figure 3).  For every
+ * batch entry, with the sequence axis last:
+ *
+ *     u          = SiLU(conv(x))                       (D, L)      ss_conv.h
+ *     [r; B; C]  = W_x  @ u                            (R+N+N, L)
+ *     delta_raw  = W_dt @ r                            (D, L)
+ *     out        = scan(u, softplus(delta_raw + dt_bias), A, B, C, Dskip) * SiLU(z)   ss_scan.h
+ *
+ * u, [r;B;C] and delta_raw are stored in io_dtype between the steps.  The backward call
+ * follows Appendix D ("Memory"): of the forward pass only [r;B;C] (R+2N rows against the 2D
+ * rows of x and z) and the scan's checkpoints are kept in `saved`; u and delta_raw are
+ * recomputed from x and [r;B;C].
+ *
+ * Rules as in ss_scan.h (device pointers owned by the caller, dense row-major layouts, io
+ * tensors 16-byte aligned, float32 ones 4-byte aligned, outputs overwritten, host-side
+ * validation, SS_OK or a negative code), with one difference: the two projections are plain
+ * GEMMs and are handed to rocBLAS, which is looked up at run time (librocblas.so.5); the
+ * first layer call on a device creates a rocBLAS handle, which allocates.  If rocBLAS cannot
+ * be loaded or refuses a call the result is SS_ERR_BACKEND.  `saved` and `scratch` must be
+ * 256-byte aligned; seqlen must be >= 1 and dstate <= SS_MAX_DSTATE.
+ *      x, z, out, dout, dx, dz : (B, D, L)     io_dtype
+ *      W_x                     : (R+2N, D)     io_dtype   rows: r (R), B (N), C (N)
+ *      W_dt                    : (D, R)        io_dtype
+ *      conv_w                  : (D, W)        float32;   conv_b, dt_bias, Dskip : (D) float32
+ *      A                       : (D, N)        float32
+ *      dW_x, dW_dt, dconv_w, dconv_b, ddt_bias, dA, dD : float32, shaped like their parameter
+ */
+#ifndef SS_LAYER_H
+#define SS_LAYER_H
+
+#include "ss_conv.h"
+#include "ss_scan.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SS_ERR_BACKEND (-7) /* rocBLAS could not be loaded or refused a call */
+
+typedef struct {
+    int32_t batch, dim, seqlen, dstate, dt_rank, conv_width; /* B, D, L, N, R, W             */
+    int32_t io_dtype;                                        /* ss_dtype                     */
+    uint32_t flags;                                          /* must be 0                    */
+    const void *x, *z;
+    const float *conv_w, *conv_b;
+    const void *W_x, *W_dt;
+    const float *dt_bias, *A, *Dskip;
+    void *out;
+    void *saved;        /* ss_layer_saved_bytes(): written by the forward call, read by the
+                           backward call; NULL in a forward call that no backward follows    */
+    size_t saved_bytes;
+    void *scratch;      /* ss_layer_scratch_bytes(): free for other use after the call       */
+    size_t scratch_bytes;
+} ss_layer_params;
+
+/* Sizes of the two buffers; only the shape fields and io_dtype are read.  for_backward
+ * selects the scratch size of ss_layer_bwd (larger) or of ss_layer_fwd. */
+size_t ss_layer_saved_bytes(const ss_layer_params *p);
+size_t ss_layer_scratch_bytes(const ss_layer_params *p, int for_backward);
+
+/* Forward: conv, projections, scan, gate. */
+int ss_layer_fwd(const ss_layer_params *p, void *stream);
+
+typedef struct {
+    ss_layer_params fwd; /* the forward call's inputs and its `saved`; out is not read;
+                            scratch sized for the backward call                              */
+    const void *dout;    /* (B,D,L) io_dtype                                                 */
+    void *dx, *dz;       /* (B,D,L) io_dtype                                                 */
+    float *dconv_w, *dconv_b, *dW_x, *dW_dt, *ddt_bias, *dA, *dD;
+} ss_layer_bwd_params;
+
+/* Backward: gradient of <out, dout> w.r.t. x, z and every parameter. */
+int ss_layer_bwd(const ss_layer_bwd_params *p, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SS_LAYER_H */

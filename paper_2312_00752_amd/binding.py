@@ -1,4 +1,4 @@
-"""Thin ctypes binding of the C-ABI library declared in ``include/ss_scan.h`` and ``include/ss_conv.h``.
+"""Thin ctypes binding of the C-ABI library declared in ``include/ss_scan.h``, ``include/ss_conv.h`` and ``include/ss_layer.h``.
 
 Argument marshalling only: every step of the path runs in the library's HIP kernels.
 PyTorch appears here solely as the owner of device memory and streams.  The library must
@@ -59,6 +59,23 @@ class ConvStepParams(ctypes.Structure):
                 ("state", _vp), ("x_t", _vp), ("w", _vp), ("bias", _vp), ("out_t", _vp)]
 
 
+class LayerParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("seqlen", ctypes.c_int32),
+                ("dstate", ctypes.c_int32), ("dt_rank", ctypes.c_int32), ("conv_width", ctypes.c_int32),
+                ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("x", _vp), ("z", _vp), ("conv_w", _vp), ("conv_b", _vp), ("W_x", _vp), ("W_dt", _vp),
+                ("dt_bias", _vp), ("A", _vp), ("Dskip", _vp), ("out", _vp),
+                ("saved", _vp), ("saved_bytes", ctypes.c_size_t),
+                ("scratch", _vp), ("scratch_bytes", ctypes.c_size_t)]
+
+
+class LayerBwdParams(ctypes.Structure):
+    _fields_ = [("fwd", LayerParams), ("dout", _vp), ("dx", _vp), ("dz", _vp),
+                ("dconv_w", _vp), ("dconv_b", _vp), ("dW_x", _vp), ("dW_dt", _vp),
+                ("ddt_bias", _vp), ("dA", _vp), ("dD", _vp)]
+
+
+SS_ERR_BACKEND = -7
 SS_CONV_SILU, SS_CONV_HAS_BIAS, SS_CONV_HAS_STATE, SS_CONV_WRITE_STATE = 1, 2, 4, 8
 SS_CONV_MAX_WIDTH = 4
 
@@ -87,6 +104,14 @@ def lib():
         l.ss_conv_bwd.argtypes = [ctypes.POINTER(ConvBwdParams), _vp]
         l.ss_conv_step.restype = ctypes.c_int
         l.ss_conv_step.argtypes = [ctypes.POINTER(ConvStepParams), _vp]
+        l.ss_layer_saved_bytes.restype = ctypes.c_size_t
+        l.ss_layer_saved_bytes.argtypes = [ctypes.POINTER(LayerParams)]
+        l.ss_layer_scratch_bytes.restype = ctypes.c_size_t
+        l.ss_layer_scratch_bytes.argtypes = [ctypes.POINTER(LayerParams), ctypes.c_int]
+        l.ss_layer_fwd.restype = ctypes.c_int
+        l.ss_layer_fwd.argtypes = [ctypes.POINTER(LayerParams), _vp]
+        l.ss_layer_bwd.restype = ctypes.c_int
+        l.ss_layer_bwd.argtypes = [ctypes.POINTER(LayerBwdParams), _vp]
         l.ss_strerror.restype = ctypes.c_char_p
         l.ss_strerror.argtypes = [ctypes.c_int]
         l.ss_version.restype = ctypes.c_int
@@ -362,3 +387,80 @@ def ss_conv_step(state, x_t, w, bias=None, silu=True, out_t=None, stream=None):
     if rc != SS_OK:
         raise SsError(rc)
     return out_t
+
+
+# ---------------------------------------------------------------- the selective SSM layer
+def _layer_shape(batch, dim, seqlen, dstate, dt_rank, conv_width, io_dtype):
+    p = LayerParams()
+    p.batch, p.dim, p.seqlen, p.dstate, p.dt_rank, p.conv_width = batch, dim, seqlen, dstate, dt_rank, conv_width
+    p.io_dtype = io_dtype
+    return p
+
+
+def ss_layer_saved_bytes(batch, dim, seqlen, dstate, dt_rank, conv_width=4, io_dtype=SS_BF16):
+    return int(lib().ss_layer_saved_bytes(ctypes.byref(
+        _layer_shape(batch, dim, seqlen, dstate, dt_rank, conv_width, io_dtype))))
+
+
+def ss_layer_scratch_bytes(batch, dim, seqlen, dstate, dt_rank, conv_width=4, io_dtype=SS_BF16, for_backward=True):
+    return int(lib().ss_layer_scratch_bytes(ctypes.byref(
+        _layer_shape(batch, dim, seqlen, dstate, dt_rank, conv_width, io_dtype)), int(bool(for_backward))))
+
+
+def _layer_params(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, saved, scratch):
+    import torch
+    f32 = torch.float32
+    nb, nd, nl = x.shape
+    nn = A.shape[1]
+    rank = W_dt.shape[1]
+    width = conv_w.shape[1]
+    io = x.dtype
+    p = _layer_shape(nb, nd, nl, nn, rank, width, _io_code(x))
+    p.x = _ptr(x, io, (nb, nd, nl), "x")
+    p.z = _ptr(z, io, (nb, nd, nl), "z")
+    p.conv_w = _ptr(conv_w, f32, (nd, width), "conv_w")
+    p.conv_b = _ptr(conv_b, f32, (nd,), "conv_b")
+    p.W_x = _ptr(W_x, io, (rank + 2 * nn, nd), "W_x")
+    p.W_dt = _ptr(W_dt, io, (nd, rank), "W_dt")
+    p.dt_bias = _ptr(dt_bias, f32, (nd,), "dt_bias")
+    p.A = _ptr(A, f32, (nd, nn), "A")
+    p.Dskip = _ptr(Dskip, f32, (nd,), "Dskip")
+    if saved is not None:
+        p.saved = _ptr(saved, torch.uint8, None, "saved")
+        p.saved_bytes = saved.numel()
+    p.scratch = _ptr(scratch, torch.uint8, None, "scratch")
+    p.scratch_bytes = scratch.numel()
+    return p
+
+
+def ss_layer_fwd(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scratch, saved=None, out=None, stream=None):
+    """Enqueue the layer's forward pass; ``saved`` (if given) is filled for ``ss_layer_bwd``."""
+    import torch
+    p = _layer_params(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, saved, scratch)
+    if out is None:
+        out = torch.empty_like(x)
+    p.out = _ptr(out, x.dtype, x.shape, "out")
+    rc = lib().ss_layer_fwd(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return out
+
+
+def ss_layer_bwd(dout, x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scratch, saved, stream=None):
+    """Enqueue the layer's backward pass.  Returns a dict of gradients (weights in float32)."""
+    import torch
+    f32 = torch.float32
+    q = LayerBwdParams()
+    q.fwd = _layer_params(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, saved, scratch)
+    dev = x.device
+    g = {"dx": torch.empty_like(x), "dz": torch.empty_like(x),
+         "dconv_w": torch.empty_like(conv_w), "dconv_b": torch.empty_like(conv_b),
+         "dW_x": torch.empty(W_x.shape, dtype=f32, device=dev), "dW_dt": torch.empty(W_dt.shape, dtype=f32, device=dev),
+         "ddt_bias": torch.empty_like(dt_bias), "dA": torch.empty_like(A), "dD": torch.empty_like(Dskip)}
+    q.dout = _ptr(dout, x.dtype, x.shape, "dout")
+    for name, t in g.items():
+        setattr(q, name, _ptr(t, None, None, name))
+    rc = lib().ss_layer_bwd(ctypes.byref(q), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return g

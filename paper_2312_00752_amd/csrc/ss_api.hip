@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include "ss_kernels.h"
+#include "ss_layer.h"
 #include "ss_scan.h"
 
 namespace {
@@ -69,7 +70,7 @@ WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
     return w;
 }
 
-int check_fwd(const ss_fwd_params* p, bool for_bwd)
+int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
 {
     if (!p) return SS_ERR_NULL;
     if (p->batch < 1 || p->dim < 1 || p->dstate < 1 || p->seqlen < 0) return SS_ERR_SHAPE;
@@ -85,9 +86,13 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd)
     if ((p->flags & SS_HAS_DELTA_BIAS) && !p->delta_bias) return SS_ERR_NULL;
     if ((p->flags & SS_HAS_H0) && !p->h0) return SS_ERR_NULL;
     if (!for_bwd && (p->flags & SS_WRITE_H_LAST) && !p->h_last) return SS_ERR_NULL;
-    const void* io[] = {p->u, p->delta, p->z, p->Bmat, p->Cmat, for_bwd ? nullptr : p->out};
+    const void* io[] = {p->u, p->delta, p->z, for_bwd ? nullptr : p->out};
     for (const void* q : io)
         if (q && !aligned(q, 16)) return SS_ERR_ALIGN;
+    // B and C are read 16 bytes at a time only when every row is a whole number of such pieces;
+    // the layer passes rows of a larger matrix here, which then are merely element-aligned
+    const size_t bc_align = (p->seqlen % 8 == 0 || bc_dense) ? 16 : (p->io_dtype == SS_BF16 ? 2 : 4);
+    if ((p->Bmat && !aligned(p->Bmat, bc_align)) || (p->Cmat && !aligned(p->Cmat, bc_align))) return SS_ERR_ALIGN;
     const void* f32[] = {p->A, p->Dskip, p->delta_bias, p->h0, for_bwd ? nullptr : p->h_last};
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
@@ -99,7 +104,7 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd)
     return SS_OK;
 }
 
-ss::FwdArgs make_fwd_args(const ss_fwd_params* p)
+ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
 {
     ss::FwdArgs a{};
     a.B = p->batch; a.D = p->dim; a.L = p->seqlen; a.N = p->dstate;
@@ -107,6 +112,7 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p)
     a.vec_ok = p->seqlen % 8 == 0;
     a.u = p->u; a.delta = p->delta; a.z = (p->flags & SS_HAS_Z) ? p->z : nullptr;
     a.Bm = p->Bmat; a.Cm = p->Cmat; a.A = p->A;
+    a.bc_bstride = bc_bstride;
     a.Dskip = p->Dskip; a.bias = p->delta_bias; a.h0 = p->h0;
     a.out = p->out;
     a.h_last = (p->flags & SS_WRITE_H_LAST) ? p->h_last : nullptr;
@@ -121,19 +127,13 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p)
 
 }  // namespace
 
-extern "C" {
+namespace ss {
 
-size_t ss_workspace_bytes(const ss_fwd_params* p, int for_backward)
+int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
 {
-    if (!p || p->batch < 1 || p->dim < 1 || p->seqlen < 0) return 0;
-    return ws_layout(p, for_backward != 0).total;
-}
-
-int ss_scan_fwd(const ss_fwd_params* p, void* stream)
-{
-    const int rc = check_fwd(p, false);
+    const int rc = check_fwd(p, false, p && bc_bstride == (long)p->dstate * p->seqlen);
     if (rc != SS_OK) return rc;
-    ss::FwdArgs a = make_fwd_args(p);
+    ss::FwdArgs a = make_fwd_args(p, bc_bstride);
     char* ws = static_cast<char*>(p->workspace);
     if (p->flags & SS_SAVE_FOR_BWD) {
         const WsLayout w = ws_layout(p, true);
@@ -156,10 +156,11 @@ int ss_scan_fwd(const ss_fwd_params* p, void* stream)
     return ss::launch_fwd(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
 }
 
-int ss_scan_bwd(const ss_bwd_params* p, void* stream)
+
+int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
 {
     if (!p) return SS_ERR_NULL;
-    const int rc = check_fwd(&p->fwd, true);
+    const int rc = check_fwd(&p->fwd, true, bc_bstride == (long)p->fwd.dstate * p->fwd.seqlen);
     if (rc != SS_OK) return rc;
     const ss_fwd_params* f = &p->fwd;
     const bool empty = f->seqlen == 0;
@@ -178,7 +179,7 @@ int ss_scan_bwd(const ss_bwd_params* p, void* stream)
     const WsLayout w = ws_layout(f, true);
     char* ws = static_cast<char*>(f->workspace);
     ss::BwdArgs a{};
-    a.f = make_fwd_args(f);
+    a.f = make_fwd_args(f, bc_bstride);
     a.f.out = nullptr;
     a.f.h_last = nullptr;
     a.f.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
@@ -200,6 +201,29 @@ int ss_scan_bwd(const ss_bwd_params* p, void* stream)
     a.dD = (f->flags & SS_HAS_D) ? p->dD : nullptr;
     a.dbias = (f->flags & SS_HAS_DELTA_BIAS) ? p->ddelta_bias : nullptr;
     return ss::launch_bwd(a, f->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+}
+
+
+}  // namespace ss
+
+extern "C" {
+
+size_t ss_workspace_bytes(const ss_fwd_params* p, int for_backward)
+{
+    if (!p || p->batch < 1 || p->dim < 1 || p->seqlen < 0) return 0;
+    return ws_layout(p, for_backward != 0).total;
+}
+
+int ss_scan_fwd(const ss_fwd_params* p, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    return ss::scan_fwd_strided(p, (long)p->dstate * p->seqlen, stream);
+}
+
+int ss_scan_bwd(const ss_bwd_params* p, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    return ss::scan_bwd_strided(p, (long)p->fwd.dstate * p->fwd.seqlen, stream);
 }
 
 int ss_step(const ss_step_params* p, void* stream)
@@ -239,6 +263,7 @@ const char* ss_strerror(int code)
     case SS_ERR_ALIGN: return "a pointer is not aligned as required";
     case SS_ERR_WORKSPACE: return "workspace missing or too small";
     case SS_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    case SS_ERR_BACKEND: return "rocBLAS could not be loaded or refused a call";
     default: return "unknown error code";
     }
 }

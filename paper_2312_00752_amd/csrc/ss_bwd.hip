@@ -144,8 +144,8 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         if (seg == f.nseg - 1) ag[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;  // abar_L g_L := dh_last
         else ag[k] = a.seg_g[(seg_rows + srow) * NPAD + w * STATES_PER_LANE + k];
         dA[k] = 0.0f;
-        gB[k] = static_cast<const T*>(f.Bm) + ((long)b * N + nc) * L;
-        gC[k] = static_cast<const T*>(f.Cm) + ((long)b * N + nc) * L;
+        gB[k] = static_cast<const T*>(f.Bm) + (long)b * f.bc_bstride + (long)nc * L;
+        gC[k] = static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride + (long)nc * L;
     }
     float* const dbc = &sm.dbc[w][0][0][0];
     float (*const red)[RED_PITCH] = sm.red[w];
@@ -172,12 +172,12 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         }
     };
     issue_group((nblocks - 1) / LG);
-    float touched = touch_bc<T>(f.Bm, f.Cm, b, N, L, w, lane, (nblocks - 1) * BT);
+    float touched = touch_bc<T>(f.Bm, f.Cm, b, f.bc_bstride, N, L, w, lane, (nblocks - 1) * BT);
 
     for (int blk = nblocks - 1; blk >= blk_begin; --blk) {
         const int tc = blk * BT;
         consume_touch(touched);
-        touched = touch_bc<T>(f.Bm, f.Cm, b, N, L, w, lane, (blk - 1) * BT);
+        touched = touch_bc<T>(f.Bm, f.Cm, b, f.bc_bstride, N, L, w, lane, (blk - 1) * BT);
         const int t0 = tc + pq * BSL;
         const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;
         // the state entering this block, left by the forward pass
@@ -414,7 +414,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
         const int nc = n_ok[k] ? n : 0;
         A2[k] = n_ok[k] ? f.A[(long)sd * N + nc] * LOG2E : 0.0f;
         ag[k] = (seg == f.nseg - 1 && n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;
-        gC[k] = static_cast<const T*>(f.Cm) + ((long)b * N + nc) * L;
+        gC[k] = static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride + (long)nc * L;
     }
     typename io8<T>::raw rd, rz, ro;
     auto issue_loads = [&](int c) {
@@ -425,11 +425,11 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
         if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
     };
     issue_loads(c_end - 1);
-    float touched = touch_bc<T>(f.Cm, f.Cm, b, N, L, w, lane, (c_end - 1) * CHUNK_T);
+    float touched = touch_bc<T>(f.Cm, f.Cm, b, f.bc_bstride, N, L, w, lane, (c_end - 1) * CHUNK_T);
     for (int c = c_end - 1; c >= c_begin; --c) {
         const int tc = c * CHUNK_T;
         consume_touch(touched);
-        touched = touch_bc<T>(f.Cm, f.Cm, b, N, L, w, lane, (c - 1) * CHUNK_T);
+        touched = touch_bc<T>(f.Cm, f.Cm, b, f.bc_bstride, N, L, w, lane, (c - 1) * CHUNK_T);
         const int nv = p_ok ? min(max(L - (tc + pq * SLICE), 0), SLICE) : 0;
         {
             float v8[SLICE], o8[SLICE], z8[SLICE], dt8[SLICE];

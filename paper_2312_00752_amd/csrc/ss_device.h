@@ -340,13 +340,13 @@ __device__ __forceinline__ bc_group<T> load_bc(const T* __restrict__ p, int t, i
 // ordinary vector loads: lanes 0..3 one element of each of its B rows, lanes 4..7 of its C
 // rows, at step t.  The value is only handed to `consume_touch` an iteration later.
 template <typename T>
-__device__ __forceinline__ float touch_bc(const void* Bm, const void* Cm, int b, int N, int L, int w,
+__device__ __forceinline__ float touch_bc(const void* Bm, const void* Cm, int b, long bstride, int N, int L, int w,
                                            int lane, int t)
 {
     float v = 0.0f;
     if (lane < 2 * STATES_PER_LANE && t >= 0 && t < L) {
         const int n = min(w * STATES_PER_LANE + (lane & 3), N - 1);
-        const T* p = static_cast<const T*>(lane < STATES_PER_LANE ? Bm : Cm) + ((long)b * N + n) * L + t;
+        const T* p = static_cast<const T*>(lane < STATES_PER_LANE ? Bm : Cm) + (long)b * bstride + (long)n * L + t;
         if constexpr (sizeof(T) == 2) v = bf16_to_f32(*p); else v = *p;
     }
     return v;

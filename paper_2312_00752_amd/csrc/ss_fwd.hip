@@ -72,8 +72,8 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         invA[k] = An[k] != 0.0f ? 1.0f / An[k] : 0.0f;
         if (seg == 0) h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * N + nc] : 0.0f;
         else h[k] = AGG ? 0.0f : a.seg_h[((long)seg * a.B * a.D + srow) * NPAD + w * STATES_PER_LANE + k];
-        gB[k] = static_cast<const T*>(a.Bm) + ((long)b * N + nc) * L;
-        gC[k] = static_cast<const T*>(a.Cm) + ((long)b * N + nc) * L;
+        gB[k] = static_cast<const T*>(a.Bm) + (long)b * a.bc_bstride + (long)nc * L;
+        gC[k] = static_cast<const T*>(a.Cm) + (long)b * a.bc_bstride + (long)nc * L;
     }
     float sum_dt = 0.0f;  // AGG: this thread's share of the segment's sum of step sizes
 
@@ -86,12 +86,12 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
     };
     issue_loads(c_begin);
-    float touched = touch_bc<T>(a.Bm, a.Cm, b, N, L, w, lane, c_begin * CHUNK_T);
+    float touched = touch_bc<T>(a.Bm, a.Cm, b, a.bc_bstride, N, L, w, lane, c_begin * CHUNK_T);
 
     for (int c = c_begin; c < c_end; ++c) {
         float u8[SLICE], z8[SLICE], v8[SLICE];
         consume_touch(touched);
-        touched = touch_bc<T>(a.Bm, a.Cm, b, N, L, w, lane, (c + 1) * CHUNK_T);
+        touched = touch_bc<T>(a.Bm, a.Cm, b, a.bc_bstride, N, L, w, lane, (c + 1) * CHUNK_T);
         const int tc = c * CHUNK_T;
         const int t0 = tc + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);

@@ -21,6 +21,7 @@ struct FwdArgs {
     uint32_t flags;
     int vec_ok;  // L % 8 == 0: every row starts 16-byte aligned and 8-step slices are whole or empty
     const void *u, *delta, *z, *Bm, *Cm;
+    long bc_bstride;  // elements between consecutive batch entries of Bm and Cm (N * L when dense)
     const float *A, *Dskip, *bias, *h0;
     void* out;
     float* h_last;  // may be null
@@ -59,5 +60,11 @@ struct StepArgs {
 int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream);
 int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream);
 int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream);
+
+// The public scan entry points with one extra degree of freedom: B and C of batch entry b
+// start b * bc_bstride elements after Bmat / Cmat (the public calls pass dstate * seqlen).
+// Validation and return codes are those of ss_scan_fwd / ss_scan_bwd.
+int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream);
+int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream);
 
 }  // namespace ss

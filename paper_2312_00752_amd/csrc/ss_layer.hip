@@ -1,0 +1,370 @@
+// Selective SSM layer: conv -> SiLU -> projections -> scan -> gate, forward and backward
+// with recomputation (see include/ss_layer.h).
+//
+// The scan and the convolution are this library's own kernels.  The two projections are
+// plain GEMMs on dense operands and go to rocBLAS, resolved with dlopen so that the library
+// itself carries no link-time dependency on it.  Everything is laid out so that the GEMMs
+// need no transposed copies: with the sequence axis last, a batch entry of u is a (D, L)
+// row-major matrix, [r;B;C] = W_x @ u lands directly in the (B, N, L) layout the scan reads
+// (B and C are rows R.. of the result: the scan is told the batch stride), and
+// delta_raw = W_dt @ r lands in the (B, D, L) layout of the scan's step-size input.
+#include <dlfcn.h>
+#include <hip/hip_runtime.h>
+#include <mutex>
+#include <rocblas/rocblas.h>  // types and signatures only; the functions are looked up at run time
+
+#include "ss_device.h"
+#include "ss_kernels.h"
+#include "ss_layer.h"
+
+namespace {
+
+inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- rocBLAS, looked up once ------------------------------------------------------------------
+struct Blas {
+    decltype(&rocblas_create_handle) create = nullptr;
+    decltype(&rocblas_set_stream) set_stream = nullptr;
+    decltype(&rocblas_gemm_strided_batched_ex) gemm = nullptr;
+    bool ok = false;
+    static constexpr int kMaxDevices = 64;
+    rocblas_handle handle[kMaxDevices] = {};
+    std::mutex mu;
+};
+Blas g_blas;
+std::once_flag g_blas_once;
+
+void load_blas()
+{
+    void* so = dlopen("librocblas.so.5", RTLD_NOW | RTLD_LOCAL);
+    if (!so) so = dlopen("librocblas.so", RTLD_NOW | RTLD_LOCAL);
+    if (!so) so = dlopen("/opt/rocm/lib/librocblas.so.5", RTLD_NOW | RTLD_LOCAL);
+    if (!so) return;
+    g_blas.create = reinterpret_cast<decltype(g_blas.create)>(dlsym(so, "rocblas_create_handle"));
+    g_blas.set_stream = reinterpret_cast<decltype(g_blas.set_stream)>(dlsym(so, "rocblas_set_stream"));
+    g_blas.gemm = reinterpret_cast<decltype(g_blas.gemm)>(dlsym(so, "rocblas_gemm_strided_batched_ex"));
+    g_blas.ok = g_blas.create && g_blas.set_stream && g_blas.gemm;
+}
+
+// Handle of the current device, bound to `stream`; nullptr if rocBLAS is unavailable.
+rocblas_handle blas_handle(hipStream_t stream)
+{
+    std::call_once(g_blas_once, load_blas);
+    if (!g_blas.ok) return nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= Blas::kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_blas.mu);
+    if (!g_blas.handle[dev] && g_blas.create(&g_blas.handle[dev]) != rocblas_status_success) {
+        g_blas.handle[dev] = nullptr;
+        return nullptr;
+    }
+    if (g_blas.set_stream(g_blas.handle[dev], stream) != rocblas_status_success) return nullptr;
+    return g_blas.handle[dev];
+}
+
+// C[i] (M x N) = op(A[i]) (M x K) @ op(B[i]) (K x N) + beta * C[i], all ROW-major with row
+// pitches lda/ldb/ldc of the stored matrices and element strides sA/sB/sC between batch
+// entries.  A row-major matrix is the column-major matrix of its transpose, so the product
+// is handed to rocBLAS as C^T = op(B)^T op(A)^T with the operands swapped.
+bool gemm_rm(rocblas_handle h, bool tA, bool tB, int M, int N, int K, const void* A, int lda, long sA,
+             const void* B, int ldb, long sB, float beta, void* C, int ldc, long sC, int batch, bool bf16)
+{
+    const float alpha = 1.0f;
+    const rocblas_datatype t = bf16 ? rocblas_datatype_bf16_r : rocblas_datatype_f32_r;
+    const rocblas_status st = g_blas.gemm(
+        h, tB ? rocblas_operation_transpose : rocblas_operation_none,
+        tA ? rocblas_operation_transpose : rocblas_operation_none, N, M, K, &alpha, B, t, ldb, sB, A, t, lda, sA,
+        &beta, C, t, ldc, sC, C, t, ldc, sC, batch, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
+    return st == rocblas_status_success;
+}
+
+// ---- small kernels around the GEMMs -----------------------------------------------------------
+// dB, dC (B,N,L) float32 -> rows R.. of d[r;B;C] (B, R+2N, L) in the io dtype.
+template <typename T>
+__global__ void pack_dbc_kernel(const float* __restrict__ dB, const float* __restrict__ dC, T* __restrict__ dP,
+                                int N, int R, long L, long total)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;   // over B * 2N * L
+    if (i >= total) return;
+    const long l = i % L;
+    const long row = i / L;               // b * 2N + j
+    const long b = row / (2 * N);
+    const int j = int(row - b * 2 * N);   // 0..N-1: B, N..2N-1: C
+    const float v = j < N ? dB[(b * N + j) * L + l] : dC[(b * N + (j - N)) * L + l];
+    T* dst = dP + (b * (R + 2 * N) + R + j) * L + l;
+    if constexpr (sizeof(T) == 2) *dst = T(ss::f32_to_bf16_bits(v));
+    else *dst = v;
+}
+
+// out[i] = sum_b part[b][i], float32 accumulation in batch order.
+template <typename T>
+__global__ void sum_partials_kernel(const T* __restrict__ part, int nb, long n, float* __restrict__ out)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float acc = 0.0f;
+    for (int b = 0; b < nb; ++b) {
+        if constexpr (sizeof(T) == 2) acc += ss::bf16_to_f32(part[b * n + i]);
+        else acc += part[b * n + i];
+    }
+    out[i] = acc;
+}
+
+// ---- buffers -------------------------------------------------------------------------------------
+struct Shape {
+    size_t B, D, L, N, R, Mx, esz;
+};
+Shape shape_of(const ss_layer_params* p)
+{
+    Shape s;
+    s.B = p->batch; s.D = p->dim; s.L = p->seqlen; s.N = p->dstate; s.R = p->dt_rank;
+    s.Mx = s.R + 2 * s.N;
+    s.esz = p->io_dtype == SS_BF16 ? 2 : 4;
+    return s;
+}
+
+ss_fwd_params scan_params(const ss_layer_params* p)
+{
+    ss_fwd_params f{};
+    f.batch = p->batch; f.dim = p->dim; f.seqlen = p->seqlen; f.dstate = p->dstate;
+    f.io_dtype = p->io_dtype;
+    f.flags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z;
+    return f;
+}
+
+// saved:   [P = [r;B;C] (B, Mx, L) io][workspace of the scan]
+struct SavedLayout { size_t P_off, scan_off, scan_bytes, total; };
+SavedLayout saved_layout(const ss_layer_params* p)
+{
+    const Shape s = shape_of(p);
+    const ss_fwd_params f = scan_params(p);
+    SavedLayout w{};
+    w.P_off = 0;
+    w.scan_off = round_up(s.B * s.Mx * s.L * s.esz, 256);
+    w.scan_bytes = ss_workspace_bytes(&f, 1);
+    w.total = w.scan_off + round_up(w.scan_bytes, 256);
+    return w;
+}
+
+// scratch: forward  [u][delta][P and the scan's split scratch, used if nothing is saved]
+//          backward [u][delta][du][ddelta][dP (B,Mx,L) io][dB, dC (B,N,L) f32]
+//                   [partials of dW_dt (B,D,R) io][partials of dW_x (B,Mx,D) io]
+struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, du, ddelta, dP, dB, dC, part_dt, part_x, total; };
+ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
+{
+    const Shape s = shape_of(p);
+    ScratchLayout w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += round_up(bytes, 256); return at; };
+    const size_t T = s.B * s.D * s.L * s.esz;
+    w.u = take(T);
+    w.delta = take(T);
+    if (!bwd) {
+        w.P = take(s.B * s.Mx * s.L * s.esz);
+        const ss_fwd_params f = scan_params(p);
+        w.scan_ws_bytes = ss_workspace_bytes(&f, 0);
+        w.scan_ws = take(w.scan_ws_bytes);
+    } else {
+        w.du = take(T);
+        w.ddelta = take(T);
+        w.dP = take(s.B * s.Mx * s.L * s.esz);
+        w.dB = take(s.B * s.N * s.L * sizeof(float));
+        w.dC = take(s.B * s.N * s.L * sizeof(float));
+        w.part_dt = take(s.B * s.D * s.R * s.esz);
+        w.part_x = take(s.B * s.Mx * s.D * s.esz);
+    }
+    w.total = off;
+    return w;
+}
+
+bool shape_ok(const ss_layer_params* p)
+{
+    return p->batch >= 1 && p->dim >= 1 && p->seqlen >= 1 && p->dstate >= 1 && p->dt_rank >= 1 && p->conv_width >= 1;
+}
+
+int check_layer(const ss_layer_params* p, bool bwd)
+{
+    if (!p) return SS_ERR_NULL;
+    if (!shape_ok(p)) return SS_ERR_SHAPE;
+    if (p->dstate > SS_MAX_DSTATE || p->conv_width > SS_CONV_MAX_WIDTH) return SS_ERR_UNSUPPORTED;
+    if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+    if (p->flags != 0) return SS_ERR_UNSUPPORTED;
+    // rocBLAS takes 32-bit sizes
+    if ((long)p->dim * p->dt_rank >= 0x7fffffffL || (long)p->dim * (p->dt_rank + 2 * p->dstate) >= 0x7fffffffL)
+        return SS_ERR_UNSUPPORTED;
+    if (!p->x || !p->z || !p->conv_w || !p->conv_b || !p->W_x || !p->W_dt || !p->dt_bias || !p->A || !p->Dskip)
+        return SS_ERR_NULL;
+    if (!bwd && !p->out) return SS_ERR_NULL;
+    const void* io[] = {p->x, p->z, p->W_x, p->W_dt, bwd ? nullptr : p->out};
+    for (const void* q : io)
+        if (q && !aligned_to(q, 16)) return SS_ERR_ALIGN;
+    const void* f32[] = {p->conv_w, p->conv_b, p->dt_bias, p->A, p->Dskip};
+    for (const void* q : f32)
+        if (!aligned_to(q, 4)) return SS_ERR_ALIGN;
+    if (bwd || p->saved) {
+        if (!p->saved || p->saved_bytes < saved_layout(p).total) return SS_ERR_WORKSPACE;
+        if (!aligned_to(p->saved, 256)) return SS_ERR_ALIGN;
+    }
+    if (!p->scratch || p->scratch_bytes < scratch_layout(p, bwd).total) return SS_ERR_WORKSPACE;
+    if (!aligned_to(p->scratch, 256)) return SS_ERR_ALIGN;
+    return SS_OK;
+}
+
+ss_conv_params conv_params(const ss_layer_params* p, void* u)
+{
+    ss_conv_params c{};
+    c.batch = p->batch; c.dim = p->dim; c.seqlen = p->seqlen; c.width = p->conv_width;
+    c.io_dtype = p->io_dtype;
+    c.flags = SS_CONV_SILU | SS_CONV_HAS_BIAS;
+    c.x = p->x; c.w = p->conv_w; c.bias = p->conv_b;
+    c.out = u;
+    return c;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ss_layer_saved_bytes(const ss_layer_params* p)
+{
+    if (!p || !shape_ok(p)) return 0;
+    return saved_layout(p).total;
+}
+
+size_t ss_layer_scratch_bytes(const ss_layer_params* p, int for_backward)
+{
+    if (!p || !shape_ok(p)) return 0;
+    return scratch_layout(p, for_backward != 0).total;
+}
+
+int ss_layer_fwd(const ss_layer_params* p, void* stream)
+{
+    int rc = check_layer(p, false);
+    if (rc != SS_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rocblas_handle h = blas_handle(st);
+    if (!h) return SS_ERR_BACKEND;
+    const Shape s = shape_of(p);
+    const bool bf16 = p->io_dtype == SS_BF16;
+    const ScratchLayout sc = scratch_layout(p, false);
+    const SavedLayout sv = saved_layout(p);
+    char* scratch = static_cast<char*>(p->scratch);
+    char* saved = static_cast<char*>(p->saved);
+    char* u = scratch + sc.u;
+    char* delta = scratch + sc.delta;
+    char* P = saved ? saved + sv.P_off : scratch + sc.P;
+    const int B = p->batch, D = p->dim, L = p->seqlen, N = p->dstate, R = p->dt_rank, Mx = R + 2 * N;
+
+    const ss_conv_params c = conv_params(p, u);
+    if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
+    // [r;B;C] = W_x @ u
+    if (!gemm_rm(h, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16))
+        return SS_ERR_BACKEND;
+    // delta_raw = W_dt @ r
+    if (!gemm_rm(h, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
+        return SS_ERR_BACKEND;
+    ss_fwd_params f = scan_params(p);
+    f.u = u; f.delta = delta; f.z = p->z;
+    f.Bmat = P + (size_t)R * L * s.esz;
+    f.Cmat = P + (size_t)(R + N) * L * s.esz;
+    f.A = p->A; f.Dskip = p->Dskip; f.delta_bias = p->dt_bias;
+    f.out = p->out;
+    if (saved) {
+        f.flags |= SS_SAVE_FOR_BWD;
+        f.workspace = saved + sv.scan_off;
+        f.workspace_bytes = sv.scan_bytes;
+    } else if (sc.scan_ws_bytes) {
+        f.workspace = scratch + sc.scan_ws;   // lets a long sequence with few rows be split
+        f.workspace_bytes = sc.scan_ws_bytes;
+    }
+    return ss::scan_fwd_strided(&f, (long)Mx * L, stream);
+}
+
+int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
+{
+    if (!q) return SS_ERR_NULL;
+    const ss_layer_params* p = &q->fwd;
+    int rc = check_layer(p, true);
+    if (rc != SS_OK) return rc;
+    if (!q->dout || !q->dx || !q->dz || !q->dconv_w || !q->dconv_b || !q->dW_x || !q->dW_dt || !q->ddt_bias ||
+        !q->dA || !q->dD)
+        return SS_ERR_NULL;
+    if (!aligned_to(q->dout, 16) || !aligned_to(q->dx, 16) || !aligned_to(q->dz, 16)) return SS_ERR_ALIGN;
+    const void* f32[] = {q->dconv_w, q->dconv_b, q->dW_x, q->dW_dt, q->ddt_bias, q->dA, q->dD};
+    for (const void* g : f32)
+        if (!aligned_to(g, 4)) return SS_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rocblas_handle h = blas_handle(st);
+    if (!h) return SS_ERR_BACKEND;
+    const Shape s = shape_of(p);
+    const bool bf16 = p->io_dtype == SS_BF16;
+    const ScratchLayout sc = scratch_layout(p, true);
+    const SavedLayout sv = saved_layout(p);
+    char* scratch = static_cast<char*>(p->scratch);
+    char* saved = static_cast<char*>(p->saved);
+    char *u = scratch + sc.u, *delta = scratch + sc.delta, *du = scratch + sc.du, *ddelta = scratch + sc.ddelta;
+    char *dP = scratch + sc.dP, *part_dt = scratch + sc.part_dt, *part_x = scratch + sc.part_x;
+    float* dB = reinterpret_cast<float*>(scratch + sc.dB);
+    float* dC = reinterpret_cast<float*>(scratch + sc.dC);
+    char* P = saved + sv.P_off;
+    const int B = p->batch, D = p->dim, L = p->seqlen, N = p->dstate, R = p->dt_rank, Mx = R + 2 * N;
+
+    // recompute the two cheap intermediates
+    ss_conv_params c = conv_params(p, u);
+    if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
+    if (!gemm_rm(h, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
+        return SS_ERR_BACKEND;
+
+    // the scan
+    ss_bwd_params b{};
+    b.fwd = scan_params(p);
+    b.fwd.u = u; b.fwd.delta = delta; b.fwd.z = p->z;
+    b.fwd.Bmat = P + (size_t)R * L * s.esz;
+    b.fwd.Cmat = P + (size_t)(R + N) * L * s.esz;
+    b.fwd.A = p->A; b.fwd.Dskip = p->Dskip; b.fwd.delta_bias = p->dt_bias;
+    b.fwd.workspace = saved + sv.scan_off;
+    b.fwd.workspace_bytes = sv.scan_bytes;
+    b.dout = q->dout;
+    b.du = du; b.ddelta = ddelta; b.dz = q->dz;
+    b.dB = dB; b.dC = dC;
+    b.dA = q->dA; b.dD = q->dD; b.ddelta_bias = q->ddt_bias;
+    if ((rc = ss::scan_bwd_strided(&b, (long)Mx * L, stream)) != SS_OK) return rc;
+
+    // delta_raw = W_dt @ r:  dr = W_dt^T @ ddelta  (rows 0..R-1 of dP),  dW_dt = sum_b ddelta r^T
+    if (!gemm_rm(h, true, false, R, L, D, p->W_dt, R, 0, ddelta, L, (long)D * L, 0.0f, dP, L, (long)Mx * L, B, bf16))
+        return SS_ERR_BACKEND;
+    if (!gemm_rm(h, false, true, D, R, L, ddelta, L, (long)D * L, P, L, (long)Mx * L, 0.0f, part_dt, R, (long)D * R, B, bf16))
+        return SS_ERR_BACKEND;
+    // rows R.. of dP from the scan's float32 dB, dC
+    {
+        const long total = (long)B * 2 * N * L;
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (bf16) hipLaunchKernelGGL(pack_dbc_kernel<ss::bf16_t>, grid, dim3(256), 0, st, dB, dC, reinterpret_cast<ss::bf16_t*>(dP), N, R, (long)L, total);
+        else hipLaunchKernelGGL(pack_dbc_kernel<float>, grid, dim3(256), 0, st, dB, dC, reinterpret_cast<float*>(dP), N, R, (long)L, total);
+        if (hipGetLastError() != hipSuccess) return SS_ERR_LAUNCH;
+    }
+    // [r;B;C] = W_x @ u:  du += W_x^T @ dP,  dW_x = sum_b dP u^T
+    if (!gemm_rm(h, true, false, D, L, Mx, p->W_x, D, 0, dP, L, (long)Mx * L, 1.0f, du, L, (long)D * L, B, bf16))
+        return SS_ERR_BACKEND;
+    if (!gemm_rm(h, false, true, Mx, D, L, dP, L, (long)Mx * L, u, L, (long)D * L, 0.0f, part_x, D, (long)Mx * D, B, bf16))
+        return SS_ERR_BACKEND;
+    {
+        const long n_dt = (long)D * R, n_x = (long)Mx * D;
+        if (bf16) {
+            hipLaunchKernelGGL(sum_partials_kernel<ss::bf16_t>, dim3((unsigned)((n_dt + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const ss::bf16_t*>(part_dt), B, n_dt, q->dW_dt);
+            hipLaunchKernelGGL(sum_partials_kernel<ss::bf16_t>, dim3((unsigned)((n_x + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const ss::bf16_t*>(part_x), B, n_x, q->dW_x);
+        } else {
+            hipLaunchKernelGGL(sum_partials_kernel<float>, dim3((unsigned)((n_dt + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const float*>(part_dt), B, n_dt, q->dW_dt);
+            hipLaunchKernelGGL(sum_partials_kernel<float>, dim3((unsigned)((n_x + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const float*>(part_x), B, n_x, q->dW_x);
+        }
+        if (hipGetLastError() != hipSuccess) return SS_ERR_LAUNCH;
+    }
+    // u = SiLU(conv(x))
+    ss_conv_bwd_params cb{};
+    cb.fwd = conv_params(p, nullptr);
+    cb.dout = du; cb.dx = q->dx; cb.dw = q->dconv_w; cb.dbias = q->dconv_b;
+    return ss_conv_bwd(&cb, stream);
+}
+
+}  // extern "C"

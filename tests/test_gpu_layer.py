@@ -1,0 +1,74 @@
+"""GPU parity of the selective SSM layer (conv, projections, scan, gate) against the float64 oracle.
+
+For bf16 the oracle rounds the three intermediates the layer stores in bf16 (u, [r;B;C], delta_raw)
+exactly where the layer does; everything else is float64."""
+import numpy as np
+import pytest
+
+from oracle import inner_oracle as inn
+from paper_2312_00752_amd.workloads import make_layer_inputs, round_to_bf16
+from tests.util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+PARAMS = ("x", "z", "conv_w", "conv_b", "W_x", "W_dt", "dt_bias", "A", "Dskip")
+GRADS = {"dx": "dx", "dz": "dz", "dconv_w": "dconv_w", "dconv_b": "dconv_b", "dW_x": "dW_x", "dW_dt": "dW_dt",
+         "ddt_bias": "ddt_bias", "dA": "dA", "dD": "dD"}
+
+
+def _rnd(io):
+    if io == "bf16":
+        return lambda a: round_to_bf16(a).astype(np.float64)
+    return lambda a: a.astype(np.float32).astype(np.float64)
+
+
+def _gpu(w, backward=True):
+    import torch
+    from paper_2312_00752_amd import binding as B
+    io = torch.bfloat16 if w["io"] == "bf16" else torch.float32
+    t = {}
+    for k in PARAMS + ("dout",):
+        a = torch.from_numpy(np.ascontiguousarray(w[k])).cuda()
+        t[k] = a.to(io) if k in ("x", "z", "W_x", "W_dt", "dout") else a
+    batch, seqlen, dim, dstate, rank, width = w["shape"]
+    code = B.SS_BF16 if w["io"] == "bf16" else B.SS_F32
+    saved = torch.empty(B.ss_layer_saved_bytes(batch, dim, seqlen, dstate, rank, width, code), dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(B.ss_layer_scratch_bytes(batch, dim, seqlen, dstate, rank, width, code, True), dtype=torch.uint8, device="cuda")
+    args = [t[k] for k in PARAMS]
+    out = B.ss_layer_fwd(*args, scratch=scratch, saved=saved)
+    # a forward call that keeps nothing gives the same result (same kernels, same order)
+    out2 = B.ss_layer_fwd(*args, scratch=scratch)
+    assert torch.equal(out, out2)
+    g = None
+    if backward:
+        scratch.fill_(0x7f)   # nothing in the scratch buffer survives the forward call
+        g = B.ss_layer_bwd(t["dout"], *args, scratch=scratch, saved=saved)
+    torch.cuda.synchronize()
+    return out, g
+
+
+def _check(w, nthreads=0):
+    out, g = _gpu(w)
+    kw = {k: w[k] for k in PARAMS}
+    ref = inn.inner_fwd(rnd=_rnd(w["io"]), nthreads=nthreads, **kw)
+    assert_close(out, ref["out"], w["io"], "out")
+    rg = inn.inner_bwd(dout=w["dout"], rnd=_rnd(w["io"]), nthreads=nthreads, **kw)
+    for name in GRADS:
+        assert_close(g[name], rg[name], w["io"], name)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 200, 96, 16, 3), (1, 1031, 130, 8, 5), (2, 512, 256, 16, 8), (3, 77, 64, 4, 1)])
+def test_layer_small(io, shape):
+    batch, seqlen, dim, dstate, rank = shape
+    _check(make_layer_inputs(batch, seqlen, dim, dstate, io, seed=seqlen, rank=rank))
+
+
+def test_layer_narrow_conv_and_long_sequence():
+    _check(make_layer_inputs(1, 4096, 128, 16, "bf16", seed=5, width=2))
+    _check(make_layer_inputs(1, 2560, 64, 16, "f32", seed=6, width=3))
+
+
+def test_layer_full_size_bf16():
+    """The headline layer shape: batch 8, 2048 tokens, D = 4096, N = 16, R = 128."""
+    _check(make_layer_inputs(8, 2048, 4096, 16, "bf16", seed=2))
