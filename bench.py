@@ -120,6 +120,50 @@ def decode_bench(dev, tokens=512):
             "frac_of_hbm_peak_graph": state_bytes / (us_graph * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
 
+def layer_bench(dev, workload, iters=20):
+    """The layer around the scan at the headline shape (conv + SiLU, projections through rocBLAS,
+    scan, gate; backward with recomputation), and its convolution kernels against the HBM roofline."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    from paper_2312_00752_amd import workloads as wl
+    nb, nl, nd, nn = wl.CONFIGS[workload][:4]
+    w = wl.make_layer_inputs(nb, nl, nd, nn, io="bf16", seed=wl.CONFIGS[workload][5])
+    rank = w["shape"][4]
+    bf = torch.bfloat16
+    t = {k: torch.from_numpy(w[k]).to(dev) for k in ("x", "z", "conv_w", "conv_b", "W_x", "W_dt", "dt_bias", "A", "Dskip", "dout")}
+    for k in ("x", "z", "W_x", "W_dt", "dout"):
+        t[k] = t[k].to(bf)
+    saved = torch.empty(B.ss_layer_saved_bytes(nb, nd, nl, nn, rank), dtype=torch.uint8, device=dev)
+    scratch = torch.empty(B.ss_layer_scratch_bytes(nb, nd, nl, nn, rank), dtype=torch.uint8, device=dev)
+    out = torch.empty_like(t["x"])
+    args = [t[k] for k in ("x", "z", "conv_w", "conv_b", "W_x", "W_dt", "dt_bias", "A", "Dskip")]
+
+    def timed(f):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    fwd_ms = timed(lambda: B.ss_layer_fwd(*args, scratch=scratch, saved=saved, out=out))
+    bwd_ms = timed(lambda: B.ss_layer_bwd(t["dout"], *args, scratch=scratch, saved=saved))
+    cf_ms = timed(lambda: B.ss_conv_fwd(t["x"], t["conv_w"], t["conv_b"], out=out))
+    cb_ms = timed(lambda: B.ss_conv_bwd(t["dout"], t["x"], t["conv_w"], t["conv_b"]))
+    tensor = nb * nd * nl * 2
+    return {"workload": "selective SSM layer, batch %d, L %d, D %d, N %d, R %d, conv width 4, bf16 I/O" % (nb, nl, nd, nn, rank),
+            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "token_channels_per_s": nb * nd * nl / ((fwd_ms + bwd_ms) * 1e-3),
+            "saved_bytes_per_token_channel": saved.numel() / (nb * nd * nl),
+            "conv_fwd": {"ms": cf_ms, "bound": "hbm", "achieved": 2 * tensor / (cf_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": 2 * tensor / (cf_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "conv_bwd": {"ms": cb_ms, "bound": "hbm", "achieved": 3 * tensor / (cb_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": 3 * tensor / (cb_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+
+
 def paper_sweep(dev):
     """The shape of the paper's own scan benchmark (Section 4.5 / Appendix E.5: batch 1,
     D 1024, N 16, bf16 inputs, L = 2^9 .. 2^19), forward only and forward+backward."""
@@ -176,6 +220,7 @@ def main():
     ap.add_argument("--workload", default="mamba1p4b_layer_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the single-token step timing")
+    ap.add_argument("--no-layer", action="store_true", help="skip the timing of the layer around the scan")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="also time the shape of the paper's own scan benchmark over L = 2^9..2^19")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -279,6 +324,8 @@ def main():
     }
     if not args.no_decode:
         res["decode"] = decode_bench(dev)
+    if not args.no_layer and args.workload in ("mamba1p4b_layer_bf16", "mamba130m_layer_bf16"):
+        res["layer"] = layer_bench(dev, args.workload)
     if args.paper_sweep:
         res["paper_sweep"] = paper_sweep(dev)
     if not args.no_cpu_baseline:

@@ -33,18 +33,38 @@ def _identity(a):
 
 
 def inner_fwd(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, rnd=None, nthreads=0):
-    """Returns dict(out, u, P, delta_raw); P = [r; B; C] stacked along axis 1."""
+    """Returns dict(out, u, P, delta_raw, h_last, conv_state); P = [r; B; C] stacked along axis 1.
+    h_last (B,D,N) and conv_state (B,D,W-1) are what the recurrent mode continues from."""
     rnd = rnd or _identity
     x, W_x, W_dt = _f64(x), _f64(W_x), _f64(W_dt)
     N = np.asarray(A).shape[1]
     R = W_dt.shape[1]
     assert W_x.shape == (R + 2 * N, x.shape[1])
-    u = rnd(conv_oracle.conv_fwd(x, conv_w, conv_b, None, silu=True)["out"])
+    c = conv_oracle.conv_fwd(x, conv_w, conv_b, None, silu=True)
+    u = rnd(c["out"])
     P = rnd(np.matmul(W_x[None], u))                       # (B, R+2N, L)
     delta_raw = rnd(np.matmul(W_dt[None], P[:, :R]))       # (B, D, L)
     s = ss_oracle.scan_fwd(u, delta_raw, A, P[:, R:R + N], P[:, R + N:], Dskip=Dskip, z=z,
                            bias=dt_bias, softplus=True, nthreads=nthreads)
-    return {"out": s["out"], "u": u, "P": P, "delta_raw": delta_raw}
+    return {"out": s["out"], "u": u, "P": P, "delta_raw": delta_raw, "h_last": s["h_last"],
+            "conv_state": c["state_out"]}
+
+
+def inner_step(h, conv_state, x_t, z_t, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, rnd=None):
+    """One token of the layer in recurrent mode (Section 2; Eq. 2a/2b applied once after the
+    sliding conv window).  h (B,D,N), conv_state (B,D,W-1), x_t, z_t (B,D).
+    Returns (out_t (B,D), new h, new conv_state); the inputs are not modified."""
+    rnd = rnd or _identity
+    W_x, W_dt = _f64(W_x), _f64(W_dt)
+    N = np.asarray(A).shape[1]
+    R = W_dt.shape[1]
+    u_t, conv_state = conv_oracle.conv_step(conv_state, x_t, conv_w, conv_b, silu=True)
+    u_t = rnd(u_t)
+    P_t = rnd(u_t @ W_x.T)                                 # (B, R+2N)
+    delta_t = rnd(P_t[:, :R] @ W_dt.T)                     # (B, D)
+    out_t, h = ss_oracle.step(h, u_t, delta_t, A, P_t[:, R:R + N], P_t[:, R + N:], Dskip=Dskip, z_t=z_t,
+                              bias=dt_bias, softplus=True)
+    return out_t, h, conv_state
 
 
 def inner_bwd(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, dout, rnd=None, nthreads=0):

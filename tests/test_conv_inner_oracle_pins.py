@@ -169,6 +169,25 @@ def test_layer_is_causal():
     assert np.abs(out2[:, :, 5:] - base[:, :, 5:]).max() > 1e-3
 
 
+def test_layer_token_by_token_equals_whole_and_continues_a_prompt():
+    p = _layer(28, L=12)
+    whole = inn.inner_fwd(**p)
+    w = {k: v for k, v in p.items() if k not in ("x", "z")}
+    # from scratch
+    h, cs = np.zeros((2, 4, 3)), np.zeros((2, 4, 3))
+    for t in range(12):
+        o, h, cs = inn.inner_step(h, cs, p["x"][:, :, t], p["z"][:, :, t], **w)
+        np.testing.assert_allclose(o, whole["out"][:, :, t], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(h, whole["h_last"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_array_equal(cs, whole["conv_state"])
+    # after a prompt of 7 tokens processed in parallel mode
+    head = inn.inner_fwd(x=p["x"][:, :, :7], z=p["z"][:, :, :7], **w)
+    h, cs = head["h_last"], head["conv_state"]
+    for t in range(7, 12):
+        o, h, cs = inn.inner_step(h, cs, p["x"][:, :, t], p["z"][:, :, t], **w)
+        np.testing.assert_allclose(o, whole["out"][:, :, t], rtol=1e-12, atol=1e-13)
+
+
 def test_layer_gradient_finite_differences():
     p = _layer(24)
     G = _rng(25).normal(size=p["x"].shape)
