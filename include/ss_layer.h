@@ -51,6 +51,8 @@ typedef struct {
     const void *W_x, *W_dt;
     const float *dt_bias, *A, *Dskip;
     void *out;
+    float *h_last;      /* (B,D,N) float32 or NULL: state after the last token               */
+    void *conv_state;   /* (B,D,W-1) io_dtype or NULL: the last W-1 inputs of the conv       */
     void *saved;        /* ss_layer_saved_bytes(): written by the forward call, read by the
                            backward call; NULL in a forward call that no backward follows    */
     size_t saved_bytes;
@@ -63,7 +65,8 @@ typedef struct {
 size_t ss_layer_saved_bytes(const ss_layer_params *p);
 size_t ss_layer_scratch_bytes(const ss_layer_params *p, int for_backward);
 
-/* Forward: conv, projections, scan, gate. */
+/* Forward: conv, projections, scan, gate.  h_last and conv_state, if asked for, are what
+ * ss_layer_step continues from after a prompt. */
 int ss_layer_fwd(const ss_layer_params *p, void *stream);
 
 typedef struct {
@@ -76,6 +79,28 @@ typedef struct {
 
 /* Backward: gradient of <out, dout> w.r.t. x, z and every parameter. */
 int ss_layer_bwd(const ss_layer_bwd_params *p, void *stream);
+
+typedef struct {
+    int32_t batch, dim, dstate, dt_rank, conv_width; /* B, D, N, R, W                        */
+    int32_t io_dtype;
+    uint32_t flags;                                  /* must be 0                            */
+    float *h;                  /* (B,D,N) float32 state, updated IN PLACE                    */
+    void *conv_state;          /* (B,D,W-1) io_dtype window, updated IN PLACE                */
+    const void *x_t, *z_t;     /* (B,D)                                                      */
+    const float *conv_w, *conv_b;
+    const void *W_x, *W_dt;
+    const float *dt_bias, *A, *Dskip;
+    void *out_t;               /* (B,D)                                                      */
+    void *scratch;             /* ss_layer_step_scratch_bytes(), 256-byte aligned            */
+    size_t scratch_bytes;
+} ss_layer_step_params;
+
+size_t ss_layer_step_scratch_bytes(const ss_layer_step_params *p);
+
+/* One token of the layer in recurrent mode (Section 2): the conv window slides by one sample,
+ * the projections become (B, D) x (D, R+2N) and (B, R) x (R, D) products, and Eq. 2a/2b are
+ * applied once; constant time and memory per token. */
+int ss_layer_step(const ss_layer_step_params *p, void *stream);
 
 #ifdef __cplusplus
 }

@@ -65,6 +65,7 @@ class LayerParams(ctypes.Structure):
                 ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
                 ("x", _vp), ("z", _vp), ("conv_w", _vp), ("conv_b", _vp), ("W_x", _vp), ("W_dt", _vp),
                 ("dt_bias", _vp), ("A", _vp), ("Dskip", _vp), ("out", _vp),
+                ("h_last", _vp), ("conv_state", _vp),
                 ("saved", _vp), ("saved_bytes", ctypes.c_size_t),
                 ("scratch", _vp), ("scratch_bytes", ctypes.c_size_t)]
 
@@ -73,6 +74,15 @@ class LayerBwdParams(ctypes.Structure):
     _fields_ = [("fwd", LayerParams), ("dout", _vp), ("dx", _vp), ("dz", _vp),
                 ("dconv_w", _vp), ("dconv_b", _vp), ("dW_x", _vp), ("dW_dt", _vp),
                 ("ddt_bias", _vp), ("dA", _vp), ("dD", _vp)]
+
+
+class LayerStepParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("dstate", ctypes.c_int32),
+                ("dt_rank", ctypes.c_int32), ("conv_width", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("flags", ctypes.c_uint32),
+                ("h", _vp), ("conv_state", _vp), ("x_t", _vp), ("z_t", _vp), ("conv_w", _vp), ("conv_b", _vp),
+                ("W_x", _vp), ("W_dt", _vp), ("dt_bias", _vp), ("A", _vp), ("Dskip", _vp), ("out_t", _vp),
+                ("scratch", _vp), ("scratch_bytes", ctypes.c_size_t)]
 
 
 SS_ERR_BACKEND = -7
@@ -112,6 +122,10 @@ def lib():
         l.ss_layer_fwd.argtypes = [ctypes.POINTER(LayerParams), _vp]
         l.ss_layer_bwd.restype = ctypes.c_int
         l.ss_layer_bwd.argtypes = [ctypes.POINTER(LayerBwdParams), _vp]
+        l.ss_layer_step_scratch_bytes.restype = ctypes.c_size_t
+        l.ss_layer_step_scratch_bytes.argtypes = [ctypes.POINTER(LayerStepParams)]
+        l.ss_layer_step.restype = ctypes.c_int
+        l.ss_layer_step.argtypes = [ctypes.POINTER(LayerStepParams), _vp]
         l.ss_strerror.restype = ctypes.c_char_p
         l.ss_strerror.argtypes = [ctypes.c_int]
         l.ss_version.restype = ctypes.c_int
@@ -433,17 +447,65 @@ def _layer_params(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, saved, scr
     return p
 
 
-def ss_layer_fwd(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scratch, saved=None, out=None, stream=None):
-    """Enqueue the layer's forward pass; ``saved`` (if given) is filled for ``ss_layer_bwd``."""
+def ss_layer_fwd(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scratch, saved=None, out=None,
+                 return_states=False, stream=None):
+    """Enqueue the layer's forward pass; ``saved`` (if given) is filled for ``ss_layer_bwd``.
+    Returns out, or (out, h_last, conv_state) with ``return_states``."""
     import torch
     p = _layer_params(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, saved, scratch)
     if out is None:
         out = torch.empty_like(x)
     p.out = _ptr(out, x.dtype, x.shape, "out")
+    h_last = conv_state = None
+    if return_states:
+        h_last = torch.empty((p.batch, p.dim, p.dstate), dtype=torch.float32, device=x.device)
+        conv_state = torch.empty((p.batch, p.dim, p.conv_width - 1), dtype=x.dtype, device=x.device)
+        p.h_last = _ptr(h_last, None, None, "h_last")
+        p.conv_state = _ptr(conv_state, None, None, "conv_state")
     rc = lib().ss_layer_fwd(ctypes.byref(p), _stream(stream))
     if rc != SS_OK:
         raise SsError(rc)
-    return out
+    return (out, h_last, conv_state) if return_states else out
+
+
+def ss_layer_step_scratch_bytes(batch, dim, dstate, dt_rank, io_dtype=SS_BF16):
+    p = LayerStepParams()
+    p.batch, p.dim, p.dstate, p.dt_rank, p.conv_width, p.io_dtype = batch, dim, dstate, dt_rank, 4, io_dtype
+    return int(lib().ss_layer_step_scratch_bytes(ctypes.byref(p)))
+
+
+def ss_layer_step(h, conv_state, x_t, z_t, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scratch, out_t=None,
+                  stream=None):
+    """Enqueue one token of the layer; ``h`` (B,D,N) and ``conv_state`` (B,D,W-1) are updated in place."""
+    import torch
+    f32 = torch.float32
+    nb, nd, nn = h.shape
+    rank = W_dt.shape[1]
+    width = conv_w.shape[1]
+    io = x_t.dtype
+    p = LayerStepParams()
+    p.batch, p.dim, p.dstate, p.dt_rank, p.conv_width = nb, nd, nn, rank, width
+    p.io_dtype = _io_code(x_t)
+    p.h = _ptr(h, f32, (nb, nd, nn), "h")
+    p.conv_state = _ptr(conv_state, io, (nb, nd, width - 1), "conv_state")
+    p.x_t = _ptr(x_t, io, (nb, nd), "x_t")
+    p.z_t = _ptr(z_t, io, (nb, nd), "z_t")
+    p.conv_w = _ptr(conv_w, f32, (nd, width), "conv_w")
+    p.conv_b = _ptr(conv_b, f32, (nd,), "conv_b")
+    p.W_x = _ptr(W_x, io, (rank + 2 * nn, nd), "W_x")
+    p.W_dt = _ptr(W_dt, io, (nd, rank), "W_dt")
+    p.dt_bias = _ptr(dt_bias, f32, (nd,), "dt_bias")
+    p.A = _ptr(A, f32, (nd, nn), "A")
+    p.Dskip = _ptr(Dskip, f32, (nd,), "Dskip")
+    if out_t is None:
+        out_t = torch.empty_like(x_t)
+    p.out_t = _ptr(out_t, io, (nb, nd), "out_t")
+    p.scratch = _ptr(scratch, torch.uint8, None, "scratch")
+    p.scratch_bytes = scratch.numel()
+    rc = lib().ss_layer_step(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return out_t
 
 
 def ss_layer_bwd(dout, x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scratch, saved, stream=None):

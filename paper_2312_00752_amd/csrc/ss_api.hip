@@ -204,6 +204,33 @@ int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
 }
 
 
+int step_strided(const ss_step_params* p, long bc_stride, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    if (p->batch < 1 || p->dim < 1 || p->dstate < 1) return SS_ERR_SHAPE;
+    if (p->dstate > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
+    if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+    if (p->flags & ~kStepFlags) return SS_ERR_UNSUPPORTED;
+    if (!p->h || !p->u_t || !p->delta_t || !p->B_t || !p->C_t || !p->A || !p->out_t) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_Z) && !p->z_t) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_D) && !p->Dskip) return SS_ERR_NULL;
+    if ((p->flags & SS_HAS_DELTA_BIAS) && !p->delta_bias) return SS_ERR_NULL;
+    if (!aligned(p->h, 16)) return SS_ERR_ALIGN;
+    const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
+    const void* io[] = {p->u_t, p->delta_t, p->z_t, p->B_t, p->C_t, p->out_t};
+    for (const void* q : io)
+        if (q && !aligned(q, esz)) return SS_ERR_ALIGN;
+    const void* f32[] = {p->A, p->Dskip, p->delta_bias};
+    for (const void* q : f32)
+        if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
+    ss::StepArgs a{};
+    a.B = p->batch; a.D = p->dim; a.N = p->dstate; a.flags = p->flags;
+    a.h = p->h; a.u_t = p->u_t; a.delta_t = p->delta_t; a.z_t = p->z_t;
+    a.B_t = p->B_t; a.C_t = p->C_t; a.bc_stride = bc_stride; a.A = p->A; a.Dskip = p->Dskip; a.bias = p->delta_bias;
+    a.out_t = p->out_t;
+    return ss::launch_step(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+}
+
 }  // namespace ss
 
 extern "C" {
@@ -229,28 +256,7 @@ int ss_scan_bwd(const ss_bwd_params* p, void* stream)
 int ss_step(const ss_step_params* p, void* stream)
 {
     if (!p) return SS_ERR_NULL;
-    if (p->batch < 1 || p->dim < 1 || p->dstate < 1) return SS_ERR_SHAPE;
-    if (p->dstate > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
-    if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
-    if (p->flags & ~kStepFlags) return SS_ERR_UNSUPPORTED;
-    if (!p->h || !p->u_t || !p->delta_t || !p->B_t || !p->C_t || !p->A || !p->out_t) return SS_ERR_NULL;
-    if ((p->flags & SS_HAS_Z) && !p->z_t) return SS_ERR_NULL;
-    if ((p->flags & SS_HAS_D) && !p->Dskip) return SS_ERR_NULL;
-    if ((p->flags & SS_HAS_DELTA_BIAS) && !p->delta_bias) return SS_ERR_NULL;
-    if (!aligned(p->h, 16)) return SS_ERR_ALIGN;
-    const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
-    const void* io[] = {p->u_t, p->delta_t, p->z_t, p->B_t, p->C_t, p->out_t};
-    for (const void* q : io)
-        if (q && !aligned(q, esz)) return SS_ERR_ALIGN;
-    const void* f32[] = {p->A, p->Dskip, p->delta_bias};
-    for (const void* q : f32)
-        if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
-    ss::StepArgs a{};
-    a.B = p->batch; a.D = p->dim; a.N = p->dstate; a.flags = p->flags;
-    a.h = p->h; a.u_t = p->u_t; a.delta_t = p->delta_t; a.z_t = p->z_t;
-    a.B_t = p->B_t; a.C_t = p->C_t; a.A = p->A; a.Dskip = p->Dskip; a.bias = p->delta_bias;
-    a.out_t = p->out_t;
-    return ss::launch_step(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+    return ss::step_strided(p, p->dstate, stream);
 }
 
 const char* ss_strerror(int code)

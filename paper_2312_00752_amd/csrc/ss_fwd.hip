@@ -268,7 +268,7 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
         const float4 A4 = *reinterpret_cast<const float4*>(a.A + (long)d * NPAD + q * STATES_PER_LANE);
         hv[0] = h4.x; hv[1] = h4.y; hv[2] = h4.z; hv[3] = h4.w;
         Av[0] = A4.x; Av[1] = A4.y; Av[2] = A4.z; Av[3] = A4.w;
-        const long bo = (long)b * NPAD + q * STATES_PER_LANE;
+        const long bo = (long)b * a.bc_stride + q * STATES_PER_LANE;
         if constexpr (sizeof(T) == 2) {
             const uint2 Bw = *reinterpret_cast<const uint2*>(B_t + bo);
             const uint2 Cw = *reinterpret_cast<const uint2*>(C_t + bo);
@@ -287,8 +287,8 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
             const bool ok = n < N;
             hv[k] = ok ? hp[k] : 0.0f;
             Av[k] = ok ? a.A[(long)d * N + n] : 0.0f;
-            Bv[k] = ok ? ld(B_t, (long)b * N + n) : 0.0f;
-            Cv[k] = ok ? ld(C_t, (long)b * N + n) : 0.0f;
+            Bv[k] = ok ? ld(B_t, (long)b * a.bc_stride + n) : 0.0f;
+            Cv[k] = ok ? ld(C_t, (long)b * a.bc_stride + n) : 0.0f;
         }
     }
     const float u = ld(u_t, row);
@@ -388,7 +388,8 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
     // which N == 16 and the element-aligned base pointers checked by the caller give only
     // when the bases themselves are that aligned
     const size_t va = io_dtype == 0 ? 16 : 8;
-    const bool vec = a.N == NPAD && reinterpret_cast<uintptr_t>(a.B_t) % va == 0 &&
+    const bool vec = a.N == NPAD && (a.bc_stride * (io_dtype == 0 ? 4 : 2)) % va == 0 &&
+                     reinterpret_cast<uintptr_t>(a.B_t) % va == 0 &&
                      reinterpret_cast<uintptr_t>(a.C_t) % va == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
     const bool zoh = a.flags & F_EXACT_ZOH_B;
 #define SS_LAUNCH_STEP(T, V, Z) step_kernel<T, V, Z><<<grid, block, 0, stream>>>(a)

@@ -52,6 +52,7 @@ struct StepArgs {
     uint32_t flags;
     float* h;
     const void *u_t, *delta_t, *z_t, *B_t, *C_t;
+    long bc_stride;  // elements between consecutive batch rows of B_t and C_t (N when dense)
     const float *A, *Dskip, *bias;
     void* out_t;
 };
@@ -66,5 +67,7 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream);
 // Validation and return codes are those of ss_scan_fwd / ss_scan_bwd.
 int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream);
 int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream);
+// ss_step with B_t / C_t rows bc_stride elements apart (the public call passes dstate).
+int step_strided(const ss_step_params* p, long bc_stride, void* stream);
 
 }  // namespace ss

@@ -196,6 +196,8 @@ int check_layer(const ss_layer_params* p, bool bwd)
     if (!p->x || !p->z || !p->conv_w || !p->conv_b || !p->W_x || !p->W_dt || !p->dt_bias || !p->A || !p->Dskip)
         return SS_ERR_NULL;
     if (!bwd && !p->out) return SS_ERR_NULL;
+    if (!bwd && ((p->h_last && !aligned_to(p->h_last, 4)) || (p->conv_state && !aligned_to(p->conv_state, 2))))
+        return SS_ERR_ALIGN;
     const void* io[] = {p->x, p->z, p->W_x, p->W_dt, bwd ? nullptr : p->out};
     for (const void* q : io)
         if (q && !aligned_to(q, 16)) return SS_ERR_ALIGN;
@@ -256,7 +258,11 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     char* P = saved ? saved + sv.P_off : scratch + sc.P;
     const int B = p->batch, D = p->dim, L = p->seqlen, N = p->dstate, R = p->dt_rank, Mx = R + 2 * N;
 
-    const ss_conv_params c = conv_params(p, u);
+    ss_conv_params c = conv_params(p, u);
+    if (p->conv_state && p->conv_width > 1) {
+        c.flags |= SS_CONV_WRITE_STATE;
+        c.state_out = p->conv_state;
+    }
     if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
     // [r;B;C] = W_x @ u
     if (!gemm_rm(h, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16))
@@ -270,6 +276,10 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     f.Cmat = P + (size_t)(R + N) * L * s.esz;
     f.A = p->A; f.Dskip = p->Dskip; f.delta_bias = p->dt_bias;
     f.out = p->out;
+    if (p->h_last) {
+        f.flags |= SS_WRITE_H_LAST;
+        f.h_last = p->h_last;
+    }
     if (saved) {
         f.flags |= SS_SAVE_FOR_BWD;
         f.workspace = saved + sv.scan_off;
@@ -365,6 +375,58 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
     cb.fwd = conv_params(p, nullptr);
     cb.dout = du; cb.dx = q->dx; cb.dw = q->dconv_w; cb.dbias = q->dconv_b;
     return ss_conv_bwd(&cb, stream);
+}
+
+size_t ss_layer_step_scratch_bytes(const ss_layer_step_params* p)
+{
+    if (!p || p->batch < 1 || p->dim < 1 || p->dstate < 1 || p->dt_rank < 1) return 0;
+    const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
+    const size_t B = p->batch, D = p->dim, Mx = (size_t)p->dt_rank + 2 * (size_t)p->dstate;
+    return 2 * round_up(B * D * esz, 256) + round_up(B * Mx * esz, 256);   // u_t, delta_t, [r;B;C]_t
+}
+
+int ss_layer_step(const ss_layer_step_params* p, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    if (p->batch < 1 || p->dim < 1 || p->dstate < 1 || p->dt_rank < 1 || p->conv_width < 1) return SS_ERR_SHAPE;
+    if (p->dstate > SS_MAX_DSTATE || p->conv_width > SS_CONV_MAX_WIDTH) return SS_ERR_UNSUPPORTED;
+    if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+    if (p->flags != 0) return SS_ERR_UNSUPPORTED;
+    if (!p->h || !p->x_t || !p->z_t || !p->conv_w || !p->conv_b || !p->W_x || !p->W_dt || !p->dt_bias || !p->A ||
+        !p->Dskip || !p->out_t || (p->conv_width > 1 && !p->conv_state))
+        return SS_ERR_NULL;
+    if (!aligned_to(p->W_x, 16) || !aligned_to(p->W_dt, 16)) return SS_ERR_ALIGN;
+    if (!p->scratch || p->scratch_bytes < ss_layer_step_scratch_bytes(p)) return SS_ERR_WORKSPACE;
+    if (!aligned_to(p->scratch, 256)) return SS_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rocblas_handle h = blas_handle(st);
+    if (!h) return SS_ERR_BACKEND;
+    const bool bf16 = p->io_dtype == SS_BF16;
+    const size_t esz = bf16 ? 2 : 4;
+    const int B = p->batch, D = p->dim, N = p->dstate, R = p->dt_rank, Mx = R + 2 * N;
+    char* scratch = static_cast<char*>(p->scratch);
+    char* u_t = scratch;
+    char* delta_t = u_t + round_up((size_t)B * D * esz, 256);
+    char* P_t = delta_t + round_up((size_t)B * D * esz, 256);
+
+    ss_conv_step_params c{};
+    c.batch = B; c.dim = D; c.width = p->conv_width; c.io_dtype = p->io_dtype;
+    c.flags = SS_CONV_SILU | SS_CONV_HAS_BIAS;
+    c.state = p->conv_state; c.x_t = p->x_t; c.w = p->conv_w; c.bias = p->conv_b; c.out_t = u_t;
+    int rc = ss_conv_step(&c, stream);
+    if (rc != SS_OK) return rc;
+    // [r;B;C]_t (B, Mx) = u_t (B, D) @ W_x^T;   delta_t (B, D) = r_t (B, R) @ W_dt^T
+    if (!gemm_rm(h, false, true, B, Mx, D, u_t, D, 0, p->W_x, D, 0, 0.0f, P_t, Mx, 0, 1, bf16)) return SS_ERR_BACKEND;
+    if (!gemm_rm(h, false, true, B, D, R, P_t, Mx, 0, p->W_dt, R, 0, 0.0f, delta_t, D, 0, 1, bf16)) return SS_ERR_BACKEND;
+    ss_step_params s{};
+    s.batch = B; s.dim = D; s.dstate = N; s.io_dtype = p->io_dtype;
+    s.flags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z;
+    s.h = p->h; s.u_t = u_t; s.delta_t = delta_t; s.z_t = p->z_t;
+    s.B_t = P_t + (size_t)R * esz;
+    s.C_t = P_t + (size_t)(R + N) * esz;
+    s.A = p->A; s.Dskip = p->Dskip; s.delta_bias = p->dt_bias;
+    s.out_t = p->out_t;
+    return ss::step_strided(&s, Mx, stream);
 }
 
 }  // extern "C"

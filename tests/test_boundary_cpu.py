@@ -19,13 +19,14 @@ def test_library_exports_every_declared_symbol():
         hdr = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, fn)).read(), flags=re.S)
         names |= set(re.findall(r"\b(ss_[a-z_]+)\s*\(", hdr))
     assert {"ss_scan_fwd", "ss_scan_bwd", "ss_step", "ss_workspace_bytes", "ss_strerror", "ss_version",
-            "ss_conv_fwd", "ss_conv_bwd", "ss_conv_step"} <= names
+            "ss_conv_fwd", "ss_conv_bwd", "ss_conv_step", "ss_layer_fwd", "ss_layer_bwd", "ss_layer_step",
+            "ss_layer_saved_bytes", "ss_layer_scratch_bytes", "ss_layer_step_scratch_bytes"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), n
     assert B.ss_version() >= 100
     assert B.ss_strerror(0) == "success"
-    for code in range(-6, 0):
+    for code in range(-7, 0):
         assert B.ss_strerror(code) not in ("", "success", "unknown error code")
 
 
@@ -205,3 +206,52 @@ def test_conv_struct_layout_and_rejections():
     assert B.lib().ss_conv_step(ctypes.byref(s), None) == B.SS_ERR_NULL
     s.width = 9
     assert B.lib().ss_conv_step(ctypes.byref(s), None) == B.SS_ERR_UNSUPPORTED
+
+
+# ---------------------------------------------------------------- the layer
+def _good_layer():
+    p = B.LayerParams()
+    p.batch, p.dim, p.seqlen, p.dstate, p.dt_rank, p.conv_width = 2, 64, 128, 16, 4, 4
+    p.io_dtype = B.SS_BF16
+    for f in ("x", "z", "conv_w", "conv_b", "W_x", "W_dt", "dt_bias", "A", "Dskip", "out", "scratch"):
+        setattr(p, f, FAKE)
+    p.scratch_bytes = 1 << 30
+    return p
+
+
+def test_layer_struct_layout_sizes_and_rejections():
+    assert ctypes.sizeof(B.LayerParams) == 8 * 4 + 16 * 8
+    assert ctypes.sizeof(B.LayerBwdParams) == ctypes.sizeof(B.LayerParams) + 10 * 8
+    assert ctypes.sizeof(B.LayerStepParams) == 7 * 4 + 4 + 14 * 8
+    saved = B.ss_layer_saved_bytes(8, 4096, 2048, 16, 128)
+    # [r;B;C] in bf16 plus the scan's own workspace
+    assert saved >= 8 * 160 * 2048 * 2 + B.ss_workspace_bytes(8, 4096, 2048, 16, True, B.SS_BF16, True)
+    assert saved < 1.02 * (8 * 160 * 2048 * 2 + B.ss_workspace_bytes(8, 4096, 2048, 16, True, B.SS_BF16, True))
+    assert B.ss_layer_scratch_bytes(8, 4096, 2048, 16, 128, for_backward=False) >= 2 * 8 * 4096 * 2048 * 2
+    assert B.ss_layer_scratch_bytes(8, 4096, 2048, 16, 128, for_backward=True) >= 4 * 8 * 4096 * 2048 * 2
+    fwd = lambda p: B.lib().ss_layer_fwd(ctypes.byref(p), None)
+    assert B.lib().ss_layer_fwd(None, None) == B.SS_ERR_NULL
+    for f in ("x", "z", "conv_w", "conv_b", "W_x", "W_dt", "dt_bias", "A", "Dskip", "out"):
+        p = _good_layer(); setattr(p, f, None)
+        assert fwd(p) == B.SS_ERR_NULL, f
+    for f, v in (("batch", 0), ("dim", 0), ("seqlen", 0), ("dstate", 0), ("dt_rank", 0), ("conv_width", 0)):
+        p = _good_layer(); setattr(p, f, v)
+        assert fwd(p) == B.SS_ERR_SHAPE, f
+    p = _good_layer(); p.dstate = 17
+    assert fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_layer(); p.flags = 1
+    assert fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_layer(); p.scratch_bytes = 1000
+    assert fwd(p) == B.SS_ERR_WORKSPACE
+    p = _good_layer(); p.scratch = None
+    assert fwd(p) == B.SS_ERR_WORKSPACE
+    p = _good_layer(); p.saved = FAKE; p.saved_bytes = 10
+    assert fwd(p) == B.SS_ERR_WORKSPACE
+    p = _good_layer(); p.x = FAKE + 4
+    assert fwd(p) == B.SS_ERR_ALIGN
+    q = B.LayerBwdParams(); q.fwd = _good_layer()
+    assert B.lib().ss_layer_bwd(ctypes.byref(q), None) == B.SS_ERR_WORKSPACE   # nothing saved
+    s = B.LayerStepParams()
+    s.batch, s.dim, s.dstate, s.dt_rank, s.conv_width, s.io_dtype = 2, 8, 4, 2, 4, B.SS_F32
+    assert B.lib().ss_layer_step(ctypes.byref(s), None) == B.SS_ERR_NULL
+    assert B.ss_strerror(B.SS_ERR_BACKEND) not in ("", "unknown error code")

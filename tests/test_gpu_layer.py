@@ -72,3 +72,35 @@ def test_layer_narrow_conv_and_long_sequence():
 def test_layer_full_size_bf16():
     """The headline layer shape: batch 8, 2048 tokens, D = 4096, N = 16, R = 128."""
     _check(make_layer_inputs(8, 2048, 4096, 16, "bf16", seed=2))
+
+
+@pytest.mark.parametrize("io,shape", [("bf16", (4, 96, 256, 16, 8)), ("f32", (2, 40, 72, 5, 3)), ("bf16", (1, 33, 128, 16, 6))])
+def test_layer_prompt_then_token_by_token(io, shape):
+    """Recurrent mode (Section 2): a prompt in parallel mode hands its states to single-token steps;
+    the outputs must equal the parallel mode over the whole sequence."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    batch, seqlen, dim, dstate, rank = shape
+    w = make_layer_inputs(batch, seqlen, dim, dstate, io, seed=seqlen + 1, rank=rank)
+    tio = torch.bfloat16 if io == "bf16" else torch.float32
+    t = {}
+    for k in PARAMS:
+        a = torch.from_numpy(np.ascontiguousarray(w[k])).cuda()
+        t[k] = a.to(tio) if k in ("x", "z", "W_x", "W_dt") else a
+    code = B.SS_BF16 if io == "bf16" else B.SS_F32
+    scratch = torch.empty(B.ss_layer_scratch_bytes(batch, dim, seqlen, dstate, rank, 4, code, False), dtype=torch.uint8, device="cuda")
+    step_scratch = torch.empty(B.ss_layer_step_scratch_bytes(batch, dim, dstate, rank, code), dtype=torch.uint8, device="cuda")
+    weights = [t[k] for k in PARAMS[2:]]
+    cut = seqlen - 12
+    head, h, cs = B.ss_layer_fwd(t["x"][:, :, :cut].contiguous(), t["z"][:, :, :cut].contiguous(), *weights,
+                                 scratch=scratch, return_states=True)
+    outs = [head]
+    for i in range(cut, seqlen):
+        o = B.ss_layer_step(h, cs, t["x"][:, :, i].contiguous(), t["z"][:, :, i].contiguous(), *weights, scratch=step_scratch)
+        outs.append(o[:, :, None].clone())
+    got = torch.cat(outs, 2)
+    ref = inn.inner_fwd(rnd=_rnd(io), **{k: w[k] for k in PARAMS})
+    assert_close(got[:, :, :cut], ref["out"][:, :, :cut], io, "prompt out")
+    assert_close(got[:, :, cut:], ref["out"][:, :, cut:], io, "decoded out")
+    assert_close(h, ref["h_last"], io, "h after decode")
+    np.testing.assert_array_equal(cs.float().cpu().numpy(), ref["conv_state"].astype(np.float32))
