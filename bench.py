@@ -154,10 +154,24 @@ def layer_bench(dev, workload, iters=20):
     bwd_ms = timed(lambda: B.ss_layer_bwd(t["dout"], *args, scratch=scratch, saved=saved))
     cf_ms = timed(lambda: B.ss_conv_fwd(t["x"], t["conv_w"], t["conv_b"], out=out))
     cb_ms = timed(lambda: B.ss_conv_bwd(t["dout"], t["x"], t["conv_w"], t["conv_b"]))
+    # recurrent mode: the prompt's states, then 128 single-token steps at batch 64
+    db = 64
+    xs = torch.randn(8, db, nd, device=dev).to(bf)
+    zs = torch.randn(8, db, nd, device=dev).to(bf)
+    h = torch.zeros(db, nd, nn, device=dev)
+    cs = torch.zeros(db, nd, 3, device=dev, dtype=bf)
+    o_t = torch.empty(db, nd, device=dev, dtype=bf)
+    sscr = torch.empty(B.ss_layer_step_scratch_bytes(db, nd, nn, rank), dtype=torch.uint8, device=dev)
+
+    def decode():
+        for i in range(128):
+            B.ss_layer_step(h, cs, xs[i % 8], zs[i % 8], *args[2:], scratch=sscr, out_t=o_t)
+    dec_ms = timed(decode) if iters >= 5 else None
     tensor = nb * nd * nl * 2
     return {"workload": "selective SSM layer, batch %d, L %d, D %d, N %d, R %d, conv width 4, bf16 I/O" % (nb, nl, nd, nn, rank),
             "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "token_channels_per_s": nb * nd * nl / ((fwd_ms + bwd_ms) * 1e-3),
             "saved_bytes_per_token_channel": saved.numel() / (nb * nd * nl),
+            "decode_us_per_token_batch64": None if dec_ms is None else dec_ms * 1e3 / 128,
             "conv_fwd": {"ms": cf_ms, "bound": "hbm", "achieved": 2 * tensor / (cf_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                          "unit": "GB/s", "frac": 2 * tensor / (cf_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "conv_bwd": {"ms": cb_ms, "bound": "hbm", "achieved": 3 * tensor / (cb_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
