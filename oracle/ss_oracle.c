@@ -31,7 +31,8 @@
  *
  * Layouts (row-major, last index fastest):
  *   u, delta, z, out, dout, du, ddelta, dz : (B, D, L)
- *   Bm, Cm, dB, dC                         : (B, N, L)
+ *   Bm, Cm, dB, dC                         : (B, N, L); (D, N) for one that is "fixed"
+ *                                            (time-invariant, Algorithm 1 / the ablation of Table 7)
  *   A, dA                                  : (D, N)
  *   Dskip, bias, dD, dbias                 : (D)
  *   h0, h_last, dh_last, dh0               : (B, D, N)
@@ -97,13 +98,20 @@ int ss_oracle_threads(void)
 #endif
 }
 
+/* Position of B or C for batch b, channel d, state n, step t: the selective (B,N,L) tensor
+ * of Algorithm 2, or the time-invariant (D,N) parameter of Algorithm 1. */
+static long bc_index(int fixed, int b, int d, int n, long t, int nn, long nl)
+{
+    return fixed ? (long)d * nn + n : ((long)b * nn + n) * nl + t;
+}
+
 /* Forward.  Optional pointers may be NULL: z, Dskip, bias, h0, h_last, y_pre.
  * y_pre, when given, receives y_t before the gate.  Returns 0, or -1 on bad sizes. */
 int ss_oracle_fwd(int nb, int nd, long nl, int nn,
                   const double *u, const double *delta, const double *z,
                   const double *Bm, const double *Cm, const double *A,
                   const double *Dskip, const double *bias, const double *h0,
-                  int softplus, int exact_zoh,
+                  int softplus, int exact_zoh, int b_fixed, int c_fixed,
                   double *out, double *h_last, double *y_pre, int nthreads)
 {
     if (nb <= 0 || nd <= 0 || nl < 0 || nn <= 0)
@@ -129,9 +137,9 @@ int ss_oracle_fwd(int nb, int nd, long nl, int nn,
             for (int n = 0; n < nn; ++n) {
                 double a = A[(long)d * nn + n];
                 double abar = exp(dt * a);
-                double bbar = phi_f64(exact_zoh, dt, a) * Bm[((long)b * nn + n) * nl + t];
+                double bbar = phi_f64(exact_zoh, dt, a) * Bm[bc_index(b_fixed, b, d, n, t, nn, nl)];
                 h[n] = abar * h[n] + bbar * ut;
-                y += Cm[((long)b * nn + n) * nl + t] * h[n];
+                y += Cm[bc_index(c_fixed, b, d, n, t, nn, nl)] * h[n];
             }
             if (Dskip)
                 y += Dskip[d] * ut;
@@ -158,7 +166,7 @@ int ss_oracle_bwd(int nb, int nd, long nl, int nn,
                   const double *u, const double *delta, const double *z,
                   const double *Bm, const double *Cm, const double *A,
                   const double *Dskip, const double *bias, const double *h0,
-                  int softplus, int exact_zoh,
+                  int softplus, int exact_zoh, int b_fixed, int c_fixed,
                   const double *dout, const double *dh_last,
                   double *du, double *ddelta, double *dz,
                   double *dB, double *dC, double *dA,
@@ -172,8 +180,8 @@ int ss_oracle_bwd(int nb, int nd, long nl, int nn,
 #else
     nthreads = 1;
 #endif
-    memset(dB, 0, sizeof(double) * (size_t)nb * nn * nl);
-    memset(dC, 0, sizeof(double) * (size_t)nb * nn * nl);
+    memset(dB, 0, sizeof(double) * (b_fixed ? (size_t)nd * nn : (size_t)nb * nn * nl));
+    memset(dC, 0, sizeof(double) * (c_fixed ? (size_t)nd * nn : (size_t)nb * nn * nl));
     memset(dA, 0, sizeof(double) * (size_t)nd * nn);
     if (dD)
         memset(dD, 0, sizeof(double) * (size_t)nd);
@@ -217,7 +225,7 @@ int ss_oracle_bwd(int nb, int nd, long nl, int nn,
                                                  : (h0 ? h0[row * nn + n] : 0.0);
                             double abar = exp(dt * Arow[n]);
                             double bbar = phi_f64(exact_zoh, dt, Arow[n]) *
-                                          Bm[((long)b * nn + n) * nl + t];
+                                          Bm[bc_index(b_fixed, b, d, n, t, nn, nl)];
                             hs[t * nn + n] = abar * hprev + bbar * ut;
                         }
                     }
@@ -235,7 +243,7 @@ int ss_oracle_bwd(int nb, int nd, long nl, int nn,
                             double s = sigmoid_f64(zt);
                             double y = 0.0;
                             for (int n = 0; n < nn; ++n)
-                                y += Cm[((long)b * nn + n) * nl + t] * hs[t * nn + n];
+                                y += Cm[bc_index(c_fixed, b, d, n, t, nn, nl)] * hs[t * nn + n];
                             if (Dskip)
                                 y += Dskip[d] * ut;
                             /* d/dz [ z*sigmoid(z) ] = s*(1 + z*(1-s)) */
@@ -248,20 +256,27 @@ int ss_oracle_bwd(int nb, int nd, long nl, int nn,
                             dDacc += dy * ut;
                         }
                         for (int n = 0; n < nn; ++n) {
-                            long bnt = ((long)b * nn + n) * nl + t;
+                            double Bv = Bm[bc_index(b_fixed, b, d, n, t, nn, nl)];
+                            double Cv = Cm[bc_index(c_fixed, b, d, n, t, nn, nl)];
                             double a = Arow[n];
                             double hprev = t > 0 ? hs[(t - 1) * nn + n]
                                                  : (h0 ? h0[row * nn + n] : 0.0);
                             double abar = exp(dt * a);
                             double phi = phi_f64(exact_zoh, dt, a);
                             /* y_t = sum C h_t  ->  dC, and dy enters g */
-                            dCp[n * nl + t] += dy * hs[t * nn + n];
-                            double gt = g[n] + Cm[bnt] * dy;
+                            if (c_fixed)
+                                dC[(long)d * nn + n] += dy * hs[t * nn + n]; /* this thread owns channel d */
+                            else
+                                dCp[n * nl + t] += dy * hs[t * nn + n];
+                            double gt = g[n] + Cv * dy;
                             /* h_t = abar*hprev + phi*B*u */
                             double dabar = gt * hprev;
-                            double dphi = gt * Bm[bnt] * ut;
-                            dBp[n * nl + t] += gt * phi * ut;
-                            du_t += gt * phi * Bm[bnt];
+                            double dphi = gt * Bv * ut;
+                            if (b_fixed)
+                                dB[(long)d * nn + n] += gt * phi * ut;
+                            else
+                                dBp[n * nl + t] += gt * phi * ut;
+                            du_t += gt * phi * Bv;
                             /* abar = exp(dt*a) ; phi = phi(dt, a) */
                             ddt += dabar * a * abar + dphi * dphi_ddelta_f64(exact_zoh, dt, a);
                             dA[(long)d * nn + n] += dabar * dt * abar +
@@ -285,8 +300,10 @@ int ss_oracle_bwd(int nb, int nd, long nl, int nn,
                 {
                     double *dBb = dB + (size_t)b * ln, *dCb = dC + (size_t)b * ln;
                     for (size_t i = 0; i < ln; ++i) {
-                        dBb[i] += dBp[i];
-                        dCb[i] += dCp[i];
+                        if (!b_fixed)
+                            dBb[i] += dBp[i];
+                        if (!c_fixed)
+                            dCb[i] += dCp[i];
                     }
                 }
 #pragma omp barrier
@@ -303,7 +320,7 @@ int ss_oracle_step(int nb, int nd, int nn, double *h,
                    const double *u_t, const double *delta_t, const double *z_t,
                    const double *B_t, const double *C_t, const double *A,
                    const double *Dskip, const double *bias,
-                   int softplus, int exact_zoh, double *out_t)
+                   int softplus, int exact_zoh, int b_fixed, int c_fixed, double *out_t)
 {
     if (nb <= 0 || nd <= 0 || nn <= 0)
         return -1;
@@ -316,9 +333,9 @@ int ss_oracle_step(int nb, int nd, int nn, double *h,
             for (int n = 0; n < nn; ++n) {
                 double a = A[(long)d * nn + n];
                 double hn = exp(dt * a) * h[row * nn + n] +
-                            phi_f64(exact_zoh, dt, a) * B_t[(long)b * nn + n] * u_t[row];
+                            phi_f64(exact_zoh, dt, a) * B_t[bc_index(b_fixed, b, d, n, 0, nn, 1)] * u_t[row];
                 h[row * nn + n] = hn;
-                y += C_t[(long)b * nn + n] * hn;
+                y += C_t[bc_index(c_fixed, b, d, n, 0, nn, 1)] * hn;
             }
             if (Dskip)
                 y += Dskip[d] * u_t[row];
