@@ -27,6 +27,7 @@
  *      u, delta, z, out, dout, du, ddelta, dz : (B, D, L)  in io_dtype
  *      Bmat, Cmat                             : (B, N, L)  in io_dtype
  *      dB, dC                                 : (B, N, L)  float32
+ *        (with SS_B_FIXED / SS_C_FIXED: Bmat, dB / Cmat, dC are (D, N) float32, like A)
  *      A, dA                                  : (D, N)     float32
  *      Dskip, delta_bias, dD, ddelta_bias     : (D)        float32
  *      h0, h_last, dh_last, dh0               : (B, D, N)  float32
@@ -65,7 +66,10 @@ enum {
     SS_HAS_H0         = 16u, /* h0 is given (else the scan starts from the zero state)     */
     SS_WRITE_H_LAST   = 32u, /* h_last is written                                          */
     SS_SAVE_FOR_BWD   = 64u, /* forward: leave state checkpoints in `workspace`            */
-    SS_EXACT_ZOH_B    = 128u /* exact zero-order-hold B-bar of Eq. 4 instead of dt * B     */
+    SS_EXACT_ZOH_B    = 128u, /* exact zero-order-hold B-bar of Eq. 4 instead of dt * B    */
+    SS_B_FIXED        = 256u, /* Bmat is the time-invariant (D,N) float32 parameter of
+                                 Algorithm 1 (the non-selective arm of Table 7); dB likewise */
+    SS_C_FIXED        = 512u  /* the same for Cmat / dC                                     */
 };
 
 enum {
@@ -134,10 +138,10 @@ typedef struct {
     int32_t batch, dim, dstate;       /* B, D, N                                           */
     int32_t io_dtype;                 /* of u_t, delta_t, z_t, B_t, C_t, out_t             */
     uint32_t flags;                   /* SS_DELTA_SOFTPLUS, SS_HAS_DELTA_BIAS, SS_HAS_D,
-                                         SS_HAS_Z, SS_EXACT_ZOH_B                          */
+                                         SS_HAS_Z, SS_EXACT_ZOH_B, SS_B_FIXED, SS_C_FIXED  */
     float *h;                         /* (B,D,N) float32 state, updated IN PLACE           */
     const void *u_t, *delta_t, *z_t;  /* (B,D)                                             */
-    const void *B_t, *C_t;            /* (B,N)                                             */
+    const void *B_t, *C_t;            /* (B,N); (D,N) float32 with SS_B_FIXED / SS_C_FIXED */
     const float *A, *Dskip, *delta_bias;
     void *out_t;                      /* (B,D)                                             */
 } ss_step_params;

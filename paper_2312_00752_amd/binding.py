@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libss_scan.so")
 SS_F32, SS_BF16 = 0, 1
 SS_DELTA_SOFTPLUS, SS_HAS_DELTA_BIAS, SS_HAS_D, SS_HAS_Z = 1, 2, 4, 8
 SS_HAS_H0, SS_WRITE_H_LAST, SS_SAVE_FOR_BWD, SS_EXACT_ZOH_B = 16, 32, 64, 128
+SS_B_FIXED, SS_C_FIXED = 256, 512
 SS_OK, SS_ERR_NULL, SS_ERR_SHAPE, SS_ERR_UNSUPPORTED = 0, -1, -2, -3
 SS_ERR_ALIGN, SS_ERR_WORKSPACE, SS_ERR_LAUNCH = -4, -5, -6
 SS_MAX_DSTATE = 16
@@ -194,8 +195,17 @@ def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplu
     flags = 0
     p.u = _ptr(u, io, (nb, nd, nl), "u")
     p.delta = _ptr(delta, io, (nb, nd, nl), "delta")
-    p.Bmat = _ptr(Bmat, io, (nb, nn, nl), "Bmat")
-    p.Cmat = _ptr(Cmat, io, (nb, nn, nl), "Cmat")
+    # a 2-D float32 (D,N) tensor is the time-invariant form of B / C (Algorithm 1)
+    if Bmat.dim() == 2:
+        p.Bmat = _ptr(Bmat, f32, (nd, nn), "Bmat")
+        flags |= SS_B_FIXED
+    else:
+        p.Bmat = _ptr(Bmat, io, (nb, nn, nl), "Bmat")
+    if Cmat.dim() == 2:
+        p.Cmat = _ptr(Cmat, f32, (nd, nn), "Cmat")
+        flags |= SS_C_FIXED
+    else:
+        p.Cmat = _ptr(Cmat, io, (nb, nn, nl), "Cmat")
     p.A = _ptr(A, f32, (nd, nn), "A")
     if z is not None:
         p.z = _ptr(z, io, (nb, nd, nl), "z")
@@ -217,12 +227,13 @@ def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplu
     return p
 
 
-def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True, io_dtype=SS_F32, has_z=True):
-    """Workspace size; the defaults (float32 I/O, gate present) give an upper bound."""
+def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True, io_dtype=SS_F32, has_z=True,
+                       b_fixed=False, c_fixed=False):
+    """Workspace size; the defaults (float32 I/O, gate present) give an upper bound for selective B, C."""
     p = FwdParams()
     p.batch, p.dim, p.seqlen, p.dstate = batch, dim, seqlen, dstate
     p.io_dtype = io_dtype
-    p.flags = SS_HAS_Z if has_z else 0
+    p.flags = (SS_HAS_Z if has_z else 0) | (SS_B_FIXED if b_fixed else 0) | (SS_C_FIXED if c_fixed else 0)
     return int(lib().ss_workspace_bytes(ctypes.byref(p), int(bool(for_backward))))
 
 
@@ -272,8 +283,8 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
     dev = u.device
     g = {"du": torch.empty_like(u), "ddelta": torch.empty_like(u),
          "dz": torch.empty_like(u) if z is not None else None,
-         "dB": torch.empty((nb, nn, nl), dtype=f32, device=dev),
-         "dC": torch.empty((nb, nn, nl), dtype=f32, device=dev),
+         "dB": torch.empty(tuple(Bmat.shape), dtype=f32, device=dev),
+         "dC": torch.empty(tuple(Cmat.shape), dtype=f32, device=dev),
          "dA": torch.empty((nd, nn), dtype=f32, device=dev),
          "dD": torch.empty((nd,), dtype=f32, device=dev) if Dskip is not None else None,
          "ddelta_bias": torch.empty((nd,), dtype=f32, device=dev) if delta_bias is not None else None,
@@ -289,8 +300,9 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
 
 
 def ss_step(h, u_t, delta_t, A, B_t, C_t, Dskip=None, z_t=None, delta_bias=None,
-            delta_softplus=False, out_t=None, exact_zoh=False, stream=None):
-    """Enqueue one recurrent step; ``h`` (B,D,N) float32 is updated in place.  Returns out_t."""
+            delta_softplus=False, out_t=None, exact_zoh=False, b_fixed=False, c_fixed=False, stream=None):
+    """Enqueue one recurrent step; ``h`` (B,D,N) float32 is updated in place.  Returns out_t.
+    With ``b_fixed`` / ``c_fixed`` B_t / C_t is the time-invariant (D,N) float32 parameter."""
     import torch
     f32 = torch.float32
     nb, nd, nn = h.shape
@@ -299,11 +311,12 @@ def ss_step(h, u_t, delta_t, A, B_t, C_t, Dskip=None, z_t=None, delta_bias=None,
     p.batch, p.dim, p.dstate = nb, nd, nn
     p.io_dtype = _io_code(u_t)
     flags = (SS_DELTA_SOFTPLUS if delta_softplus else 0) | (SS_EXACT_ZOH_B if exact_zoh else 0)
+    flags |= (SS_B_FIXED if b_fixed else 0) | (SS_C_FIXED if c_fixed else 0)
     p.h = _ptr(h, f32, (nb, nd, nn), "h")
     p.u_t = _ptr(u_t, io, (nb, nd), "u_t")
     p.delta_t = _ptr(delta_t, io, (nb, nd), "delta_t")
-    p.B_t = _ptr(B_t, io, (nb, nn), "B_t")
-    p.C_t = _ptr(C_t, io, (nb, nn), "C_t")
+    p.B_t = _ptr(B_t, f32, (nd, nn), "B_t") if b_fixed else _ptr(B_t, io, (nb, nn), "B_t")
+    p.C_t = _ptr(C_t, f32, (nd, nn), "C_t") if c_fixed else _ptr(C_t, io, (nb, nn), "C_t")
     p.A = _ptr(A, f32, (nd, nn), "A")
     if z_t is not None:
         p.z_t = _ptr(z_t, io, (nb, nd), "z_t")

@@ -8,8 +8,10 @@
 namespace {
 
 constexpr uint32_t kFwdFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z |
-                               SS_HAS_H0 | SS_WRITE_H_LAST | SS_SAVE_FOR_BWD | SS_EXACT_ZOH_B;
-constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z | SS_EXACT_ZOH_B;
+                               SS_HAS_H0 | SS_WRITE_H_LAST | SS_SAVE_FOR_BWD | SS_EXACT_ZOH_B |
+                               SS_B_FIXED | SS_C_FIXED;
+constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z | SS_EXACT_ZOH_B |
+                                SS_B_FIXED | SS_C_FIXED;
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -22,11 +24,12 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct SegPlan {
     int nseg, seg_len;
 };
-SegPlan plan_segments(int B, int D, int L)
+SegPlan plan_segments(int B, int D, int L, uint32_t flags)
 {
     const long wgs = (long)B * ((D + 63) / 64);
     SegPlan s{1, (L + 31) / 32 * 32};
     if (s.seg_len == 0) s.seg_len = 32;
+    if (flags & (SS_B_FIXED | SS_C_FIXED)) return s;   // the time-invariant variants are not split
     if (wgs > 256 || L < 2048) return s;               // more than one workgroup per compute unit already
     long want = (512 + wgs - 1) / wgs;                 // about two workgroups per compute unit
     want = want < L / 512 ? want : L / 512;            // segments of at least 512 steps
@@ -44,8 +47,9 @@ SegPlan plan_segments(int B, int D, int L)
 //   with backward: [float checkpoints nck*B*D*16][io pre-gate y B*D*L, only with a gate]
 //                  [seg_h][seg_sumdt][float seg_g nseg*B*D*16]                 (only when split)
 //                  [float dA partials nseg*B*D*16][float dD partials nseg*B*D][float dbias partials nseg*B*D]
+//                  [float dB partials B*D*16][float dC partials B*D*16]    (only for a time-invariant B / C)
 struct WsLayout {
-    size_t ckpt_off, y_off, segh_off, segdt_off, segg_off, dA_off, dD_off, db_off, total;
+    size_t ckpt_off, y_off, segh_off, segdt_off, segg_off, dA_off, dD_off, db_off, dBf_off, dCf_off, total;
     SegPlan plan;
 };
 WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
@@ -54,7 +58,7 @@ WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
     const size_t rows = (size_t)p->batch * p->dim;
     const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
     WsLayout w{};
-    w.plan = plan_segments(p->batch, p->dim, p->seqlen);
+    w.plan = plan_segments(p->batch, p->dim, p->seqlen, p->flags);
     const size_t ns = (size_t)w.plan.nseg, split = ns > 1 ? 1 : 0;
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off += round_up(bytes, 256); return at; };
@@ -66,6 +70,9 @@ WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
     w.dA_off = take(for_bwd ? ns * rows * 16 * sizeof(float) : 0);
     w.dD_off = take(for_bwd ? ns * rows * sizeof(float) : 0);
     w.db_off = take(for_bwd ? ns * rows * sizeof(float) : 0);
+    // per-batch partial sums of the gradient of a time-invariant B / C
+    w.dBf_off = take(for_bwd && (p->flags & SS_B_FIXED) ? rows * 16 * sizeof(float) : 0);
+    w.dCf_off = take(for_bwd && (p->flags & SS_C_FIXED) ? rows * 16 * sizeof(float) : 0);
     w.total = off;
     return w;
 }
@@ -92,7 +99,8 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
     // B and C are read 16 bytes at a time only when every row is a whole number of such pieces;
     // the layer passes rows of a larger matrix here, which then are merely element-aligned
     const size_t bc_align = (p->seqlen % 8 == 0 || bc_dense) ? 16 : (p->io_dtype == SS_BF16 ? 2 : 4);
-    if ((p->Bmat && !aligned(p->Bmat, bc_align)) || (p->Cmat && !aligned(p->Cmat, bc_align))) return SS_ERR_ALIGN;
+    if (p->Bmat && !aligned(p->Bmat, (p->flags & SS_B_FIXED) ? 4 : bc_align)) return SS_ERR_ALIGN;
+    if (p->Cmat && !aligned(p->Cmat, (p->flags & SS_C_FIXED) ? 4 : bc_align)) return SS_ERR_ALIGN;
     const void* f32[] = {p->A, p->Dskip, p->delta_bias, p->h0, for_bwd ? nullptr : p->h_last};
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
@@ -166,6 +174,7 @@ int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
     const bool empty = f->seqlen == 0;
     if (!p->dA) return SS_ERR_NULL;
     if (!empty && (!p->dout || !p->du || !p->ddelta || !p->dB || !p->dC)) return SS_ERR_NULL;
+    if (((f->flags & SS_B_FIXED) && !p->dB) || ((f->flags & SS_C_FIXED) && !p->dC)) return SS_ERR_NULL;
     if (!empty && (f->flags & SS_HAS_Z) && !p->dz) return SS_ERR_NULL;
     if ((f->flags & SS_HAS_D) && !p->dD) return SS_ERR_NULL;
     if ((f->flags & SS_HAS_DELTA_BIAS) && !p->ddelta_bias) return SS_ERR_NULL;
@@ -194,6 +203,8 @@ int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
     a.du = p->du; a.ddelta = p->ddelta; a.dz = (f->flags & SS_HAS_Z) ? p->dz : nullptr;
     a.dB = p->dB; a.dC = p->dC;
     a.dA_part = reinterpret_cast<float*>(ws + w.dA_off);
+    a.dBf_part = reinterpret_cast<float*>(ws + w.dBf_off);
+    a.dCf_part = reinterpret_cast<float*>(ws + w.dCf_off);
     a.dD_part = reinterpret_cast<float*>(ws + w.dD_off);
     a.db_part = reinterpret_cast<float*>(ws + w.db_off);
     a.dh0 = p->dh0;
@@ -217,9 +228,11 @@ int step_strided(const ss_step_params* p, long bc_stride, void* stream)
     if ((p->flags & SS_HAS_DELTA_BIAS) && !p->delta_bias) return SS_ERR_NULL;
     if (!aligned(p->h, 16)) return SS_ERR_ALIGN;
     const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
-    const void* io[] = {p->u_t, p->delta_t, p->z_t, p->B_t, p->C_t, p->out_t};
+    const void* io[] = {p->u_t, p->delta_t, p->z_t, p->out_t};
     for (const void* q : io)
         if (q && !aligned(q, esz)) return SS_ERR_ALIGN;
+    if (!aligned(p->B_t, (p->flags & SS_B_FIXED) ? 4 : esz) || !aligned(p->C_t, (p->flags & SS_C_FIXED) ? 4 : esz))
+        return SS_ERR_ALIGN;
     const void* f32[] = {p->A, p->Dskip, p->delta_bias};
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;

@@ -87,7 +87,10 @@ __device__ __forceinline__ void reduce_take(float (*red)[RED_PITCH], float* acc,
 // q = g B u the formulas above become  ddt = sum_n abar (g h_prev A + q),
 // dA_n += g abar h_prev dt + q dphi/dA,  du = sum_n g phi B + Dskip dy,  dB = sum_d g phi u;
 // the LDS tile that otherwise carries dt*u then carries u.
-template <typename T, bool VEC, bool FULLN, bool ZOH>
+// BCFIX (bit 0: B, bit 1: C): the operand is the time-invariant (D,N) parameter; it is held in
+// registers like A and its gradient, a sum over batch and time, is accumulated per lane like
+// dA instead of being reduced over the rows of the workgroup.
+template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX = 0>
 __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -129,7 +132,9 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     const bool s_ok = d0 + lane < f.D;
     const int sd = s_ok ? d0 + lane : f.D - 1;
     const long srow = (long)b * f.D + sd;
+    constexpr bool BFIX = BCFIX & 1, CFIX = BCFIX & 2;
     float A2[STATES_PER_LANE], An[STATES_PER_LANE], invA[STATES_PER_LANE], ag[STATES_PER_LANE], dA[STATES_PER_LANE];
+    float Bf[STATES_PER_LANE], Cf[STATES_PER_LANE], dBf[STATES_PER_LANE], dCf[STATES_PER_LANE];
     const T* __restrict__ gB[STATES_PER_LANE];
     const T* __restrict__ gC[STATES_PER_LANE];
     bool n_ok[STATES_PER_LANE];
@@ -144,9 +149,15 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         if (seg == f.nseg - 1) ag[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;  // abar_L g_L := dh_last
         else ag[k] = a.seg_g[(seg_rows + srow) * NPAD + w * STATES_PER_LANE + k];
         dA[k] = 0.0f;
-        gB[k] = static_cast<const T*>(f.Bm) + (long)b * f.bc_bstride + (long)nc * L;
-        gC[k] = static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride + (long)nc * L;
+        gB[k] = BFIX ? nullptr : static_cast<const T*>(f.Bm) + (long)b * f.bc_bstride + (long)nc * L;
+        gC[k] = CFIX ? nullptr : static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride + (long)nc * L;
+        Bf[k] = (BFIX && n_ok[k]) ? static_cast<const float*>(f.Bm)[(long)sd * N + nc] : 0.0f;
+        Cf[k] = (CFIX && n_ok[k]) ? static_cast<const float*>(f.Cm)[(long)sd * N + nc] : 0.0f;
+        dBf[k] = 0.0f;
+        dCf[k] = 0.0f;
     }
+    const void* const touchB = BFIX ? f.Cm : f.Bm;   // the selective operands, if any
+    const void* const touchC = CFIX ? f.Bm : f.Cm;
     float* const dbc = &sm.dbc[w][0][0][0];
     float (*const red)[RED_PITCH] = sm.red[w];
 
@@ -172,12 +183,13 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         }
     };
     issue_group((nblocks - 1) / LG);
-    float touched = touch_bc<T>(f.Bm, f.Cm, b, f.bc_bstride, N, L, w, lane, (nblocks - 1) * BT);
+    float touched = 0.0f;
+    if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, f.bc_bstride, N, L, w, lane, (nblocks - 1) * BT);
 
     for (int blk = nblocks - 1; blk >= blk_begin; --blk) {
         const int tc = blk * BT;
         consume_touch(touched);
-        touched = touch_bc<T>(f.Bm, f.Cm, b, f.bc_bstride, N, L, w, lane, (blk - 1) * BT);
+        if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, f.bc_bstride, N, L, w, lane, (blk - 1) * BT);
         const int t0 = tc + pq * BSL;
         const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;
         // the state entering this block, left by the forward pass
@@ -234,7 +246,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                 bc_group<T> Bg[STATES_PER_LANE];
 #pragma unroll
                 for (int k = 0; k < STATES_PER_LANE; ++k)
-                    Bg[k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
+                    if (!BFIX) Bg[k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
                 const int tl = g * GROUP_T;
                 const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[lane][tl]);
                 const float4 du4 = *reinterpret_cast<const float4*>(&sm.du[lane][tl]);
@@ -246,18 +258,21 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 #pragma unroll
                     for (int k = 0; k < STATES_PER_LANE; ++k) {
                         const float abar = exp2_fast(dt * A2[k]);
-                        float bu = du * Bg[k].get(j);
+                        float bu = du * (BFIX ? Bf[k] : Bg[k].get(j));
                         if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
                         h[k] = fmaf(abar, h[k], bu);
                         as[tl + j][k] = abar;
                         hs[tl + j][k] = h[k];
-                        dCv[j * STATES_PER_LANE + k] = dy * h[k];
+                        if (CFIX) dCf[k] = fmaf(dy, h[k], dCf[k]);
+                        else dCv[j * STATES_PER_LANE + k] = dy * h[k];
                     }
                 }
-                if (g > 0) reduce_take(red, dbc + STATES_PER_LANE * BT + tl - GROUP_T, lane);  // previous group
-                reduce_put(dCv, red, lane);
+                if (!CFIX) {
+                    if (g > 0) reduce_take(red, dbc + STATES_PER_LANE * BT + tl - GROUP_T, lane);  // previous group
+                    reduce_put(dCv, red, lane);
+                }
             }
-            reduce_take(red, dbc + STATES_PER_LANE * BT + (NG - 1) * GROUP_T, lane);
+            if (!CFIX) reduce_take(red, dbc + STATES_PER_LANE * BT + (NG - 1) * GROUP_T, lane);
         }
         // ---- B2: adjoint recurrence, last step of the block first --------------------------
 #pragma unroll
@@ -265,8 +280,8 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
             bc_group<T> Bg[STATES_PER_LANE], Cg[STATES_PER_LANE];
 #pragma unroll
             for (int k = 0; k < STATES_PER_LANE; ++k) {
-                Bg[k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
-                Cg[k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+                if (!BFIX) Bg[k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
+                if (!CFIX) Cg[k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
             }
             const int tl = g * GROUP_T;
             const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[lane][tl]);
@@ -281,31 +296,36 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                 sb[j] = 0.0f;
 #pragma unroll
                 for (int k = 0; k < STATES_PER_LANE; ++k) {
-                    const float gk = fmaf(Cg[k].get(j), dy, ag[k]);   // gradient reaching h_t
+                    const float Bv = BFIX ? Bf[k] : Bg[k].get(j);
+                    const float gk = fmaf(CFIX ? Cf[k] : Cg[k].get(j), dy, ag[k]);   // gradient reaching h_t
                     ag[k] = as[t][k] * gk;                             // flows on to h_{t-1}
                     const float hprev = (t > 0) ? hs[t > 0 ? t - 1 : 0][k] : hck[k];
                     const float gh = ag[k] * hprev;                    // g abar h_{t-1}
                     if (ZOH) {
                         const zoh_terms z = zoh_phi(dt, An[k], invA[k], as[t][k], true);
-                        const float gB = gk * Bg[k].get(j), q = gB * du;   // du holds u here
+                        const float gB = gk * Bv, q = gB * du;   // du holds u here
                         dA[k] = fmaf(gh, dt, fmaf(q, z.dphi_dA, dA[k]));
                         dd[j] = fmaf(gh, An[k], fmaf(q, as[t][k], dd[j]));
                         sb[j] = fmaf(gB, z.phi, sb[j]);
-                        dBv[j * STATES_PER_LANE + k] = gk * z.phi * du;
+                        if (BFIX) dBf[k] = fmaf(gk * z.phi, du, dBf[k]);
+                        else dBv[j * STATES_PER_LANE + k] = gk * z.phi * du;
                     } else {
                         dA[k] = fmaf(gh, dt, dA[k]);
                         dd[j] = fmaf(gh, A2[k], dd[j]);
-                        sb[j] = fmaf(gk, Bg[k].get(j), sb[j]);
-                        dBv[j * STATES_PER_LANE + k] = gk * du;
+                        sb[j] = fmaf(gk, Bv, sb[j]);
+                        if (BFIX) dBf[k] = fmaf(gk, du, dBf[k]);
+                        else dBv[j * STATES_PER_LANE + k] = gk * du;
                     }
                 }
             }
             *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
             *reinterpret_cast<float4*>(&sm.psb[w][lane][tl]) = make_float4(sb[0], sb[1], sb[2], sb[3]);
-            if (g < NG - 1) reduce_take(red, dbc + tl + GROUP_T, lane);  // previous (later) group
-            reduce_put(dBv, red, lane);
+            if (!BFIX) {
+                if (g < NG - 1) reduce_take(red, dbc + tl + GROUP_T, lane);  // previous (later) group
+                reduce_put(dBv, red, lane);
+            }
         }
-        reduce_take(red, dbc, lane);
+        if (!BFIX) reduce_take(red, dbc, lane);
         // ---- flush this wave's dB/dC of the block to global memory -------------------------
         wave_lds_fence();
 #pragma unroll
@@ -313,6 +333,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
             const int idx = i * WAVE + lane;
             const int which = idx / (STATES_PER_LANE * BT), k = (idx / BT) % STATES_PER_LANE, t = idx % BT;
             const int n = w * STATES_PER_LANE + k;
+            if ((which ? CFIX : BFIX)) continue;   // that gradient is not per step
             if (n < N && tc + t < L) {
                 float* dst = (which ? a.dC : a.dB) + ((long)b * N + n) * L + tc + t;
                 atomicAdd(dst, dbc[idx]);
@@ -353,6 +374,8 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     if (s_ok) {
         float4* pa = reinterpret_cast<float4*>(a.dA_part + (seg_rows + srow) * NPAD) + w;
         *pa = make_float4(dA[0], dA[1], dA[2], dA[3]);
+        if (BFIX) *(reinterpret_cast<float4*>(a.dBf_part + srow * NPAD) + w) = make_float4(dBf[0], dBf[1], dBf[2], dBf[3]);
+        if (CFIX) *(reinterpret_cast<float4*>(a.dCf_part + srow * NPAD) + w) = make_float4(dCf[0], dCf[1], dCf[2], dCf[3]);
         if (a.dh0 && seg == 0) {
 #pragma unroll
             for (int k = 0; k < STATES_PER_LANE; ++k)
@@ -510,11 +533,15 @@ __global__ void carry_bwd_kernel(const BwdArgs a)
     }
 }
 
-// dB and dC are accumulated atomically by the scan kernel and must start at zero.
+// dB and dC are accumulated atomically by the scan kernel and must start at zero (a null
+// pointer: that gradient belongs to a time-invariant operand and is written elsewhere).
 __global__ void zero_kernel(float* __restrict__ p0, float* __restrict__ p1, long n)
 {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) { p0[i] = 0.0f; p1[i] = 0.0f; }
+    if (i < n) {
+        if (p0) p0[i] = 0.0f;
+        if (p1) p1[i] = 0.0f;
+    }
 }
 
 // Sum the per-batch partials: dA (D,N), dD (D), dbias (D).  With L == 0 (no partials
@@ -524,16 +551,21 @@ __global__ void finalize_kernel(const BwdArgs a, int have_partials)
     const int d = blockIdx.x * blockDim.x / NPAD + threadIdx.x / NPAD;
     const int n = threadIdx.x % NPAD;
     if (d >= a.f.D) return;
-    float sA = 0.0f, sD = 0.0f, sb = 0.0f;
+    float sA = 0.0f, sD = 0.0f, sb = 0.0f, sB = 0.0f, sC = 0.0f;
+    const bool bfix = a.f.flags & F_B_FIXED, cfix = a.f.flags & F_C_FIXED;
     if (have_partials) {
 #pragma unroll 8
         for (int b = 0; b < a.f.B * a.f.nseg; ++b) {  // per segment and batch entry
             const long row = (long)b * a.f.D + d;
             sA += a.dA_part[row * NPAD + n];
+            if (bfix) sB += a.dBf_part[row * NPAD + n];   // time-invariant B / C are never split: nseg == 1
+            if (cfix) sC += a.dCf_part[row * NPAD + n];
             if (n == 0) { sD += a.dD_part[row]; sb += a.db_part[row]; }
         }
     }
     if (n < a.f.N) a.dA[(long)d * a.f.N + n] = sA;
+    if (n < a.f.N && bfix) a.dB[(long)d * a.f.N + n] = sB;
+    if (n < a.f.N && cfix) a.dC[(long)d * a.f.N + n] = sC;
     if (n == 0) {
         if (a.dD) a.dD[d] = sD;
         if (a.dbias) a.dbias[d] = sb;
@@ -546,9 +578,28 @@ __global__ void copy_dh_kernel(const float* __restrict__ src, float* __restrict_
     if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
+template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX>
+static int launch_scan_bwd_fixed(const BwdArgs& a, dim3 grid, hipStream_t stream)
+{
+    static bool configured = false;  // raising the dynamic LDS limit is needed once per kernel
+    auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH, BCFIX>;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)sizeof(BwdSmem)) != hipSuccess)
+            return -1;
+        configured = true;
+    }
+    kern<<<dim3(grid.x, 1u), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH>
 static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
+    const int bcfix = ((a.f.flags & F_B_FIXED) ? 1 : 0) | ((a.f.flags & F_C_FIXED) ? 2 : 0);
+    if (bcfix == 1) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 1>(a, grid, stream);
+    if (bcfix == 2) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 2>(a, grid, stream);
+    if (bcfix == 3) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 3>(a, grid, stream);
     static bool configured = false;  // raising the dynamic LDS limit is needed once per kernel
     auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH>;
     if (!configured) {
@@ -579,7 +630,9 @@ int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream)
         return hipGetLastError() == hipSuccess ? 0 : -1;
     }
     const long nbc = (long)f.B * f.N * f.L;
-    zero_kernel<<<dim3((unsigned)((nbc + 255) / 256)), dim3(256), 0, stream>>>(a.dB, a.dC, nbc);
+    float* const zB = (f.flags & F_B_FIXED) ? nullptr : a.dB;
+    float* const zC = (f.flags & F_C_FIXED) ? nullptr : a.dC;
+    if (zB || zC) zero_kernel<<<dim3((unsigned)((nbc + 255) / 256)), dim3(256), 0, stream>>>(zB, zC, nbc);
     const int groups = (f.D + ROWS - 1) / ROWS;
     const dim3 grid((unsigned)(f.B * groups));
     const bool fulln = f.N == NPAD;

@@ -22,7 +22,9 @@ namespace ss {
 // carry_fwd_kernel has turned those into each segment's incoming state, with AGG = false.
 // ZOH selects the exact zero-order-hold B-bar of Eq. 4: the LDS tile that otherwise carries
 // dt*u then carries u, and each state multiplies it by phi(dt, A) = (abar - 1) / A.
-template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH>
+// BCFIX: bit 0 / bit 1 set when B / C is the time-invariant (D,N) float32 parameter of
+// Algorithm 1 instead of the selective (B,N,L) tensor: it then sits in registers like A.
+template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -58,7 +60,9 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     const bool s_ok = d0 + lane < a.D;
     const int sd = s_ok ? d0 + lane : a.D - 1;
     const long srow = (long)b * a.D + sd;
+    constexpr bool BFIX = BCFIX & 1, CFIX = BCFIX & 2;
     float A2[STATES_PER_LANE], An[STATES_PER_LANE], invA[STATES_PER_LANE], h[STATES_PER_LANE];
+    float Bf[STATES_PER_LANE], Cf[STATES_PER_LANE];
     const T* __restrict__ gB[STATES_PER_LANE];
     const T* __restrict__ gC[STATES_PER_LANE];
     bool n_ok[STATES_PER_LANE];
@@ -72,9 +76,14 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         invA[k] = An[k] != 0.0f ? 1.0f / An[k] : 0.0f;
         if (seg == 0) h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * N + nc] : 0.0f;
         else h[k] = AGG ? 0.0f : a.seg_h[((long)seg * a.B * a.D + srow) * NPAD + w * STATES_PER_LANE + k];
-        gB[k] = static_cast<const T*>(a.Bm) + (long)b * a.bc_bstride + (long)nc * L;
-        gC[k] = static_cast<const T*>(a.Cm) + (long)b * a.bc_bstride + (long)nc * L;
+        gB[k] = BFIX ? nullptr : static_cast<const T*>(a.Bm) + (long)b * a.bc_bstride + (long)nc * L;
+        gC[k] = CFIX ? nullptr : static_cast<const T*>(a.Cm) + (long)b * a.bc_bstride + (long)nc * L;
+        Bf[k] = (BFIX && n_ok[k]) ? static_cast<const float*>(a.Bm)[(long)sd * N + nc] : 0.0f;
+        Cf[k] = (CFIX && n_ok[k]) ? static_cast<const float*>(a.Cm)[(long)sd * N + nc] : 0.0f;
     }
+    // the selective operands (if any) whose cache lines are touched one chunk ahead
+    const void* const touchB = BFIX ? a.Cm : a.Bm;
+    const void* const touchC = CFIX ? a.Bm : a.Cm;
     float sum_dt = 0.0f;  // AGG: this thread's share of the segment's sum of step sizes
 
     typename io8<T>::raw ru, rd, rz;
@@ -86,12 +95,13 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
     };
     issue_loads(c_begin);
-    float touched = touch_bc<T>(a.Bm, a.Cm, b, a.bc_bstride, N, L, w, lane, c_begin * CHUNK_T);
+    float touched = 0.0f;
+    if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, a.bc_bstride, N, L, w, lane, c_begin * CHUNK_T);
 
     for (int c = c_begin; c < c_end; ++c) {
         float u8[SLICE], z8[SLICE], v8[SLICE];
         consume_touch(touched);
-        touched = touch_bc<T>(a.Bm, a.Cm, b, a.bc_bstride, N, L, w, lane, (c + 1) * CHUNK_T);
+        if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, a.bc_bstride, N, L, w, lane, (c + 1) * CHUNK_T);
         const int tc = c * CHUNK_T;
         const int t0 = tc + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);
@@ -133,8 +143,8 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         auto fetch_bc = [&](int g, int slot) {
 #pragma unroll
             for (int k = 0; k < STATES_PER_LANE; ++k) {
-                Bg[slot][k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
-                Cg[slot][k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+                if (!BFIX) Bg[slot][k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
+                if (!CFIX && !AGG) Cg[slot][k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
             }
         };
         fetch_bc(0, 0);
@@ -154,10 +164,10 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 #pragma unroll
                 for (int k = 0; k < STATES_PER_LANE; ++k) {
                     const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
-                    float bu = du * Bg[cur][k].get(j);
+                    float bu = du * (BFIX ? Bf[k] : Bg[cur][k].get(j));
                     if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
                     h[k] = fmaf(abar, h[k], bu);                                 // Eq. 2a
-                    if (!AGG) y = fmaf(Cg[cur][k].get(j), h[k], y);              // Eq. 2b
+                    if (!AGG) y = fmaf(CFIX ? Cf[k] : Cg[cur][k].get(j), h[k], y);  // Eq. 2b
                 }
                 yp[j] = y;
             }
@@ -258,6 +268,8 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     const T* z_t = static_cast<const T*>(a.z_t);
     const T* B_t = static_cast<const T*>(a.B_t);
     const T* C_t = static_cast<const T*>(a.C_t);
+    // time-invariant B / C are (D,N) float32 parameters; the launcher sends them down the generic path
+    const bool bfix = !FULLN && (a.flags & F_B_FIXED), cfix = !FULLN && (a.flags & F_C_FIXED);
     auto ld = [](const T* p, long i) -> float {
         if constexpr (sizeof(T) == 2) return bf16_to_f32(p[i]); else return p[i];
     };
@@ -287,8 +299,8 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
             const bool ok = n < N;
             hv[k] = ok ? hp[k] : 0.0f;
             Av[k] = ok ? a.A[(long)d * N + n] : 0.0f;
-            Bv[k] = ok ? ld(B_t, (long)b * a.bc_stride + n) : 0.0f;
-            Cv[k] = ok ? ld(C_t, (long)b * a.bc_stride + n) : 0.0f;
+            Bv[k] = !ok ? 0.0f : bfix ? static_cast<const float*>(a.B_t)[(long)d * N + n] : ld(B_t, (long)b * a.bc_stride + n);
+            Cv[k] = !ok ? 0.0f : cfix ? static_cast<const float*>(a.C_t)[(long)d * N + n] : ld(C_t, (long)b * a.bc_stride + n);
         }
     }
     const float u = ld(u_t, row);
@@ -336,11 +348,23 @@ __global__ void copy_state_kernel(const float* __restrict__ src, float* __restri
     if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
+template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX>
+static void launch_fwd_fixed(const FwdArgs& a, hipStream_t stream)
+{
+    const int groups = (a.D + ROWS - 1) / ROWS;
+    scan_fwd_kernel<T, VEC, FULLN, false, ZOH, BCFIX><<<dim3((unsigned)(a.B * groups), 1u), dim3(THREADS), 0, stream>>>(a);
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH>
 static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
 {
     const int groups = (a.D + ROWS - 1) / ROWS;
     const dim3 block(THREADS);
+    // time-invariant B and/or C: never split (the planner keeps nseg == 1 for them)
+    const int bcfix = ((a.flags & F_B_FIXED) ? 1 : 0) | ((a.flags & F_C_FIXED) ? 2 : 0);
+    if (bcfix == 1) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 1>(a, stream);
+    if (bcfix == 2) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 2>(a, stream);
+    if (bcfix == 3) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 3>(a, stream);
     if (a.nseg > 1) {
         scan_fwd_kernel<T, VEC, FULLN, true, ZOH><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
         const long n = (long)a.B * a.D * NPAD;
@@ -388,7 +412,7 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
     // which N == 16 and the element-aligned base pointers checked by the caller give only
     // when the bases themselves are that aligned
     const size_t va = io_dtype == 0 ? 16 : 8;
-    const bool vec = a.N == NPAD && (a.bc_stride * (io_dtype == 0 ? 4 : 2)) % va == 0 &&
+    const bool vec = a.N == NPAD && !(a.flags & (F_B_FIXED | F_C_FIXED)) && (a.bc_stride * (io_dtype == 0 ? 4 : 2)) % va == 0 &&
                      reinterpret_cast<uintptr_t>(a.B_t) % va == 0 &&
                      reinterpret_cast<uintptr_t>(a.C_t) % va == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
     const bool zoh = a.flags & F_EXACT_ZOH_B;

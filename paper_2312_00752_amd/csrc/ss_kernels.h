@@ -14,6 +14,8 @@ enum : uint32_t {
     F_HAS_Z = SS_HAS_Z,
     F_HAS_H0 = SS_HAS_H0,
     F_EXACT_ZOH_B = SS_EXACT_ZOH_B,
+    F_B_FIXED = SS_B_FIXED,
+    F_C_FIXED = SS_C_FIXED,
 };
 
 struct FwdArgs {
@@ -39,7 +41,9 @@ struct BwdArgs {
     const void* dout;
     const float* dh_last;
     void *du, *ddelta, *dz;
-    float *dB, *dC;             // (B,N,L), zeroed before the scan kernel, atomically accumulated
+    float *dB, *dC;             // (B,N,L), zeroed before the scan kernel, atomically accumulated;
+                                // (D,N), written by the reduction kernel, for a time-invariant B / C
+    float *dBf_part, *dCf_part; // [B][D][16] per-batch partial sums of a time-invariant B's / C's gradient
     float *dA_part;             // [nseg][B][D][16] partial sums per segment and batch entry
     float *dD_part, *db_part;   // [nseg][B][D]
     float* seg_g;               // [nseg][B][D][16]: adjoint carry of a segment (local, then incoming)

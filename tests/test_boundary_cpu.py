@@ -255,3 +255,19 @@ def test_layer_struct_layout_sizes_and_rejections():
     s.batch, s.dim, s.dstate, s.dt_rank, s.conv_width, s.io_dtype = 2, 8, 4, 2, 4, B.SS_F32
     assert B.lib().ss_layer_step(ctypes.byref(s), None) == B.SS_ERR_NULL
     assert B.ss_strerror(B.SS_ERR_BACKEND) not in ("", "unknown error code")
+
+
+def test_time_invariant_bc_flags():
+    # partial sums for the (D,N) gradients are added to the workspace, and the sequence is never split
+    base = B.ss_workspace_bytes(1, 256, 1 << 16, 16, True, B.SS_F32, True)
+    fixed = B.ss_workspace_bytes(1, 256, 1 << 16, 16, True, B.SS_F32, True, b_fixed=True, c_fixed=True)
+    assert fixed != base
+    assert B.ss_workspace_bytes(1, 256, 1 << 16, 16, False, B.SS_F32, True) > 0
+    assert B.ss_workspace_bytes(1, 256, 1 << 16, 16, False, B.SS_F32, True, b_fixed=True) == 0
+    small = B.ss_workspace_bytes(2, 64, 128, 16, True, B.SS_BF16, True)
+    assert B.ss_workspace_bytes(2, 64, 128, 16, True, B.SS_BF16, True, b_fixed=True) == small + 2 * 64 * 16 * 4
+    # a (D,N) float32 parameter needs only 4-byte alignment
+    p = _good_fwd(); p.flags = B.SS_B_FIXED; p.Bmat = FAKE + 4
+    assert _fwd(p) != B.SS_ERR_ALIGN
+    p = _good_fwd(); p.Bmat = FAKE + 4
+    assert _fwd(p) == B.SS_ERR_ALIGN
