@@ -167,11 +167,23 @@ def layer_bench(dev, workload, iters=20):
         for i in range(128):
             B.ss_layer_step(h, cs, xs[i % 8], zs[i % 8], *args[2:], scratch=sscr, out_t=o_t)
     dec_ms = timed(decode) if iters >= 5 else None
+    # the same 128 steps replayed from a HIP graph (the rocBLAS products capture like the kernels)
+    dec_graph_us = None
+    if dec_ms is not None:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                decode()
+        torch.cuda.current_stream().wait_stream(side)
+        dec_graph_us = timed(graph.replay) * 1e3 / 128
     tensor = nb * nd * nl * 2
     return {"workload": "selective SSM layer, batch %d, L %d, D %d, N %d, R %d, conv width 4, bf16 I/O" % (nb, nl, nd, nn, rank),
             "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "token_channels_per_s": nb * nd * nl / ((fwd_ms + bwd_ms) * 1e-3),
             "saved_bytes_per_token_channel": saved.numel() / (nb * nd * nl),
             "decode_us_per_token_batch64": None if dec_ms is None else dec_ms * 1e3 / 128,
+            "decode_us_per_token_batch64_graph": dec_graph_us,
             "conv_fwd": {"ms": cf_ms, "bound": "hbm", "achieved": 2 * tensor / (cf_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                          "unit": "GB/s", "frac": 2 * tensor / (cf_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "conv_bwd": {"ms": cb_ms, "bound": "hbm", "achieved": 3 * tensor / (cb_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
@@ -300,8 +312,10 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    fwd_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    bwd_all = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    fwd_ms = sum(fwd_all) / args.steps
+    bwd_ms = sum(bwd_all) / args.steps
 
     tc = nb * nd * nl
     fwd_b, bwd_b = algorithmic_bytes(nb, nl, nd, nn, esz)
@@ -330,6 +344,8 @@ def main():
                          "frac": bwd_b / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "traffic": traffic.get("scan_bwd_kernel_hbm_bytes")},
         "passes": {"fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+                   "fwd_ms_median": fwd_all[len(fwd_all) // 2], "fwd_ms_min": fwd_all[0],
+                   "bwd_ms_median": bwd_all[len(bwd_all) // 2], "bwd_ms_min": bwd_all[0],
                    "fwd_algorithmic_GBs": fwd_b / (fwd_ms * 1e-3) / 1e9,
                    "fwd_bwd_algorithmic_GBs": (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9,
                    "fwd_bwd_frac_of_hbm_peak": (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -104,3 +104,46 @@ def test_layer_prompt_then_token_by_token(io, shape):
     assert_close(got[:, :, cut:], ref["out"][:, :, cut:], io, "decoded out")
     assert_close(h, ref["h_last"], io, "h after decode")
     np.testing.assert_array_equal(cs.float().cpu().numpy(), ref["conv_state"].astype(np.float32))
+
+
+def test_layer_steps_replayed_from_a_hip_graph():
+    """Decode steps captured once and replayed: every replay must equal the eager run."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    batch, dim, dstate, rank, steps = 8, 256, 16, 8, 12
+    w = make_layer_inputs(batch, steps, dim, dstate, "bf16", seed=41, rank=rank)
+    bf = torch.bfloat16
+    t = {}
+    for k in PARAMS:
+        a = torch.from_numpy(np.ascontiguousarray(w[k])).cuda()
+        t[k] = a.to(bf) if k in ("x", "z", "W_x", "W_dt") else a
+    xs = t["x"].permute(2, 0, 1).contiguous()
+    zs = t["z"].permute(2, 0, 1).contiguous()
+    weights = [t[k] for k in PARAMS[2:]]
+    scratch = torch.empty(B.ss_layer_step_scratch_bytes(batch, dim, dstate, rank), dtype=torch.uint8, device="cuda")
+    h = torch.zeros(batch, dim, dstate, device="cuda")
+    cs = torch.zeros(batch, dim, 3, device="cuda", dtype=bf)
+    outs = torch.empty(steps, batch, dim, device="cuda", dtype=bf)
+
+    def run():
+        for i in range(steps):
+            B.ss_layer_step(h, cs, xs[i], zs[i], *weights, scratch=scratch, out_t=outs[i])
+    run()                                   # eager; also creates the rocBLAS handle outside the capture
+    torch.cuda.synchronize()
+    want_out, want_h = outs.clone(), h.clone()
+    ref = inn.inner_fwd(rnd=_rnd("bf16"), **{k: w[k] for k in PARAMS})
+    assert_close(want_out.permute(1, 2, 0), ref["out"], "bf16", "eager decode")
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    h.zero_(); cs.zero_()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        h.zero_(); cs.zero_(); outs.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, want_out) and torch.equal(h, want_h)
