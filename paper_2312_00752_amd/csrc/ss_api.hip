@@ -17,28 +17,58 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Split of the sequence across workgroups.  The scan kernels run one workgroup per 64 rows
-// of a batch entry; when that gives fewer workgroups than the chip has compute units and
-// the sequence is long, L is cut into segments (multiples of 32 steps) that are scanned
+// of a batch entry; when that fills the chip badly and the sequence is long, L is cut into
+// segments (multiples of 32 steps) that are scanned
 // concurrently and stitched with a carry pass (Appendix D: the scan continues from the
 // state the previous chunk ended in; here the chunks run in parallel from aggregates).
 struct SegPlan {
     int nseg, seg_len;
 };
+// Modelled duration (in steps of one unsplit workgroup running alone on its compute unit) of a
+// launch of n equal workgroups of len steps each.  Two workgroups fit a compute unit and then
+// each runs at about 3/4 of the speed it has alone (measured: 256 workgroups of 2048 steps
+// take 1.01 ms, 512 take 1.35 ms), so the chip takes workgroups in rounds of 512.
+double launch_cost(long n, long len)
+{
+    const double pair = 1.0 / 0.75;
+    const long full = n / 512, rest = n % 512;
+    return (double)len * ((double)full * pair + (rest == 0 ? 0.0 : (rest <= 256 ? 1.0 : pair)));
+}
+
+long segment_length(int L, long nseg)
+{
+    long len = ((L + nseg - 1) / nseg + 31) / 32 * 32;
+    // A segment length that is a large power of two makes every workgroup walk the memory
+    // channels in lockstep (all segment starts alias); an odd multiple of 32 steps staggers them.
+    if (nseg > 1 && len % 256 == 0) len += 160;
+    return len;
+}
+
 SegPlan plan_segments(int B, int D, int L, uint32_t flags)
 {
     const long wgs = (long)B * ((D + 63) / 64);
     SegPlan s{1, (L + 31) / 32 * 32};
     if (s.seg_len == 0) s.seg_len = 32;
     if (flags & (SS_B_FIXED | SS_C_FIXED)) return s;   // the time-invariant variants are not split
-    if (wgs > 256 || L < 2048) return s;               // more than one workgroup per compute unit already
-    long want = (512 + wgs - 1) / wgs;                 // about two workgroups per compute unit
-    want = want < L / 512 ? want : L / 512;            // segments of at least 512 steps
-    if (want < 2) return s;
-    s.seg_len = (int)(((L + want - 1) / want + 31) / 32 * 32);
-    // A segment length that is a large power of two makes every workgroup walk the memory
-    // channels in lockstep (all segment starts alias); an odd multiple of 32 steps staggers them.
-    if (s.seg_len % 256 == 0) s.seg_len += 160;
-    s.nseg = (L + s.seg_len - 1) / s.seg_len;
+    if (L < 2048) return s;
+    // Pick the number of segments that the model says finishes first: the main pass over
+    // wgs * nseg workgroups plus the aggregate pass over wgs * (nseg - 1) of them, which costs
+    // about 0.31 of a main pass per step (measured over forward + backward).  Segments stay
+    // at least 512 steps long so that the carry kernels remain negligible.
+    double best = launch_cost(wgs, s.seg_len);
+    long best_n = 1;
+    const long most = L / 512 < 4096 ? L / 512 : 4096;
+    for (long want = 2; want <= most; ++want) {
+        const long len = segment_length(L, want);
+        const long n = (L + len - 1) / len;   // what that length really gives
+        if (n < 2) continue;
+        const double c = launch_cost(wgs * n, len) + 0.31 * launch_cost(wgs * (n - 1), len);
+        if (c < best * 0.97) { best = c; best_n = want; }   // more segments only for a clear gain
+    }
+    if (best_n > 1) {
+        s.seg_len = (int)segment_length(L, best_n);
+        s.nseg = (L + s.seg_len - 1) / s.seg_len;
+    }
     return s;
 }
 
