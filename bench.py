@@ -247,6 +247,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the single-token step timing")
     ap.add_argument("--no-layer", action="store_true", help="skip the timing of the layer around the scan")
+    ap.add_argument("--layer-iters", type=int, default=20,
+                    help="timed repetitions of each layer call (below 5 the layer's decode loop is skipped)")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="also time the shape of the paper's own scan benchmark over L = 2^9..2^19")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -355,7 +357,7 @@ def main():
     if not args.no_decode:
         res["decode"] = decode_bench(dev)
     if not args.no_layer and args.workload in ("mamba1p4b_layer_bf16", "mamba130m_layer_bf16"):
-        res["layer"] = layer_bench(dev, args.workload)
+        res["layer"] = layer_bench(dev, args.workload, iters=args.layer_iters)
     if args.paper_sweep:
         res["paper_sweep"] = paper_sweep(dev)
     if not args.no_cpu_baseline:
