@@ -39,7 +39,11 @@
  *    seqlen == 0 is valid: tensors with a zero-length axis may then be NULL, h_last (if
  *    requested) receives h0 or 0, and the backward call returns zero parameter gradients
  *    and dh0 = dh_last.
- *  - Supported: 1 <= dstate <= SS_MAX_DSTATE, io_dtype in {SS_F32, SS_BF16}.
+ *  - Supported: 1 <= dstate <= SS_MAX_DSTATE, io_dtype in {SS_F32, SS_BF16}.  The kernels hold
+ *    16 states per row on chip; more states are handled 16 at a time in passes over the
+ *    sequence that add up in the output (time and checkpoint size grow with ceil(dstate/16),
+ *    io_dtype sums are rounded once per pass, and a gated forward call then needs the
+ *    workspace even without SS_SAVE_FOR_BWD).
  */
 #ifndef SS_SCAN_H
 #define SS_SCAN_H
@@ -51,7 +55,7 @@
 extern "C" {
 #endif
 
-#define SS_MAX_DSTATE 16
+#define SS_MAX_DSTATE 256
 /* Spacing, in time steps, of the state checkpoints the forward pass leaves for the
  * backward pass (Appendix D: states are recomputed, not stored). */
 #define SS_CHECKPOINT_STEPS 16

@@ -17,7 +17,7 @@ SS_HAS_H0, SS_WRITE_H_LAST, SS_SAVE_FOR_BWD, SS_EXACT_ZOH_B = 16, 32, 64, 128
 SS_B_FIXED, SS_C_FIXED = 256, 512
 SS_OK, SS_ERR_NULL, SS_ERR_SHAPE, SS_ERR_UNSUPPORTED = 0, -1, -2, -3
 SS_ERR_ALIGN, SS_ERR_WORKSPACE, SS_ERR_LAUNCH = -4, -5, -6
-SS_MAX_DSTATE = 16
+SS_MAX_DSTATE = 256
 SS_CHECKPOINT_STEPS = 16
 
 _vp = ctypes.c_void_p

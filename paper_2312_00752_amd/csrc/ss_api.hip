@@ -76,13 +76,14 @@ SegPlan plan_segments(int B, int D, int L, uint32_t flags)
 }
 
 // Workspace layouts, each block 256-byte aligned.
-//   forward only:  [float seg_h nseg*B*D*16][float seg_sumdt nseg*B*D]        (only when split)
-//   with backward: [float checkpoints nck*B*D*16][io pre-gate y B*D*L, only with a gate]
+//   forward only:  [io pre-gate y B*D*L, only with a gate and more than 16 states]
+//                  [float seg_h nseg*B*D*16][float seg_sumdt nseg*B*D]        (only when split)
+//   with backward: [float checkpoints groups*nck*B*D*16][io pre-gate y B*D*L, only with a gate]
 //                  [seg_h][seg_sumdt][float seg_g nseg*B*D*16]                 (only when split)
 //                  [float dA partials nseg*B*D*16][float dD partials nseg*B*D][float dbias partials nseg*B*D]
 //                  [float dB partials B*D*16][float dC partials B*D*16]    (only for a time-invariant B / C)
 struct WsLayout {
-    size_t ckpt_off, y_off, segh_off, segdt_off, segg_off, dA_off, dD_off, db_off, dBf_off, dCf_off, total;
+    size_t ckpt_off, ckpt_group, y_off, segh_off, segdt_off, segg_off, dA_off, dD_off, db_off, dBf_off, dCf_off, total;
     SegPlan plan;
 };
 WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
@@ -95,8 +96,11 @@ WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
     const size_t ns = (size_t)w.plan.nseg, split = ns > 1 ? 1 : 0;
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off += round_up(bytes, 256); return at; };
-    w.ckpt_off = take(for_bwd ? nck * rows * 16 * sizeof(float) : 0);
-    w.y_off = take(for_bwd && (p->flags & SS_HAS_Z) ? rows * (size_t)p->seqlen * esz : 0);
+    const size_t groups = ((size_t)p->dstate + 15) / 16;   // states are handled 16 at a time
+    w.ckpt_group = nck * rows * 16 * sizeof(float);
+    w.ckpt_off = take(for_bwd ? groups * w.ckpt_group : 0);
+    // the pre-gate y: for the backward pass, and as the accumulator across state groups
+    w.y_off = take((for_bwd || groups > 1) && (p->flags & SS_HAS_Z) ? rows * (size_t)p->seqlen * esz : 0);
     w.segh_off = take(split * ns * rows * 16 * sizeof(float));
     w.segdt_off = take(split * ns * rows * sizeof(float));
     w.segg_off = take(for_bwd ? split * ns * rows * 16 * sizeof(float) : 0);
@@ -137,6 +141,11 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
     const void* f32[] = {p->A, p->Dskip, p->delta_bias, p->h0, for_bwd ? nullptr : p->h_last};
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
+    if (!for_bwd && !(p->flags & SS_SAVE_FOR_BWD) && p->dstate > 16 && (p->flags & SS_HAS_Z) && p->seqlen > 0) {
+        // the pre-gate output is accumulated over the groups of 16 states in the workspace
+        if (!p->workspace || p->workspace_bytes < ws_layout(p, false).total) return SS_ERR_WORKSPACE;
+        if (!aligned(p->workspace, 256)) return SS_ERR_ALIGN;
+    }
     if (for_bwd || (p->flags & SS_SAVE_FOR_BWD)) {
         const size_t need = ws_layout(p, true).total;
         if (!p->workspace || p->workspace_bytes < need) return SS_ERR_WORKSPACE;
@@ -148,7 +157,8 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
 ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
 {
     ss::FwdArgs a{};
-    a.B = p->batch; a.D = p->dim; a.L = p->seqlen; a.N = p->dstate;
+    a.B = p->batch; a.D = p->dim; a.L = p->seqlen; a.N = p->dstate; a.NS = p->dstate;
+    a.acc_y = 0;
     a.flags = p->flags;
     a.vec_ok = p->seqlen % 8 == 0;
     a.u = p->u; a.delta = p->delta; a.z = (p->flags & SS_HAS_Z) ? p->z : nullptr;
@@ -166,6 +176,28 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
     return a;
 }
 
+// Narrows the arguments of a whole call to the g-th group of 16 states: every (..., n) pointer
+// moves to the group's first state (the stride stays NS), checkpoints get the group's block.
+template <typename P> P* at(P* base, long elems) { return base ? base + elems : base; }
+const void* at_bytes(const void* base, size_t bytes) { return base ? static_cast<const char*>(base) + bytes : base; }
+
+void narrow_to_group(ss::FwdArgs& a, const ss_fwd_params* p, int g, size_t ckpt_group_bytes)
+{
+    const int n0 = g * 16;
+    const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
+    a.N = p->dstate - n0 < 16 ? p->dstate - n0 : 16;
+    a.A = at(a.A, n0);
+    a.h0 = at(a.h0, n0);
+    a.h_last = at(a.h_last, n0);
+    a.Bm = (p->flags & SS_B_FIXED) ? at_bytes(a.Bm, (size_t)n0 * 4) : at_bytes(a.Bm, (size_t)n0 * p->seqlen * esz);
+    a.Cm = (p->flags & SS_C_FIXED) ? at_bytes(a.Cm, (size_t)n0 * 4) : at_bytes(a.Cm, (size_t)n0 * p->seqlen * esz);
+    if (a.ckpt) a.ckpt = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ckpt) + (size_t)g * ckpt_group_bytes);
+    if (g > 0) {
+        a.flags &= ~(uint32_t)SS_HAS_D;   // the skip term enters once
+        a.acc_y = 1;
+    }
+}
+
 }  // namespace
 
 namespace ss {
@@ -176,8 +208,11 @@ int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
     if (rc != SS_OK) return rc;
     ss::FwdArgs a = make_fwd_args(p, bc_bstride);
     char* ws = static_cast<char*>(p->workspace);
+    const int groups = p->seqlen == 0 ? 1 : (p->dstate + 15) / 16;
+    size_t ckpt_group = 0;
     if (p->flags & SS_SAVE_FOR_BWD) {
         const WsLayout w = ws_layout(p, true);
+        ckpt_group = w.ckpt_group;
         a.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
         a.ysave = (p->flags & SS_HAS_Z) ? ws + w.y_off : nullptr;
         if (w.plan.nseg > 1) {
@@ -188,13 +223,22 @@ int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
     } else {
         // a plain forward call splits the sequence only if the caller lent the scratch for it
         const WsLayout w = ws_layout(p, false);
-        if (w.plan.nseg > 1 && ws && p->workspace_bytes >= w.total && aligned(ws, 256)) {
+        const bool lent = ws && p->workspace_bytes >= w.total && aligned(ws, 256);
+        if (groups > 1 && (p->flags & SS_HAS_Z)) a.ysave = ws + w.y_off;   // checked to be there
+        if (w.plan.nseg > 1 && lent) {
             a.nseg = w.plan.nseg; a.seg_len = w.plan.seg_len;
             a.seg_h = reinterpret_cast<float*>(ws + w.segh_off);
             a.seg_sumdt = reinterpret_cast<float*>(ws + w.segdt_off);
         }
     }
-    return ss::launch_fwd(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+    // one pass per group of 16 states; the passes run in stream order and share the segment
+    // buffers, each adds its C*h to the y of the ones before it
+    for (int g = 0; g < groups; ++g) {
+        ss::FwdArgs ag = a;
+        if (groups > 1) narrow_to_group(ag, p, g, ckpt_group);
+        if (ss::launch_fwd(ag, p->io_dtype, static_cast<hipStream_t>(stream)) != 0) return SS_ERR_LAUNCH;
+    }
+    return SS_OK;
 }
 
 
@@ -244,7 +288,28 @@ int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
     a.dA = p->dA;
     a.dD = (f->flags & SS_HAS_D) ? p->dD : nullptr;
     a.dbias = (f->flags & SS_HAS_DELTA_BIAS) ? p->ddelta_bias : nullptr;
-    return ss::launch_bwd(a, f->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+    a.acc = 0;
+    a.dbc_bstride = (long)f->dstate * f->seqlen;
+    // one pass per group of 16 states, in stream order: each adds its share of du, ddelta and
+    // dbias to the earlier ones' and writes its own slices of dA, dB, dC and dh0
+    const int groups = (f->dstate + 15) / 16;
+    for (int g = 0; g < groups; ++g) {
+        ss::BwdArgs ag = a;
+        if (groups > 1) {
+            const int n0 = g * 16;
+            narrow_to_group(ag.f, f, g, w.ckpt_group);
+            ag.f.acc_y = 0;
+            ag.acc = g > 0;
+            ag.dh_last = at(ag.dh_last, n0);
+            ag.dh0 = at(ag.dh0, n0);
+            ag.dA = at(ag.dA, n0);
+            ag.dB = at(ag.dB, (f->flags & SS_B_FIXED) ? (long)n0 : (long)n0 * f->seqlen);
+            ag.dC = at(ag.dC, (f->flags & SS_C_FIXED) ? (long)n0 : (long)n0 * f->seqlen);
+            if (g > 0) { ag.dz = nullptr; ag.dD = nullptr; }
+        }
+        if (ss::launch_bwd(ag, f->io_dtype, static_cast<hipStream_t>(stream)) != 0) return SS_ERR_LAUNCH;
+    }
+    return SS_OK;
 }
 
 

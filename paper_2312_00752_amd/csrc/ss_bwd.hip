@@ -103,7 +103,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
     const int groups = (f.D + ROWS - 1) / ROWS;
     const int b = blockIdx.x / groups;
     const int d0 = (blockIdx.x % groups) * ROWS;
-    const int L = f.L, N = f.N;
+    const int L = f.L, N = f.N, NS = f.NS;
     const bool has_z = f.flags & F_HAS_Z, has_D = f.flags & F_HAS_D;
     const bool softplus = f.flags & F_DELTA_SOFTPLUS;
     const int seg = blockIdx.y;  // segment of the sequence (see scan_fwd_kernel)
@@ -143,16 +143,16 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         const int n = w * STATES_PER_LANE + k;
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
-        An[k] = n_ok[k] ? f.A[(long)sd * N + nc] : 0.0f;
+        An[k] = n_ok[k] ? f.A[(long)sd * NS + nc] : 0.0f;
         A2[k] = An[k] * LOG2E;
         invA[k] = An[k] != 0.0f ? 1.0f / An[k] : 0.0f;
-        if (seg == f.nseg - 1) ag[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;  // abar_L g_L := dh_last
+        if (seg == f.nseg - 1) ag[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * NS + nc] : 0.0f;  // abar_L g_L := dh_last
         else ag[k] = a.seg_g[(seg_rows + srow) * NPAD + w * STATES_PER_LANE + k];
         dA[k] = 0.0f;
         gB[k] = BFIX ? nullptr : static_cast<const T*>(f.Bm) + (long)b * f.bc_bstride + (long)nc * L;
         gC[k] = CFIX ? nullptr : static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride + (long)nc * L;
-        Bf[k] = (BFIX && n_ok[k]) ? static_cast<const float*>(f.Bm)[(long)sd * N + nc] : 0.0f;
-        Cf[k] = (CFIX && n_ok[k]) ? static_cast<const float*>(f.Cm)[(long)sd * N + nc] : 0.0f;
+        Bf[k] = (BFIX && n_ok[k]) ? static_cast<const float*>(f.Bm)[(long)sd * NS + nc] : 0.0f;
+        Cf[k] = (CFIX && n_ok[k]) ? static_cast<const float*>(f.Cm)[(long)sd * NS + nc] : 0.0f;
         dBf[k] = 0.0f;
         dCf[k] = 0.0f;
     }
@@ -226,7 +226,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                     dz4[j] = o4[j] * y4[j] * s * fmaf(z4[j], 1.0f - s, 1.0f);  // dout y d[z sigmoid(z)]/dz
                     dy4[j] = o4[j] * z4[j] * s;
                 }
-                io4<T>::template store<VEC>(gdz + t0, dz4, nv);
+                if (a.dz) io4<T>::template store<VEC>(gdz + t0, dz4, nv);   // null for all but the first state group
             }
             *reinterpret_cast<float4*>(&sm.dt[pr][pq * BSL]) = make_float4(dt4[0], dt4[1], dt4[2], dt4[3]);
             *reinterpret_cast<float4*>(&sm.du[pr][pq * BSL]) = make_float4(du4[0], du4[1], du4[2], du4[3]);
@@ -335,7 +335,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
             const int n = w * STATES_PER_LANE + k;
             if ((which ? CFIX : BFIX)) continue;   // that gradient is not per step
             if (n < N && tc + t < L) {
-                float* dst = (which ? a.dC : a.dB) + ((long)b * N + n) * L + tc + t;
+                float* dst = (which ? a.dC : a.dB) + (long)b * a.dbc_bstride + (long)n * L + tc + t;
                 atomicAdd(dst, dbc[idx]);
             }
         }
@@ -363,6 +363,13 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                 dD_acc = fmaf(dy, u4[j], dD_acc);
                 db_acc += (j < nv) ? dl4[j] : 0.0f;
             }
+            if (a.acc) {  // states beyond the first 16: add to the earlier groups' du and ddelta
+                float pu[BSL], pl[BSL];
+                io4<T>::unpack(io4<T>::template load<VEC>(gdu + t0, nv), pu);
+                io4<T>::unpack(io4<T>::template load<VEC>(gdd + t0, nv), pl);
+#pragma unroll
+                for (int j = 0; j < BSL; ++j) { du4[j] += pu[j]; dl4[j] += pl[j]; }
+            }
             io4<T>::template store<VEC>(gdu + t0, du4, nv);
             io4<T>::template store<VEC>(gdd + t0, dl4, nv);
         }
@@ -379,7 +386,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
         if (a.dh0 && seg == 0) {
 #pragma unroll
             for (int k = 0; k < STATES_PER_LANE; ++k)
-                if (n_ok[k]) a.dh0[srow * N + w * STATES_PER_LANE + k] = ag[k];
+                if (n_ok[k]) a.dh0[srow * NS + w * STATES_PER_LANE + k] = ag[k];
         }
     }
     dD_acc += __shfl_xor(dD_acc, 1);
@@ -409,7 +416,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
     const int groups = (f.D + ROWS - 1) / ROWS;
     const int b = blockIdx.x / groups;
     const int d0 = (blockIdx.x % groups) * ROWS;
-    const int L = f.L, N = f.N;
+    const int L = f.L, N = f.N, NS = f.NS;
     const bool has_z = f.flags & F_HAS_Z, softplus = f.flags & F_DELTA_SOFTPLUS;
     const int seg = blockIdx.y + 1;  // segment 0 passes nothing on
     const int c_begin = seg * (f.seg_len / CHUNK_T);
@@ -435,8 +442,8 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
         const int n = w * STATES_PER_LANE + k;
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
-        A2[k] = n_ok[k] ? f.A[(long)sd * N + nc] * LOG2E : 0.0f;
-        ag[k] = (seg == f.nseg - 1 && n_ok[k] && a.dh_last) ? a.dh_last[srow * N + nc] : 0.0f;
+        A2[k] = n_ok[k] ? f.A[(long)sd * NS + nc] * LOG2E : 0.0f;
+        ag[k] = (seg == f.nseg - 1 && n_ok[k] && a.dh_last) ? a.dh_last[srow * NS + nc] : 0.0f;
         gC[k] = static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride + (long)nc * L;
     }
     typename io8<T>::raw rd, rz, ro;
@@ -510,7 +517,7 @@ __global__ void carry_bwd_kernel(const BwdArgs a)
     if (i >= rows * NPAD) return;
     const long row = i / NPAD;
     const int n = i % NPAD, d = row % f.D;
-    const float A2 = n < f.N ? f.A[(long)d * f.N + n] * LOG2E : 0.0f;
+    const float A2 = n < f.N ? f.A[(long)d * f.NS + n] * LOG2E : 0.0f;
     float carry = a.seg_g[(long)(f.nseg - 1) * rows * NPAD + i];  // loc of the last segment (includes dh_last)
     // as in carry_fwd_kernel: loads of a batch of segments first, then the serial chain
     constexpr int CARRY_BATCH = 16;
@@ -563,12 +570,12 @@ __global__ void finalize_kernel(const BwdArgs a, int have_partials)
             if (n == 0) { sD += a.dD_part[row]; sb += a.db_part[row]; }
         }
     }
-    if (n < a.f.N) a.dA[(long)d * a.f.N + n] = sA;
-    if (n < a.f.N && bfix) a.dB[(long)d * a.f.N + n] = sB;
-    if (n < a.f.N && cfix) a.dC[(long)d * a.f.N + n] = sC;
+    if (n < a.f.N) a.dA[(long)d * a.f.NS + n] = sA;
+    if (n < a.f.N && bfix) a.dB[(long)d * a.f.NS + n] = sB;
+    if (n < a.f.N && cfix) a.dC[(long)d * a.f.NS + n] = sC;
     if (n == 0) {
-        if (a.dD) a.dD[d] = sD;
-        if (a.dbias) a.dbias[d] = sb;
+        if (a.dD) a.dD[d] = sD;   // null for all but the first state group
+        if (a.dbias) a.dbias[d] = a.acc ? a.dbias[d] + sb : sb;
     }
 }
 
@@ -623,15 +630,16 @@ int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream)
     const int fin_blocks = (f.D * NPAD + 255) / 256;
     if (f.L == 0) {
         finalize_kernel<<<dim3(fin_blocks), dim3(256), 0, stream>>>(a, 0);
-        if (a.dh0) {
-            const long n = (long)f.B * f.D * f.N;
+        if (a.dh0 && !a.acc) {
+            const long n = (long)f.B * f.D * f.NS;
             copy_dh_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a.dh_last, a.dh0, n);
         }
         return hipGetLastError() == hipSuccess ? 0 : -1;
     }
-    const long nbc = (long)f.B * f.N * f.L;
-    float* const zB = (f.flags & F_B_FIXED) ? nullptr : a.dB;
-    float* const zC = (f.flags & F_C_FIXED) ? nullptr : a.dC;
+    // the first state group clears dB and dC for all of them
+    const long nbc = (long)f.B * f.NS * f.L;
+    float* const zB = ((f.flags & F_B_FIXED) || a.acc) ? nullptr : a.dB;
+    float* const zC = ((f.flags & F_C_FIXED) || a.acc) ? nullptr : a.dC;
     if (zB || zC) zero_kernel<<<dim3((unsigned)((nbc + 255) / 256)), dim3(256), 0, stream>>>(zB, zC, nbc);
     const int groups = (f.D + ROWS - 1) / ROWS;
     const dim3 grid((unsigned)(f.B * groups));

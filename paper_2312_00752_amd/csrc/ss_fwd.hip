@@ -37,7 +37,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     const int groups = (a.D + ROWS - 1) / ROWS;
     const int b = blockIdx.x / groups;
     const int d0 = (blockIdx.x % groups) * ROWS;
-    const int L = a.L, N = a.N;
+    const int L = a.L, N = a.N, NS = a.NS;
     const bool has_z = !AGG && (a.flags & F_HAS_Z), has_D = !AGG && (a.flags & F_HAS_D);
     const bool softplus = a.flags & F_DELTA_SOFTPLUS;
     const int seg = blockIdx.y;
@@ -71,15 +71,15 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         const int n = w * STATES_PER_LANE + k;
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
-        An[k] = n_ok[k] ? a.A[(long)sd * N + nc] : 0.0f;
+        An[k] = n_ok[k] ? a.A[(long)sd * NS + nc] : 0.0f;
         A2[k] = An[k] * LOG2E;
         invA[k] = An[k] != 0.0f ? 1.0f / An[k] : 0.0f;
-        if (seg == 0) h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * N + nc] : 0.0f;
+        if (seg == 0) h[k] = (n_ok[k] && (a.flags & F_HAS_H0)) ? a.h0[srow * NS + nc] : 0.0f;
         else h[k] = AGG ? 0.0f : a.seg_h[((long)seg * a.B * a.D + srow) * NPAD + w * STATES_PER_LANE + k];
         gB[k] = BFIX ? nullptr : static_cast<const T*>(a.Bm) + (long)b * a.bc_bstride + (long)nc * L;
         gC[k] = CFIX ? nullptr : static_cast<const T*>(a.Cm) + (long)b * a.bc_bstride + (long)nc * L;
-        Bf[k] = (BFIX && n_ok[k]) ? static_cast<const float*>(a.Bm)[(long)sd * N + nc] : 0.0f;
-        Cf[k] = (CFIX && n_ok[k]) ? static_cast<const float*>(a.Cm)[(long)sd * N + nc] : 0.0f;
+        Bf[k] = (BFIX && n_ok[k]) ? static_cast<const float*>(a.Bm)[(long)sd * NS + nc] : 0.0f;
+        Cf[k] = (CFIX && n_ok[k]) ? static_cast<const float*>(a.Cm)[(long)sd * NS + nc] : 0.0f;
     }
     // the selective operands (if any) whose cache lines are touched one chunk ahead
     const void* const touchB = BFIX ? a.Cm : a.Bm;
@@ -188,6 +188,13 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 y8[4] += p1.x; y8[5] += p1.y; y8[6] += p1.z; y8[7] += p1.w;
             }
             const int nvs = p_ok ? nv : 0;
+            if (a.acc_y) {  // states beyond the first 16: add to what the earlier groups left
+                const T* prev = (has_z ? static_cast<const T*>(a.ysave) : static_cast<const T*>(a.out)) + prow * L + t0;
+                float p8[SLICE];
+                io8<T>::unpack(io8<T>::template load<VEC>(prev, nvs), p8);
+#pragma unroll
+                for (int j = 0; j < SLICE; ++j) y8[j] += p8[j];
+            }
             if (has_z) {
                 if (a.ysave)  // y before the gate, for the backward pass's dz
                     io8<T>::template store<VEC>(static_cast<T*>(a.ysave) + prow * L + t0, y8, nvs);
@@ -211,7 +218,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     } else if (a.h_last && s_ok && seg == a.nseg - 1) {
 #pragma unroll
         for (int k = 0; k < STATES_PER_LANE; ++k)
-            if (n_ok[k]) a.h_last[srow * N + w * STATES_PER_LANE + k] = h[k];
+            if (n_ok[k]) a.h_last[srow * NS + w * STATES_PER_LANE + k] = h[k];
     }
 }
 
@@ -224,7 +231,7 @@ __global__ void carry_fwd_kernel(const FwdArgs a)
     if (i >= rows * NPAD) return;
     const long row = i / NPAD;
     const int n = i % NPAD, d = row % a.D;
-    const float A2 = n < a.N ? a.A[(long)d * a.N + n] * LOG2E : 0.0f;
+    const float A2 = n < a.N ? a.A[(long)d * a.NS + n] * LOG2E : 0.0f;
     float carry = a.seg_h[i];  // loc[0]: already includes h0
     // Segments are taken CARRY_BATCH at a time: their loads do not depend on the carry, so
     // they are issued together and only the multiply-adds form the serial chain.
@@ -273,36 +280,6 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     auto ld = [](const T* p, long i) -> float {
         if constexpr (sizeof(T) == 2) return bf16_to_f32(p[i]); else return p[i];
     };
-    float hv[STATES_PER_LANE], Av[STATES_PER_LANE], Bv[STATES_PER_LANE], Cv[STATES_PER_LANE];
-    float* hp = a.h + row * N + q * STATES_PER_LANE;
-    if (FULLN) {
-        const float4 h4 = *reinterpret_cast<const float4*>(hp);
-        const float4 A4 = *reinterpret_cast<const float4*>(a.A + (long)d * NPAD + q * STATES_PER_LANE);
-        hv[0] = h4.x; hv[1] = h4.y; hv[2] = h4.z; hv[3] = h4.w;
-        Av[0] = A4.x; Av[1] = A4.y; Av[2] = A4.z; Av[3] = A4.w;
-        const long bo = (long)b * a.bc_stride + q * STATES_PER_LANE;
-        if constexpr (sizeof(T) == 2) {
-            const uint2 Bw = *reinterpret_cast<const uint2*>(B_t + bo);
-            const uint2 Cw = *reinterpret_cast<const uint2*>(C_t + bo);
-            Bv[0] = bf16_lo(Bw.x); Bv[1] = bf16_hi(Bw.x); Bv[2] = bf16_lo(Bw.y); Bv[3] = bf16_hi(Bw.y);
-            Cv[0] = bf16_lo(Cw.x); Cv[1] = bf16_hi(Cw.x); Cv[2] = bf16_lo(Cw.y); Cv[3] = bf16_hi(Cw.y);
-        } else {
-            const float4 B4 = *reinterpret_cast<const float4*>(B_t + bo);
-            const float4 C4 = *reinterpret_cast<const float4*>(C_t + bo);
-            Bv[0] = B4.x; Bv[1] = B4.y; Bv[2] = B4.z; Bv[3] = B4.w;
-            Cv[0] = C4.x; Cv[1] = C4.y; Cv[2] = C4.z; Cv[3] = C4.w;
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < STATES_PER_LANE; ++k) {
-            const int n = q * STATES_PER_LANE + k;
-            const bool ok = n < N;
-            hv[k] = ok ? hp[k] : 0.0f;
-            Av[k] = ok ? a.A[(long)d * N + n] : 0.0f;
-            Bv[k] = !ok ? 0.0f : bfix ? static_cast<const float*>(a.B_t)[(long)d * N + n] : ld(B_t, (long)b * a.bc_stride + n);
-            Cv[k] = !ok ? 0.0f : cfix ? static_cast<const float*>(a.C_t)[(long)d * N + n] : ld(C_t, (long)b * a.bc_stride + n);
-        }
-    }
     const float u = ld(u_t, row);
     float x = ld(dl_t, row) + ((a.flags & F_HAS_DELTA_BIAS) ? a.bias[d] : 0.0f);
     float dt = x, sg;
@@ -310,21 +287,54 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     const float du = ZOH ? u : dt * u, dt2 = dt * LOG2E;
 
     float y = 0.0f;
-#pragma unroll
-    for (int k = 0; k < STATES_PER_LANE; ++k) {
-        const float abar = exp2_fast(dt2 * Av[k]);                  // Eq. 4
-        float bu = du * Bv[k];
-        if (ZOH) bu *= zoh_phi(dt, Av[k], Av[k] != 0.0f ? 1.0f / Av[k] : 0.0f, abar, false).phi;
-        hv[k] = fmaf(abar, hv[k], bu);                              // Eq. 2a
-        y = fmaf(Cv[k], hv[k], y);                                  // Eq. 2b
-    }
-    if (row_ok) {
+    // 16 states per pass: one pass when N <= 16 (always so on the vector path)
+    for (int n0 = 0; n0 < (FULLN ? NPAD : N); n0 += NPAD) {
+        float hv[STATES_PER_LANE], Av[STATES_PER_LANE], Bv[STATES_PER_LANE], Cv[STATES_PER_LANE];
+        float* hp = a.h + row * N + n0 + q * STATES_PER_LANE;
         if (FULLN) {
-            *reinterpret_cast<float4*>(hp) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+            const float4 h4 = *reinterpret_cast<const float4*>(hp);
+            const float4 A4 = *reinterpret_cast<const float4*>(a.A + (long)d * NPAD + q * STATES_PER_LANE);
+            hv[0] = h4.x; hv[1] = h4.y; hv[2] = h4.z; hv[3] = h4.w;
+            Av[0] = A4.x; Av[1] = A4.y; Av[2] = A4.z; Av[3] = A4.w;
+            const long bo = (long)b * a.bc_stride + q * STATES_PER_LANE;
+            if constexpr (sizeof(T) == 2) {
+                const uint2 Bw = *reinterpret_cast<const uint2*>(B_t + bo);
+                const uint2 Cw = *reinterpret_cast<const uint2*>(C_t + bo);
+                Bv[0] = bf16_lo(Bw.x); Bv[1] = bf16_hi(Bw.x); Bv[2] = bf16_lo(Bw.y); Bv[3] = bf16_hi(Bw.y);
+                Cv[0] = bf16_lo(Cw.x); Cv[1] = bf16_hi(Cw.x); Cv[2] = bf16_lo(Cw.y); Cv[3] = bf16_hi(Cw.y);
+            } else {
+                const float4 B4 = *reinterpret_cast<const float4*>(B_t + bo);
+                const float4 C4 = *reinterpret_cast<const float4*>(C_t + bo);
+                Bv[0] = B4.x; Bv[1] = B4.y; Bv[2] = B4.z; Bv[3] = B4.w;
+                Cv[0] = C4.x; Cv[1] = C4.y; Cv[2] = C4.z; Cv[3] = C4.w;
+            }
         } else {
 #pragma unroll
-            for (int k = 0; k < STATES_PER_LANE; ++k)
-                if (q * STATES_PER_LANE + k < N) hp[k] = hv[k];
+            for (int k = 0; k < STATES_PER_LANE; ++k) {
+                const int n = n0 + q * STATES_PER_LANE + k;
+                const bool ok = n < N;
+                hv[k] = ok ? hp[k] : 0.0f;
+                Av[k] = ok ? a.A[(long)d * N + n] : 0.0f;
+                Bv[k] = !ok ? 0.0f : bfix ? static_cast<const float*>(a.B_t)[(long)d * N + n] : ld(B_t, (long)b * a.bc_stride + n);
+                Cv[k] = !ok ? 0.0f : cfix ? static_cast<const float*>(a.C_t)[(long)d * N + n] : ld(C_t, (long)b * a.bc_stride + n);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < STATES_PER_LANE; ++k) {
+            const float abar = exp2_fast(dt2 * Av[k]);                  // Eq. 4
+            float bu = du * Bv[k];
+            if (ZOH) bu *= zoh_phi(dt, Av[k], Av[k] != 0.0f ? 1.0f / Av[k] : 0.0f, abar, false).phi;
+            hv[k] = fmaf(abar, hv[k], bu);                              // Eq. 2a
+            y = fmaf(Cv[k], hv[k], y);                                  // Eq. 2b
+        }
+        if (row_ok) {
+            if (FULLN) {
+                *reinterpret_cast<float4*>(hp) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < STATES_PER_LANE; ++k)
+                    if (n0 + q * STATES_PER_LANE + k < N) hp[k] = hv[k];
+            }
         }
     }
     // sum over the 4 lanes of the row
@@ -377,7 +387,7 @@ int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)
 {
     if (a.L == 0) {
         if (a.h_last) {
-            const long n = (long)a.B * a.D * a.N;
+            const long n = (long)a.B * a.D * a.NS;
             copy_state_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(
                 (a.flags & F_HAS_H0) ? a.h0 : nullptr, a.h_last, n);
         }

@@ -20,6 +20,11 @@ enum : uint32_t {
 
 struct FwdArgs {
     int B, D, L, N;
+    // More than 16 states are handled 16 at a time: N is the size of the group this launch
+    // covers, NS the total number of states = the stride of every (..., n) array, whose
+    // pointers (A, h0, h_last, Bm, Cm and the gradients) already point at the group's first state.
+    int NS;
+    int acc_y;  // forward: this group's C*h is added to the y an earlier group left in ysave (or in out)
     uint32_t flags;
     int vec_ok;  // L % 8 == 0: every row starts 16-byte aligned and 8-step slices are whole or empty
     const void *u, *delta, *z, *Bm, *Cm;
@@ -38,6 +43,8 @@ struct FwdArgs {
 
 struct BwdArgs {
     FwdArgs f;  // out / h_last unused; ckpt required
+    int acc;           // du, ddelta and dbias of an earlier state group are already there: add to them
+    long dbc_bstride;  // elements between consecutive batch entries of dB and dC (NS * L)
     const void* dout;
     const float* dh_last;
     void *du, *ddelta, *dz;
@@ -52,7 +59,7 @@ struct BwdArgs {
 };
 
 struct StepArgs {
-    int B, D, N;
+    int B, D, N;   // N: all states (the step kernels loop over them; no groups)
     uint32_t flags;
     float* h;
     const void *u_t, *delta_t, *z_t, *B_t, *C_t;

@@ -34,7 +34,7 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.FwdParams) == 6 * 4 + 13 * 8
     assert ctypes.sizeof(B.BwdParams) == ctypes.sizeof(B.FwdParams) + 11 * 8
     assert ctypes.sizeof(B.StepParams) == 5 * 4 + 4 + 10 * 8
-    assert B.SS_CHECKPOINT_STEPS == 16 and B.SS_MAX_DSTATE == 16
+    assert B.SS_CHECKPOINT_STEPS == 16 and B.SS_MAX_DSTATE == 256
 
 
 def _good_fwd():
@@ -58,7 +58,7 @@ def test_forward_rejections():
     for f, v in (("batch", 0), ("dim", 0), ("dstate", 0), ("seqlen", -1), ("batch", -3)):
         p = _good_fwd(); setattr(p, f, v)
         assert _fwd(p) == B.SS_ERR_SHAPE, f
-    p = _good_fwd(); p.dstate = 17
+    p = _good_fwd(); p.dstate = 257
     assert _fwd(p) == B.SS_ERR_UNSUPPORTED
     p = _good_fwd(); p.io_dtype = 2
     assert _fwd(p) == B.SS_ERR_UNSUPPORTED
@@ -140,7 +140,7 @@ def test_step_rejections():
         assert step(p) == B.SS_ERR_NULL, f
     p = good(); p.dstate = 0
     assert step(p) == B.SS_ERR_SHAPE
-    p = good(); p.dstate = 64
+    p = good(); p.dstate = 257
     assert step(p) == B.SS_ERR_UNSUPPORTED
     p = good(); p.flags = B.SS_HAS_H0
     assert step(p) == B.SS_ERR_UNSUPPORTED
@@ -237,7 +237,7 @@ def test_layer_struct_layout_sizes_and_rejections():
     for f, v in (("batch", 0), ("dim", 0), ("seqlen", 0), ("dstate", 0), ("dt_rank", 0), ("conv_width", 0)):
         p = _good_layer(); setattr(p, f, v)
         assert fwd(p) == B.SS_ERR_SHAPE, f
-    p = _good_layer(); p.dstate = 17
+    p = _good_layer(); p.dstate = 257
     assert fwd(p) == B.SS_ERR_UNSUPPORTED
     p = _good_layer(); p.flags = 1
     assert fwd(p) == B.SS_ERR_UNSUPPORTED
