@@ -18,6 +18,15 @@
  *
  * with h_{-1} = h0[b,d,:] (SS_HAS_H0) or 0, and h_last = h_{L-1}.
  *
+ * With SS_COMPLEX_STATE the state h, A, Bmat and Cmat are complex and the same equations are
+ * taken over the complex numbers, with first-order B-bar and the real part read out:
+ *     abar = exp(dt A),  h_t = abar h_{t-1} + dt Bmat u,  y_t = Re(sum_n Cmat h_t,n) (+ Dskip u).
+ * dstate counts complex states.  Every complex array carries a (re, im) pair where the real
+ * case has one number, as the axis right after n: A, dA (D,N,2); h0, h_last, dh_last, dh0
+ * (B,D,N,2); Bmat, Cmat, dB, dC (B,N,2,L) (a row of real parts, then a row of imaginary
+ * parts, per state); a time-invariant Bmat / Cmat (D,N,2).  Gradients of complex inputs are
+ * (dLoss/dRe, dLoss/dIm).  SS_EXACT_ZOH_B is not available together with it.
+ *
  * General rules for every entry point
  *  - All data pointers are DEVICE pointers owned by the caller.  The library never
  *    allocates, frees or synchronises; a call only enqueues kernels on `stream`
@@ -73,7 +82,8 @@ enum {
     SS_EXACT_ZOH_B    = 128u, /* exact zero-order-hold B-bar of Eq. 4 instead of dt * B    */
     SS_B_FIXED        = 256u, /* Bmat is the time-invariant (D,N) float32 parameter of
                                  Algorithm 1 (the non-selective arm of Table 7); dB likewise */
-    SS_C_FIXED        = 512u  /* the same for Cmat / dC                                     */
+    SS_C_FIXED        = 512u, /* the same for Cmat / dC                                     */
+    SS_COMPLEX_STATE  = 1024u /* complex state (Section 3.6, "Real vs. Complex"): see below */
 };
 
 enum {
@@ -142,7 +152,8 @@ typedef struct {
     int32_t batch, dim, dstate;       /* B, D, N                                           */
     int32_t io_dtype;                 /* of u_t, delta_t, z_t, B_t, C_t, out_t             */
     uint32_t flags;                   /* SS_DELTA_SOFTPLUS, SS_HAS_DELTA_BIAS, SS_HAS_D,
-                                         SS_HAS_Z, SS_EXACT_ZOH_B, SS_B_FIXED, SS_C_FIXED  */
+                                         SS_HAS_Z, SS_EXACT_ZOH_B, SS_B_FIXED, SS_C_FIXED,
+                                         SS_COMPLEX_STATE                                   */
     float *h;                         /* (B,D,N) float32 state, updated IN PLACE           */
     const void *u_t, *delta_t, *z_t;  /* (B,D)                                             */
     const void *B_t, *C_t;            /* (B,N); (D,N) float32 with SS_B_FIXED / SS_C_FIXED */

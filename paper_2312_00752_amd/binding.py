@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libss_scan.so")
 SS_F32, SS_BF16 = 0, 1
 SS_DELTA_SOFTPLUS, SS_HAS_DELTA_BIAS, SS_HAS_D, SS_HAS_Z = 1, 2, 4, 8
 SS_HAS_H0, SS_WRITE_H_LAST, SS_SAVE_FOR_BWD, SS_EXACT_ZOH_B = 16, 32, 64, 128
-SS_B_FIXED, SS_C_FIXED = 256, 512
+SS_B_FIXED, SS_C_FIXED, SS_COMPLEX_STATE = 256, 512, 1024
 SS_OK, SS_ERR_NULL, SS_ERR_SHAPE, SS_ERR_UNSUPPORTED = 0, -1, -2, -3
 SS_ERR_ALIGN, SS_ERR_WORKSPACE, SS_ERR_LAUNCH = -4, -5, -6
 SS_MAX_DSTATE = 256
@@ -183,7 +183,8 @@ def _stream(stream):
     return stream.cuda_stream
 
 
-def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh=False):
+def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh=False,
+                complex_state=False):
     import torch
     f32 = torch.float32
     nb, nd, nl = u.shape
@@ -192,21 +193,23 @@ def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplu
     p = FwdParams()
     p.batch, p.dim, p.seqlen, p.dstate = nb, nd, nl, nn
     p.io_dtype = _io_code(u)
-    flags = 0
+    flags = SS_COMPLEX_STATE if complex_state else 0
+    # complex state: every complex array has a (re, im) axis right after the state axis
+    c2 = (2,) if complex_state else ()
     p.u = _ptr(u, io, (nb, nd, nl), "u")
     p.delta = _ptr(delta, io, (nb, nd, nl), "delta")
     # a 2-D float32 (D,N) tensor is the time-invariant form of B / C (Algorithm 1)
-    if Bmat.dim() == 2:
-        p.Bmat = _ptr(Bmat, f32, (nd, nn), "Bmat")
+    if Bmat.dim() == 2 + len(c2):
+        p.Bmat = _ptr(Bmat, f32, (nd, nn) + c2, "Bmat")
         flags |= SS_B_FIXED
     else:
-        p.Bmat = _ptr(Bmat, io, (nb, nn, nl), "Bmat")
-    if Cmat.dim() == 2:
-        p.Cmat = _ptr(Cmat, f32, (nd, nn), "Cmat")
+        p.Bmat = _ptr(Bmat, io, (nb, nn) + c2 + (nl,), "Bmat")
+    if Cmat.dim() == 2 + len(c2):
+        p.Cmat = _ptr(Cmat, f32, (nd, nn) + c2, "Cmat")
         flags |= SS_C_FIXED
     else:
-        p.Cmat = _ptr(Cmat, io, (nb, nn, nl), "Cmat")
-    p.A = _ptr(A, f32, (nd, nn), "A")
+        p.Cmat = _ptr(Cmat, io, (nb, nn) + c2 + (nl,), "Cmat")
+    p.A = _ptr(A, f32, (nd, nn) + c2, "A")
     if z is not None:
         p.z = _ptr(z, io, (nb, nd, nl), "z")
         flags |= SS_HAS_Z
@@ -217,7 +220,7 @@ def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplu
         p.delta_bias = _ptr(delta_bias, f32, (nd,), "delta_bias")
         flags |= SS_HAS_DELTA_BIAS
     if h0 is not None:
-        p.h0 = _ptr(h0, f32, (nb, nd, nn), "h0")
+        p.h0 = _ptr(h0, f32, (nb, nd, nn) + c2, "h0")
         flags |= SS_HAS_H0
     if delta_softplus:
         flags |= SS_DELTA_SOFTPLUS
@@ -228,33 +231,36 @@ def _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplu
 
 
 def ss_workspace_bytes(batch, dim, seqlen, dstate, for_backward=True, io_dtype=SS_F32, has_z=True,
-                       b_fixed=False, c_fixed=False):
+                       b_fixed=False, c_fixed=False, complex_state=False):
     """Workspace size; the defaults (float32 I/O, gate present) give an upper bound for selective B, C."""
     p = FwdParams()
     p.batch, p.dim, p.seqlen, p.dstate = batch, dim, seqlen, dstate
     p.io_dtype = io_dtype
-    p.flags = (SS_HAS_Z if has_z else 0) | (SS_B_FIXED if b_fixed else 0) | (SS_C_FIXED if c_fixed else 0)
+    p.flags = ((SS_HAS_Z if has_z else 0) | (SS_B_FIXED if b_fixed else 0) | (SS_C_FIXED if c_fixed else 0)
+               | (SS_COMPLEX_STATE if complex_state else 0))
     return int(lib().ss_workspace_bytes(ctypes.byref(p), int(bool(for_backward))))
 
 
 def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0=None,
                 delta_softplus=False, out=None, h_last=None, return_last_state=False,
-                workspace=None, save_for_bwd=True, exact_zoh=False, stream=None):
+                workspace=None, save_for_bwd=True, exact_zoh=False, complex_state=False, stream=None):
     """Enqueue the forward scan.  Returns (out, h_last or None).
+    With ``complex_state`` A is (D,N,2), B and C (B,N,2,L), h0 / h_last (B,D,N,2): (re, im) pairs.
 
     ``workspace`` is a uint8 CUDA tensor of at least ``ss_workspace_bytes(...)`` bytes.  With
     ``save_for_bwd`` (the default when a workspace is given) the call leaves what
     ``ss_scan_bwd`` needs in it; without, the workspace only serves as scratch that lets
     a long sequence with few rows be split across workgroups."""
     import torch
-    p = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh)
+    p = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh, complex_state)
+    state_shape = (p.batch, p.dim, p.dstate) + ((2,) if complex_state else ())
     if out is None:
         out = torch.empty_like(u)
     p.out = _ptr(out, u.dtype, u.shape, "out")
     if return_last_state or h_last is not None:
         if h_last is None:
-            h_last = torch.empty((p.batch, p.dim, p.dstate), dtype=torch.float32, device=u.device)
-        p.h_last = _ptr(h_last, torch.float32, (p.batch, p.dim, p.dstate), "h_last")
+            h_last = torch.empty(state_shape, dtype=torch.float32, device=u.device)
+        p.h_last = _ptr(h_last, torch.float32, state_shape, "h_last")
         p.flags |= SS_WRITE_H_LAST
     if workspace is not None:
         p.workspace = _ptr(workspace, torch.uint8, None, "workspace")
@@ -268,7 +274,8 @@ def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0
 
 
 def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, delta_bias=None,
-                h0=None, delta_softplus=False, dh_last=None, want_dh0=False, exact_zoh=False, stream=None):
+                h0=None, delta_softplus=False, dh_last=None, want_dh0=False, exact_zoh=False, complex_state=False,
+                stream=None):
     """Enqueue the backward scan after a forward call that filled ``workspace``.
 
     Returns a dict with du, ddelta, dz, dB, dC, dA, dD, ddelta_bias, dh0 (None where the
@@ -276,8 +283,9 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
     import torch
     f32 = torch.float32
     q = BwdParams()
-    q.fwd = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh)
+    q.fwd = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh, complex_state)
     nb, nd, nl, nn = q.fwd.batch, q.fwd.dim, q.fwd.seqlen, q.fwd.dstate
+    state_shape = (nb, nd, nn) + ((2,) if complex_state else ())
     q.fwd.workspace = _ptr(workspace, torch.uint8, None, "workspace")
     q.fwd.workspace_bytes = workspace.numel()
     dev = u.device
@@ -285,12 +293,12 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
          "dz": torch.empty_like(u) if z is not None else None,
          "dB": torch.empty(tuple(Bmat.shape), dtype=f32, device=dev),
          "dC": torch.empty(tuple(Cmat.shape), dtype=f32, device=dev),
-         "dA": torch.empty((nd, nn), dtype=f32, device=dev),
+         "dA": torch.empty(tuple(A.shape), dtype=f32, device=dev),
          "dD": torch.empty((nd,), dtype=f32, device=dev) if Dskip is not None else None,
          "ddelta_bias": torch.empty((nd,), dtype=f32, device=dev) if delta_bias is not None else None,
-         "dh0": torch.empty((nb, nd, nn), dtype=f32, device=dev) if want_dh0 else None}
+         "dh0": torch.empty(state_shape, dtype=f32, device=dev) if want_dh0 else None}
     q.dout = _ptr(dout, u.dtype, u.shape, "dout")
-    q.dh_last = _ptr(dh_last, f32, (nb, nd, nn), "dh_last")
+    q.dh_last = _ptr(dh_last, f32, state_shape, "dh_last")
     for name in ("du", "ddelta", "dz", "dB", "dC", "dA", "dD", "ddelta_bias", "dh0"):
         setattr(q, name, _ptr(g[name], None, None, name))
     rc = lib().ss_scan_bwd(ctypes.byref(q), _stream(stream))
@@ -300,24 +308,26 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
 
 
 def ss_step(h, u_t, delta_t, A, B_t, C_t, Dskip=None, z_t=None, delta_bias=None,
-            delta_softplus=False, out_t=None, exact_zoh=False, b_fixed=False, c_fixed=False, stream=None):
+            delta_softplus=False, out_t=None, exact_zoh=False, b_fixed=False, c_fixed=False, complex_state=False,
+            stream=None):
     """Enqueue one recurrent step; ``h`` (B,D,N) float32 is updated in place.  Returns out_t.
     With ``b_fixed`` / ``c_fixed`` B_t / C_t is the time-invariant (D,N) float32 parameter."""
     import torch
     f32 = torch.float32
-    nb, nd, nn = h.shape
+    nb, nd, nn = h.shape[:3]
+    c2 = (2,) if complex_state else ()
     io = u_t.dtype
     p = StepParams()
     p.batch, p.dim, p.dstate = nb, nd, nn
     p.io_dtype = _io_code(u_t)
     flags = (SS_DELTA_SOFTPLUS if delta_softplus else 0) | (SS_EXACT_ZOH_B if exact_zoh else 0)
-    flags |= (SS_B_FIXED if b_fixed else 0) | (SS_C_FIXED if c_fixed else 0)
-    p.h = _ptr(h, f32, (nb, nd, nn), "h")
+    flags |= (SS_B_FIXED if b_fixed else 0) | (SS_C_FIXED if c_fixed else 0) | (SS_COMPLEX_STATE if complex_state else 0)
+    p.h = _ptr(h, f32, (nb, nd, nn) + c2, "h")
     p.u_t = _ptr(u_t, io, (nb, nd), "u_t")
     p.delta_t = _ptr(delta_t, io, (nb, nd), "delta_t")
-    p.B_t = _ptr(B_t, f32, (nd, nn), "B_t") if b_fixed else _ptr(B_t, io, (nb, nn), "B_t")
-    p.C_t = _ptr(C_t, f32, (nd, nn), "C_t") if c_fixed else _ptr(C_t, io, (nb, nn), "C_t")
-    p.A = _ptr(A, f32, (nd, nn), "A")
+    p.B_t = _ptr(B_t, f32, (nd, nn) + c2, "B_t") if b_fixed else _ptr(B_t, io, (nb, nn) + c2, "B_t")
+    p.C_t = _ptr(C_t, f32, (nd, nn) + c2, "C_t") if c_fixed else _ptr(C_t, io, (nb, nn) + c2, "C_t")
+    p.A = _ptr(A, f32, (nd, nn) + c2, "A")
     if z_t is not None:
         p.z_t = _ptr(z_t, io, (nb, nd), "z_t")
         flags |= SS_HAS_Z

@@ -9,12 +9,16 @@ namespace {
 
 constexpr uint32_t kFwdFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z |
                                SS_HAS_H0 | SS_WRITE_H_LAST | SS_SAVE_FOR_BWD | SS_EXACT_ZOH_B |
-                               SS_B_FIXED | SS_C_FIXED;
+                               SS_B_FIXED | SS_C_FIXED | SS_COMPLEX_STATE;
 constexpr uint32_t kStepFlags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z | SS_EXACT_ZOH_B |
-                                SS_B_FIXED | SS_C_FIXED;
+                                SS_B_FIXED | SS_C_FIXED | SS_COMPLEX_STATE;
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+// Real numbers per state vector: a complex state is a (re, im) pair of slots, and everything
+// below the validation works on slots.
+inline int slots(const ss_fwd_params* p) { return p->dstate * ((p->flags & SS_COMPLEX_STATE) ? 2 : 1); }
+inline int slots(const ss_step_params* p) { return p->dstate * ((p->flags & SS_COMPLEX_STATE) ? 2 : 1); }
 
 // Split of the sequence across workgroups.  The scan kernels run one workgroup per 64 rows
 // of a batch entry; when that fills the chip badly and the sequence is long, L is cut into
@@ -96,7 +100,7 @@ WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
     const size_t ns = (size_t)w.plan.nseg, split = ns > 1 ? 1 : 0;
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off += round_up(bytes, 256); return at; };
-    const size_t groups = ((size_t)p->dstate + 15) / 16;   // states are handled 16 at a time
+    const size_t groups = ((size_t)slots(p) + 15) / 16;   // states are handled 16 at a time
     w.ckpt_group = nck * rows * 16 * sizeof(float);
     w.ckpt_off = take(for_bwd ? groups * w.ckpt_group : 0);
     // the pre-gate y: for the backward pass, and as the accumulator across state groups
@@ -118,7 +122,8 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
 {
     if (!p) return SS_ERR_NULL;
     if (p->batch < 1 || p->dim < 1 || p->dstate < 1 || p->seqlen < 0) return SS_ERR_SHAPE;
-    if (p->dstate > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
+    if (p->dstate > SS_MAX_DSTATE || slots(p) > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
+    if ((p->flags & SS_COMPLEX_STATE) && (p->flags & SS_EXACT_ZOH_B)) return SS_ERR_UNSUPPORTED;
     if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
     if (p->flags & ~kFwdFlags) return SS_ERR_UNSUPPORTED;
     const bool empty = p->seqlen == 0;  // tensors with a zero-length axis may be NULL
@@ -141,7 +146,7 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
     const void* f32[] = {p->A, p->Dskip, p->delta_bias, p->h0, for_bwd ? nullptr : p->h_last};
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
-    if (!for_bwd && !(p->flags & SS_SAVE_FOR_BWD) && p->dstate > 16 && (p->flags & SS_HAS_Z) && p->seqlen > 0) {
+    if (!for_bwd && !(p->flags & SS_SAVE_FOR_BWD) && slots(p) > 16 && (p->flags & SS_HAS_Z) && p->seqlen > 0) {
         // the pre-gate output is accumulated over the groups of 16 states in the workspace
         if (!p->workspace || p->workspace_bytes < ws_layout(p, false).total) return SS_ERR_WORKSPACE;
         if (!aligned(p->workspace, 256)) return SS_ERR_ALIGN;
@@ -157,7 +162,7 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
 ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
 {
     ss::FwdArgs a{};
-    a.B = p->batch; a.D = p->dim; a.L = p->seqlen; a.N = p->dstate; a.NS = p->dstate;
+    a.B = p->batch; a.D = p->dim; a.L = p->seqlen; a.N = slots(p); a.NS = slots(p);
     a.acc_y = 0;
     a.flags = p->flags;
     a.vec_ok = p->seqlen % 8 == 0;
@@ -185,7 +190,7 @@ void narrow_to_group(ss::FwdArgs& a, const ss_fwd_params* p, int g, size_t ckpt_
 {
     const int n0 = g * 16;
     const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
-    a.N = p->dstate - n0 < 16 ? p->dstate - n0 : 16;
+    a.N = slots(p) - n0 < 16 ? slots(p) - n0 : 16;
     a.A = at(a.A, n0);
     a.h0 = at(a.h0, n0);
     a.h_last = at(a.h_last, n0);
@@ -204,11 +209,11 @@ namespace ss {
 
 int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
 {
-    const int rc = check_fwd(p, false, p && bc_bstride == (long)p->dstate * p->seqlen);
+    const int rc = check_fwd(p, false, p && bc_bstride == (long)slots(p) * p->seqlen);
     if (rc != SS_OK) return rc;
     ss::FwdArgs a = make_fwd_args(p, bc_bstride);
     char* ws = static_cast<char*>(p->workspace);
-    const int groups = p->seqlen == 0 ? 1 : (p->dstate + 15) / 16;
+    const int groups = p->seqlen == 0 ? 1 : (slots(p) + 15) / 16;
     size_t ckpt_group = 0;
     if (p->flags & SS_SAVE_FOR_BWD) {
         const WsLayout w = ws_layout(p, true);
@@ -245,7 +250,7 @@ int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
 int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
 {
     if (!p) return SS_ERR_NULL;
-    const int rc = check_fwd(&p->fwd, true, bc_bstride == (long)p->fwd.dstate * p->fwd.seqlen);
+    const int rc = check_fwd(&p->fwd, true, bc_bstride == (long)slots(&p->fwd) * p->fwd.seqlen);
     if (rc != SS_OK) return rc;
     const ss_fwd_params* f = &p->fwd;
     const bool empty = f->seqlen == 0;
@@ -289,10 +294,10 @@ int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
     a.dD = (f->flags & SS_HAS_D) ? p->dD : nullptr;
     a.dbias = (f->flags & SS_HAS_DELTA_BIAS) ? p->ddelta_bias : nullptr;
     a.acc = 0;
-    a.dbc_bstride = (long)f->dstate * f->seqlen;
+    a.dbc_bstride = (long)slots(f) * f->seqlen;
     // one pass per group of 16 states, in stream order: each adds its share of du, ddelta and
     // dbias to the earlier ones' and writes its own slices of dA, dB, dC and dh0
-    const int groups = (f->dstate + 15) / 16;
+    const int groups = (slots(f) + 15) / 16;
     for (int g = 0; g < groups; ++g) {
         ss::BwdArgs ag = a;
         if (groups > 1) {
@@ -317,7 +322,8 @@ int step_strided(const ss_step_params* p, long bc_stride, void* stream)
 {
     if (!p) return SS_ERR_NULL;
     if (p->batch < 1 || p->dim < 1 || p->dstate < 1) return SS_ERR_SHAPE;
-    if (p->dstate > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
+    if (p->dstate > SS_MAX_DSTATE || slots(p) > SS_MAX_DSTATE) return SS_ERR_UNSUPPORTED;
+    if ((p->flags & SS_COMPLEX_STATE) && (p->flags & SS_EXACT_ZOH_B)) return SS_ERR_UNSUPPORTED;
     if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
     if (p->flags & ~kStepFlags) return SS_ERR_UNSUPPORTED;
     if (!p->h || !p->u_t || !p->delta_t || !p->B_t || !p->C_t || !p->A || !p->out_t) return SS_ERR_NULL;
@@ -335,7 +341,7 @@ int step_strided(const ss_step_params* p, long bc_stride, void* stream)
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
     ss::StepArgs a{};
-    a.B = p->batch; a.D = p->dim; a.N = p->dstate; a.flags = p->flags;
+    a.B = p->batch; a.D = p->dim; a.N = slots(p); a.flags = p->flags;
     a.h = p->h; a.u_t = p->u_t; a.delta_t = p->delta_t; a.z_t = p->z_t;
     a.B_t = p->B_t; a.C_t = p->C_t; a.bc_stride = bc_stride; a.A = p->A; a.Dskip = p->Dskip; a.bias = p->delta_bias;
     a.out_t = p->out_t;
@@ -355,19 +361,19 @@ size_t ss_workspace_bytes(const ss_fwd_params* p, int for_backward)
 int ss_scan_fwd(const ss_fwd_params* p, void* stream)
 {
     if (!p) return SS_ERR_NULL;
-    return ss::scan_fwd_strided(p, (long)p->dstate * p->seqlen, stream);
+    return ss::scan_fwd_strided(p, (long)slots(p) * p->seqlen, stream);
 }
 
 int ss_scan_bwd(const ss_bwd_params* p, void* stream)
 {
     if (!p) return SS_ERR_NULL;
-    return ss::scan_bwd_strided(p, (long)p->fwd.dstate * p->fwd.seqlen, stream);
+    return ss::scan_bwd_strided(p, (long)slots(&p->fwd) * p->fwd.seqlen, stream);
 }
 
 int ss_step(const ss_step_params* p, void* stream)
 {
     if (!p) return SS_ERR_NULL;
-    return ss::step_strided(p, p->dstate, stream);
+    return ss::step_strided(p, slots(p), stream);
 }
 
 const char* ss_strerror(int code)

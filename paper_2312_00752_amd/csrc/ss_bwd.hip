@@ -10,6 +10,14 @@
 //     ddt_t  = sum_n g_t,n (abar_t,n h_{t-1,n} A_n + B_t,n u_t)
 //     du_t   = dt_t sum_n g_t,n B_t,n + Dskip dy_t        dh0_n = abar_0,n g_0,n
 // and the softplus / SiLU factors of the pointwise stages.
+//
+// Complex state (CPLX): a lane's slots (k, k+1) are (re, im) of one complex state, the step is the
+// real 2x2 map  (hr, hi) <- M (hr, hi) + dt u (Br, Bi),  M = [[abr, -abi], [abi, abr]],
+// abar = abr + i abi = exp(dt (Ar + i Ai)), and y = Cr hr - Ci hi.  With (gr, gi) the gradient
+// reaching (hr, hi):  (gr, gi) = (Cr, -Ci) dy + M^T (gr, gi)+,   dCr = dy hr, dCi = -dy hi,
+// dBr = gr dt u, dBi = gi dt u,   and with  P = d_abr abr + d_abi abi,  Q = -d_abr abi + d_abi abr,
+// d_abr = gr hr- + gi hi-,  d_abi = -gr hi- + gi hr-  (h- the previous state):
+// ddt += Ar P + Ai Q + (gr Br + gi Bi) u,   dAr += dt P,   dAi += dt Q,   du += dt (gr Br + gi Bi).
 #include "ss_kernels.h"
 #include "ss_device.h"
 
@@ -90,8 +98,10 @@ __device__ __forceinline__ void reduce_take(float (*red)[RED_PITCH], float* acc,
 // BCFIX (bit 0: B, bit 1: C): the operand is the time-invariant (D,N) parameter; it is held in
 // registers like A and its gradient, a sum over batch and time, is accumulated per lane like
 // dA instead of being reduced over the rows of the workgroup.
-template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX = 0>
-__global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
+// The exact-ZOH and time-invariant-B/C variants need more registers than two workgroups per
+// compute unit leave (they spilled hundreds); they are built for one workgroup per unit instead.
+template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX = 0, bool CPLX = false>
+__global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd_kernel(const BwdArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     BwdSmem& sm = *reinterpret_cast<BwdSmem*>(smem_raw);
@@ -255,6 +265,21 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 #pragma unroll
                 for (int j = 0; j < GROUP_T; ++j) {
                     const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
+                    if constexpr (CPLX) {
+#pragma unroll
+                        for (int k = 0; k < STATES_PER_LANE; k += 2) {
+                            const cplx ab = complex_decay(dt, A2[k], An[k + 1]);
+                            const float br = du * (BFIX ? Bf[k] : Bg[k].get(j));
+                            const float bi = du * (BFIX ? Bf[k + 1] : Bg[k + 1].get(j));
+                            const float hr = fmaf(ab.re, h[k], fmaf(-ab.im, h[k + 1], br));
+                            const float hi = fmaf(ab.im, h[k], fmaf(ab.re, h[k + 1], bi));
+                            h[k] = hr; h[k + 1] = hi;
+                            as[tl + j][k] = ab.re; as[tl + j][k + 1] = ab.im;
+                            hs[tl + j][k] = hr; hs[tl + j][k + 1] = hi;
+                            if (CFIX) { dCf[k] = fmaf(dy, hr, dCf[k]); dCf[k + 1] = fmaf(-dy, hi, dCf[k + 1]); }
+                            else { dCv[j * STATES_PER_LANE + k] = dy * hr; dCv[j * STATES_PER_LANE + k + 1] = -dy * hi; }
+                        }
+                    } else {
 #pragma unroll
                     for (int k = 0; k < STATES_PER_LANE; ++k) {
                         const float abar = exp2_fast(dt * A2[k]);
@@ -265,6 +290,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                         hs[tl + j][k] = h[k];
                         if (CFIX) dCf[k] = fmaf(dy, h[k], dCf[k]);
                         else dCv[j * STATES_PER_LANE + k] = dy * h[k];
+                    }
                     }
                 }
                 if (!CFIX) {
@@ -294,6 +320,27 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                 const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
                 dd[j] = 0.0f;
                 sb[j] = 0.0f;
+                if constexpr (CPLX) {
+#pragma unroll
+                    for (int k = 0; k < STATES_PER_LANE; k += 2) {
+                        const float Br = BFIX ? Bf[k] : Bg[k].get(j), Bi = BFIX ? Bf[k + 1] : Bg[k + 1].get(j);
+                        const float gr = fmaf(CFIX ? Cf[k] : Cg[k].get(j), dy, ag[k]);
+                        const float gi = fmaf(-(CFIX ? Cf[k + 1] : Cg[k + 1].get(j)), dy, ag[k + 1]);
+                        const float abr = as[t][k], abi = as[t][k + 1];
+                        ag[k] = fmaf(abr, gr, abi * gi);                  // M^T g flows on to h_{t-1}
+                        ag[k + 1] = fmaf(abr, gi, -abi * gr);
+                        const float hpr = (t > 0) ? hs[t > 0 ? t - 1 : 0][k] : hck[k];
+                        const float hpi = (t > 0) ? hs[t > 0 ? t - 1 : 0][k + 1] : hck[k + 1];
+                        const float d_abr = fmaf(gr, hpr, gi * hpi), d_abi = fmaf(gi, hpr, -gr * hpi);
+                        const float P = fmaf(d_abr, abr, d_abi * abi), Q = fmaf(d_abi, abr, -d_abr * abi);
+                        dA[k] = fmaf(P, dt, dA[k]);
+                        dA[k + 1] = fmaf(Q, dt, dA[k + 1]);
+                        dd[j] = fmaf(P, A2[k], fmaf(Q, A2[k + 1], dd[j]));
+                        sb[j] = fmaf(gr, Br, fmaf(gi, Bi, sb[j]));
+                        if (BFIX) { dBf[k] = fmaf(gr, du, dBf[k]); dBf[k + 1] = fmaf(gi, du, dBf[k + 1]); }
+                        else { dBv[j * STATES_PER_LANE + k] = gr * du; dBv[j * STATES_PER_LANE + k + 1] = gi * du; }
+                    }
+                } else {
 #pragma unroll
                 for (int k = 0; k < STATES_PER_LANE; ++k) {
                     const float Bv = BFIX ? Bf[k] : Bg[k].get(j);
@@ -316,6 +363,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
                         if (BFIX) dBf[k] = fmaf(gk, du, dBf[k]);
                         else dBv[j * STATES_PER_LANE + k] = gk * du;
                     }
+                }
                 }
             }
             *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
@@ -404,7 +452,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_kernel(const BwdArgs a)
 // from dh_last), and leaves the carry abar g at the segment's first step in seg_g.  Needs
 // no states, so it is the forward kernel's loop structure walked backwards: 32-step chunks,
 // dt and dy staged through LDS, C on the scalar path.
-template <typename T, bool VEC, bool FULLN>
+template <typename T, bool VEC, bool FULLN, bool CPLX = false>
 __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -434,7 +482,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
     const bool s_ok = d0 + lane < f.D;
     const int sd = s_ok ? d0 + lane : f.D - 1;
     const long srow = (long)b * f.D + sd;
-    float A2[STATES_PER_LANE], ag[STATES_PER_LANE];
+    float A2[STATES_PER_LANE], An[STATES_PER_LANE], ag[STATES_PER_LANE];
     const T* __restrict__ gC[STATES_PER_LANE];
     bool n_ok[STATES_PER_LANE];
 #pragma unroll
@@ -442,7 +490,8 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
         const int n = w * STATES_PER_LANE + k;
         n_ok[k] = n < N;
         const int nc = n_ok[k] ? n : 0;
-        A2[k] = n_ok[k] ? f.A[(long)sd * NS + nc] * LOG2E : 0.0f;
+        An[k] = n_ok[k] ? f.A[(long)sd * NS + nc] : 0.0f;
+        A2[k] = An[k] * LOG2E;
         ag[k] = (seg == f.nseg - 1 && n_ok[k] && a.dh_last) ? a.dh_last[srow * NS + nc] : 0.0f;
         gC[k] = static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride + (long)nc * L;
     }
@@ -494,9 +543,19 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
 #pragma unroll
             for (int j = GROUP_T - 1; j >= 0; --j) {
                 const float dt = f4_get(dt4, j), dy = f4_get(dy4, j);
+                if constexpr (CPLX) {
 #pragma unroll
-                for (int k = 0; k < STATES_PER_LANE; ++k)
-                    ag[k] = exp2_fast(dt * A2[k]) * fmaf(Cg[k].get(j), dy, ag[k]);
+                    for (int k = 0; k < STATES_PER_LANE; k += 2) {
+                        const cplx ab = complex_decay(dt, A2[k], An[k + 1]);
+                        const float gr = fmaf(Cg[k].get(j), dy, ag[k]), gi = fmaf(-Cg[k + 1].get(j), dy, ag[k + 1]);
+                        ag[k] = fmaf(ab.re, gr, ab.im * gi);
+                        ag[k + 1] = fmaf(ab.re, gi, -ab.im * gr);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < STATES_PER_LANE; ++k)
+                        ag[k] = exp2_fast(dt * A2[k]) * fmaf(Cg[k].get(j), dy, ag[k]);
+                }
             }
         }
         __syncthreads();
@@ -518,15 +577,22 @@ __global__ void carry_bwd_kernel(const BwdArgs a)
     const long row = i / NPAD;
     const int n = i % NPAD, d = row % f.D;
     const float A2 = n < f.N ? f.A[(long)d * f.NS + n] * LOG2E : 0.0f;
+    // complex state: slots (n, n^1) are one state; the carry is multiplied by conj(exp(A sum_dt))
+    const bool cplx_state = f.flags & F_COMPLEX;
+    const long ip = i ^ 1;
+    const float A2r = cplx_state && (n & ~1) < f.N ? f.A[(long)d * f.NS + (n & ~1)] * LOG2E : 0.0f;
+    const float Aim = cplx_state && (n | 1) < f.N ? f.A[(long)d * f.NS + (n | 1)] : 0.0f;
     float carry = a.seg_g[(long)(f.nseg - 1) * rows * NPAD + i];  // loc of the last segment (includes dh_last)
+    float other = cplx_state ? a.seg_g[(long)(f.nseg - 1) * rows * NPAD + ip] : 0.0f;
     // as in carry_fwd_kernel: loads of a batch of segments first, then the serial chain
     constexpr int CARRY_BATCH = 16;
     for (int s0 = f.nseg - 2; s0 >= 0; s0 -= CARRY_BATCH) {
-        float loc[CARRY_BATCH], sdt[CARRY_BATCH];
+        float loc[CARRY_BATCH], locp[CARRY_BATCH], sdt[CARRY_BATCH];
 #pragma unroll
         for (int j = 0; j < CARRY_BATCH; ++j) {
             const int s = s0 - j;
             loc[j] = s >= 1 ? a.seg_g[(long)s * rows * NPAD + i] : 0.0f;   // segment 0 has no aggregate
+            locp[j] = (cplx_state && s >= 1) ? a.seg_g[(long)s * rows * NPAD + ip] : 0.0f;
             sdt[j] = s >= 1 ? f.seg_sumdt[(long)s * rows + row] : 0.0f;
         }
 #pragma unroll
@@ -534,7 +600,16 @@ __global__ void carry_bwd_kernel(const BwdArgs a)
             const int s = s0 - j;
             if (s >= 0) {
                 a.seg_g[(long)s * rows * NPAD + i] = carry;  // carry entering segment s from the right
-                carry = fmaf(exp2_fast(A2 * sdt[j]), carry, loc[j]);
+                if (cplx_state) {
+                    const cplx ab = complex_decay(sdt[j], A2r, Aim);
+                    const float re = (n & 1) ? other : carry, im = (n & 1) ? carry : other;
+                    const float nre = fmaf(ab.re, re, ab.im * im) + ((n & 1) ? locp[j] : loc[j]);
+                    const float nim = fmaf(ab.re, im, -ab.im * re) + ((n & 1) ? loc[j] : locp[j]);
+                    carry = (n & 1) ? nim : nre;
+                    other = (n & 1) ? nre : nim;
+                } else {
+                    carry = fmaf(exp2_fast(A2 * sdt[j]), carry, loc[j]);
+                }
             }
         }
     }
@@ -600,10 +675,39 @@ static int launch_scan_bwd_fixed(const BwdArgs& a, dim3 grid, hipStream_t stream
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// complex state: first-order B-bar only; selective or time-invariant B / C
+template <typename T, bool VEC, bool FULLN, int BCFIX>
+static int launch_scan_bwd_complex(const BwdArgs& a, dim3 grid, hipStream_t stream)
+{
+    static bool configured = false;  // raising the dynamic LDS limit is needed once per kernel
+    auto kern = scan_bwd_kernel<T, VEC, FULLN, false, BCFIX, true>;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)sizeof(BwdSmem)) != hipSuccess)
+            return -1;
+        configured = true;
+    }
+    if (a.f.nseg > 1) {   // only with selective B and C (the planner does not split the others)
+        adjoint_agg_kernel<T, VEC, FULLN, true><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
+        const long n = (long)a.f.B * a.f.D * NPAD;
+        carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    }
+    kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH>
 static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
     const int bcfix = ((a.f.flags & F_B_FIXED) ? 1 : 0) | ((a.f.flags & F_C_FIXED) ? 2 : 0);
+    if constexpr (!ZOH) {
+        if (a.f.flags & F_COMPLEX) {
+            if (bcfix == 0) return launch_scan_bwd_complex<T, VEC, FULLN, 0>(a, grid, stream);
+            if (bcfix == 1) return launch_scan_bwd_complex<T, VEC, FULLN, 1>(a, grid, stream);
+            if (bcfix == 2) return launch_scan_bwd_complex<T, VEC, FULLN, 2>(a, grid, stream);
+            return launch_scan_bwd_complex<T, VEC, FULLN, 3>(a, grid, stream);
+        }
+    }
     if (bcfix == 1) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 1>(a, grid, stream);
     if (bcfix == 2) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 2>(a, grid, stream);
     if (bcfix == 3) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 3>(a, grid, stream);

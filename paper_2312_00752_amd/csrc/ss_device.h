@@ -91,6 +91,21 @@ __device__ __forceinline__ zoh_terms zoh_phi(float dt, float A, float invA, floa
     return r;
 }
 
+// Complex decay factor of one step, abar = exp(dt (Ar + i Ai)) = (re, im): the magnitude from
+// the exponential unit, the rotation from the hardware sine / cosine, which take their
+// argument in revolutions (the fraction is taken first; they are specified for |x| <= 256).
+struct cplx { float re, im; };
+constexpr float INV_2PI = 0.15915494309189535f;
+__device__ __forceinline__ cplx complex_decay(float dt, float Ar_log2e, float Ai)
+{
+    const float mag = exp2_fast(dt * Ar_log2e);
+    const float rev = __builtin_amdgcn_fractf(dt * Ai * INV_2PI);
+    cplx r;
+    r.re = mag * __builtin_amdgcn_cosf(rev);
+    r.im = mag * __builtin_amdgcn_sinf(rev);
+    return r;
+}
+
 __device__ __forceinline__ float sigmoid_fast(float z)
 {
     return rcp_fast(1.0f + exp2_fast(-z * LOG2E));

@@ -24,7 +24,9 @@ namespace ss {
 // dt*u then carries u, and each state multiplies it by phi(dt, A) = (abar - 1) / A.
 // BCFIX: bit 0 / bit 1 set when B / C is the time-invariant (D,N) float32 parameter of
 // Algorithm 1 instead of the selective (B,N,L) tensor: it then sits in registers like A.
-template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0>
+// CPLX: the lane's four state slots are two complex states (re, im) each (Section 3.6); only
+// the recurrence and the read-out differ, everything around them sees 2N real "states".
+template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -161,13 +163,30 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             for (int j = 0; j < GROUP_T; ++j) {
                 const float dt = f4_get(dt4, j), du = f4_get(du4, j);
                 float y = 0.0f;
+                if constexpr (CPLX) {
 #pragma unroll
-                for (int k = 0; k < STATES_PER_LANE; ++k) {
-                    const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
-                    float bu = du * (BFIX ? Bf[k] : Bg[cur][k].get(j));
-                    if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
-                    h[k] = fmaf(abar, h[k], bu);                                 // Eq. 2a
-                    if (!AGG) y = fmaf(CFIX ? Cf[k] : Cg[cur][k].get(j), h[k], y);  // Eq. 2b
+                    for (int k = 0; k < STATES_PER_LANE; k += 2) {
+                        const cplx ab = complex_decay(dt, A2[k], An[k + 1]);         // Eq. 4 over C
+                        const float br = du * (BFIX ? Bf[k] : Bg[cur][k].get(j));
+                        const float bi = du * (BFIX ? Bf[k + 1] : Bg[cur][k + 1].get(j));
+                        const float hr = fmaf(ab.re, h[k], fmaf(-ab.im, h[k + 1], br));  // Eq. 2a over C
+                        const float hi = fmaf(ab.im, h[k], fmaf(ab.re, h[k + 1], bi));
+                        h[k] = hr;
+                        h[k + 1] = hi;
+                        if (!AGG) {                                                  // Re(C h)
+                            y = fmaf(CFIX ? Cf[k] : Cg[cur][k].get(j), hr, y);
+                            y = fmaf(-(CFIX ? Cf[k + 1] : Cg[cur][k + 1].get(j)), hi, y);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < STATES_PER_LANE; ++k) {
+                        const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
+                        float bu = du * (BFIX ? Bf[k] : Bg[cur][k].get(j));
+                        if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
+                        h[k] = fmaf(abar, h[k], bu);                                 // Eq. 2a
+                        if (!AGG) y = fmaf(CFIX ? Cf[k] : Cg[cur][k].get(j), h[k], y);  // Eq. 2b
+                    }
                 }
                 yp[j] = y;
             }
@@ -232,16 +251,24 @@ __global__ void carry_fwd_kernel(const FwdArgs a)
     const long row = i / NPAD;
     const int n = i % NPAD, d = row % a.D;
     const float A2 = n < a.N ? a.A[(long)d * a.NS + n] * LOG2E : 0.0f;
+    // complex state: slots (n, n^1) are (re, im) of one state; the thread carries both parts
+    // and writes its own (slot n even: real part)
+    const bool cplx_state = a.flags & F_COMPLEX;
+    const long ip = i ^ 1;
+    const float A2r = cplx_state && (n & ~1) < a.N ? a.A[(long)d * a.NS + (n & ~1)] * LOG2E : 0.0f;
+    const float Aim = cplx_state && (n | 1) < a.N ? a.A[(long)d * a.NS + (n | 1)] : 0.0f;
     float carry = a.seg_h[i];  // loc[0]: already includes h0
+    float other = cplx_state ? a.seg_h[ip] : 0.0f;
     // Segments are taken CARRY_BATCH at a time: their loads do not depend on the carry, so
     // they are issued together and only the multiply-adds form the serial chain.
     constexpr int CARRY_BATCH = 16;
     for (int s0 = 1; s0 < a.nseg; s0 += CARRY_BATCH) {
-        float loc[CARRY_BATCH], sdt[CARRY_BATCH];
+        float loc[CARRY_BATCH], locp[CARRY_BATCH], sdt[CARRY_BATCH];
 #pragma unroll
         for (int j = 0; j < CARRY_BATCH; ++j) {
             const int s = s0 + j;
             loc[j] = s < a.nseg - 1 ? a.seg_h[(long)s * rows * NPAD + i] : 0.0f;   // the last segment has no aggregate
+            locp[j] = (cplx_state && s < a.nseg - 1) ? a.seg_h[(long)s * rows * NPAD + ip] : 0.0f;
             sdt[j] = s < a.nseg - 1 ? a.seg_sumdt[(long)s * rows + row] : 0.0f;
         }
 #pragma unroll
@@ -249,7 +276,16 @@ __global__ void carry_fwd_kernel(const FwdArgs a)
             const int s = s0 + j;
             if (s < a.nseg) {
                 a.seg_h[(long)s * rows * NPAD + i] = carry;  // incoming state of segment s
-                carry = fmaf(exp2_fast(A2 * sdt[j]), carry, loc[j]);
+                if (cplx_state) {
+                    const cplx ab = complex_decay(sdt[j], A2r, Aim);
+                    const float re = (n & 1) ? other : carry, im = (n & 1) ? carry : other;
+                    const float nre = fmaf(ab.re, re, -ab.im * im) + ((n & 1) ? locp[j] : loc[j]);
+                    const float nim = fmaf(ab.im, re, ab.re * im) + ((n & 1) ? loc[j] : locp[j]);
+                    carry = (n & 1) ? nim : nre;
+                    other = (n & 1) ? nre : nim;
+                } else {
+                    carry = fmaf(exp2_fast(A2 * sdt[j]), carry, loc[j]);
+                }
             }
         }
     }
@@ -319,13 +355,25 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
                 Cv[k] = !ok ? 0.0f : cfix ? static_cast<const float*>(a.C_t)[(long)d * N + n] : ld(C_t, (long)b * a.bc_stride + n);
             }
         }
+        if (a.flags & F_COMPLEX) {   // slots (0,1) and (2,3) are (re, im) of two complex states
 #pragma unroll
-        for (int k = 0; k < STATES_PER_LANE; ++k) {
-            const float abar = exp2_fast(dt2 * Av[k]);                  // Eq. 4
-            float bu = du * Bv[k];
-            if (ZOH) bu *= zoh_phi(dt, Av[k], Av[k] != 0.0f ? 1.0f / Av[k] : 0.0f, abar, false).phi;
-            hv[k] = fmaf(abar, hv[k], bu);                              // Eq. 2a
-            y = fmaf(Cv[k], hv[k], y);                                  // Eq. 2b
+            for (int k = 0; k < STATES_PER_LANE; k += 2) {
+                const cplx ab = complex_decay(dt, Av[k] * LOG2E, Av[k + 1]);
+                const float hr = fmaf(ab.re, hv[k], fmaf(-ab.im, hv[k + 1], du * Bv[k]));
+                const float hi = fmaf(ab.im, hv[k], fmaf(ab.re, hv[k + 1], du * Bv[k + 1]));
+                hv[k] = hr;
+                hv[k + 1] = hi;
+                y = fmaf(Cv[k], hr, fmaf(-Cv[k + 1], hi, y));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k) {
+                const float abar = exp2_fast(dt2 * Av[k]);                  // Eq. 4
+                float bu = du * Bv[k];
+                if (ZOH) bu *= zoh_phi(dt, Av[k], Av[k] != 0.0f ? 1.0f / Av[k] : 0.0f, abar, false).phi;
+                hv[k] = fmaf(abar, hv[k], bu);                              // Eq. 2a
+                y = fmaf(Cv[k], hv[k], y);                                  // Eq. 2b
+            }
         }
         if (row_ok) {
             if (FULLN) {
@@ -365,6 +413,20 @@ static void launch_fwd_fixed(const FwdArgs& a, hipStream_t stream)
     scan_fwd_kernel<T, VEC, FULLN, false, ZOH, BCFIX><<<dim3((unsigned)(a.B * groups), 1u), dim3(THREADS), 0, stream>>>(a);
 }
 
+// complex state: first-order B-bar only; selective or time-invariant B / C
+template <typename T, bool VEC, bool FULLN, int BCFIX>
+static void launch_fwd_complex(const FwdArgs& a, hipStream_t stream)
+{
+    const int groups = (a.D + ROWS - 1) / ROWS;
+    const dim3 block(THREADS);
+    if (a.nseg > 1) {
+        scan_fwd_kernel<T, VEC, FULLN, true, false, BCFIX, true><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
+        const long n = (long)a.B * a.D * NPAD;
+        carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    }
+    scan_fwd_kernel<T, VEC, FULLN, false, false, BCFIX, true><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH>
 static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
 {
@@ -372,6 +434,14 @@ static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
     const dim3 block(THREADS);
     // time-invariant B and/or C: never split (the planner keeps nseg == 1 for them)
     const int bcfix = ((a.flags & F_B_FIXED) ? 1 : 0) | ((a.flags & F_C_FIXED) ? 2 : 0);
+    if constexpr (!ZOH) {
+        if (a.flags & F_COMPLEX) {
+            if (bcfix == 0) return launch_fwd_complex<T, VEC, FULLN, 0>(a, stream);
+            if (bcfix == 1) return launch_fwd_complex<T, VEC, FULLN, 1>(a, stream);
+            if (bcfix == 2) return launch_fwd_complex<T, VEC, FULLN, 2>(a, stream);
+            return launch_fwd_complex<T, VEC, FULLN, 3>(a, stream);
+        }
+    }
     if (bcfix == 1) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 1>(a, stream);
     if (bcfix == 2) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 2>(a, stream);
     if (bcfix == 3) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 3>(a, stream);

@@ -14,6 +14,7 @@ enum : uint32_t {
     F_HAS_Z = SS_HAS_Z,
     F_HAS_H0 = SS_HAS_H0,
     F_EXACT_ZOH_B = SS_EXACT_ZOH_B,
+    F_COMPLEX = SS_COMPLEX_STATE,
     F_B_FIXED = SS_B_FIXED,
     F_C_FIXED = SS_C_FIXED,
 };
