@@ -152,6 +152,18 @@ def layer_bench(dev, workload, iters=20):
 
     fwd_ms = timed(lambda: B.ss_layer_fwd(*args, scratch=scratch, saved=saved, out=out))
     bwd_ms = timed(lambda: B.ss_layer_bwd(t["dout"], *args, scratch=scratch, saved=saved))
+    # forward + backward of the layer replayed from one HIP graph (no launch gaps between its ~25 kernels)
+    fb_graph_ms = None
+    if iters >= 5:
+        graph_fb = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph_fb, stream=side):
+                B.ss_layer_fwd(*args, scratch=scratch, saved=saved, out=out)
+                B.ss_layer_bwd(t["dout"], *args, scratch=scratch, saved=saved)
+        torch.cuda.current_stream().wait_stream(side)
+        fb_graph_ms = timed(graph_fb.replay)
     cf_ms = timed(lambda: B.ss_conv_fwd(t["x"], t["conv_w"], t["conv_b"], out=out))
     cb_ms = timed(lambda: B.ss_conv_bwd(t["dout"], t["x"], t["conv_w"], t["conv_b"]))
     # recurrent mode: the prompt's states, then 128 single-token steps at batch 64
@@ -181,6 +193,7 @@ def layer_bench(dev, workload, iters=20):
     tensor = nb * nd * nl * 2
     return {"workload": "selective SSM layer, batch %d, L %d, D %d, N %d, R %d, conv width 4, bf16 I/O" % (nb, nl, nd, nn, rank),
             "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "token_channels_per_s": nb * nd * nl / ((fwd_ms + bwd_ms) * 1e-3),
+            "fwd_bwd_ms_hip_graph": fb_graph_ms,
             "saved_bytes_per_token_channel": saved.numel() / (nb * nd * nl),
             "decode_us_per_token_batch64": None if dec_ms is None else dec_ms * 1e3 / 128,
             "decode_us_per_token_batch64_graph": dec_graph_us,
@@ -188,6 +201,57 @@ def layer_bench(dev, workload, iters=20):
                          "unit": "GB/s", "frac": 2 * tensor / (cf_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "conv_bwd": {"ms": cb_ms, "bound": "hbm", "achieved": 3 * tensor / (cb_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                          "unit": "GB/s", "frac": 3 * tensor / (cb_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+
+
+def variants_bench(dev, workload):
+    """The scan variants of the paper's ablations at the workload's shape: complex state, more than
+    16 states, time-invariant B / C, exact zero-order hold (forward and backward call durations, ms)."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    from paper_2312_00752_amd import workloads as wl
+    nb, nl, nd = wl.CONFIGS[workload][:3]
+    bf = torch.bfloat16
+    mk = lambda *s: torch.randn(*s, device=dev).to(bf)
+    u, dl, z, do = mk(nb, nd, nl), mk(nb, nd, nl), mk(nb, nd, nl), mk(nb, nd, nl)
+    Dk = torch.randn(nd, device=dev)
+    bias = torch.full((nd,), -4.0, device=dev)
+    out = torch.empty_like(u)
+
+    def timed(f, iters=10):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    res = {}
+    cases = [("selective_real_N16", 16, {}), ("complex_N8", 8, {"complex_state": True}),
+             ("complex_N16", 16, {"complex_state": True}), ("real_N32", 32, {}), ("real_N64", 64, {}),
+             ("time_invariant_BC_N16", 16, {"fixed": True}), ("exact_zoh_N16", 16, {"exact_zoh": True})]
+    for name, nn, opt in cases:
+        cplx = opt.get("complex_state", False)
+        fixed = opt.get("fixed", False)
+        if cplx:
+            A = torch.stack([-0.5 * torch.ones(nd, nn, device=dev),
+                             torch.arange(nn, device=dev).float().repeat(nd, 1)], -1).contiguous()   # S4D-Lin
+            Bm, Cm = mk(nb, nn, 2, nl), mk(nb, nn, 2, nl)
+        else:
+            A = -torch.arange(1, nn + 1, device=dev).float().repeat(nd, 1).contiguous()             # S4D-Real
+            Bm, Cm = (torch.randn(nd, nn, device=dev), torch.randn(nd, nn, device=dev)) if fixed else (mk(nb, nn, nl), mk(nb, nn, nl))
+        ws = torch.empty(B.ss_workspace_bytes(nb, nd, nl, nn, io_dtype=B.SS_BF16, b_fixed=fixed, c_fixed=fixed,
+                                              complex_state=cplx), dtype=torch.uint8, device=dev)
+        kw = dict(Dskip=Dk, z=z, delta_bias=bias, delta_softplus=True, complex_state=cplx,
+                  exact_zoh=opt.get("exact_zoh", False))
+        f_ms = timed(lambda: B.ss_scan_fwd(u, dl, A, Bm, Cm, out=out, workspace=ws, **kw))
+        b_ms = timed(lambda: B.ss_scan_bwd(do, u, dl, A, Bm, Cm, ws, **kw))
+        res[name] = {"fwd_ms": f_ms, "bwd_ms": b_ms}
+        del ws
+    return res
 
 
 def paper_sweep(dev):
@@ -249,6 +313,8 @@ def main():
     ap.add_argument("--no-layer", action="store_true", help="skip the timing of the layer around the scan")
     ap.add_argument("--layer-iters", type=int, default=20,
                     help="timed repetitions of each layer call (below 5 the layer's decode loop is skipped)")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the scan variants (complex state, N > 16, time-invariant B/C, exact ZOH)")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="also time the shape of the paper's own scan benchmark over L = 2^9..2^19")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -358,6 +424,8 @@ def main():
         res["decode"] = decode_bench(dev)
     if not args.no_layer and args.workload in ("mamba1p4b_layer_bf16", "mamba130m_layer_bf16"):
         res["layer"] = layer_bench(dev, args.workload, iters=args.layer_iters)
+    if args.variants:
+        res["variants"] = variants_bench(dev, args.workload)
     if args.paper_sweep:
         res["paper_sweep"] = paper_sweep(dev)
     if not args.no_cpu_baseline:

@@ -271,3 +271,25 @@ def test_time_invariant_bc_flags():
     assert _fwd(p) != B.SS_ERR_ALIGN
     p = _good_fwd(); p.Bmat = FAKE + 4
     assert _fwd(p) == B.SS_ERR_ALIGN
+
+
+def test_headers_are_plain_c():
+    """The boundary is a C ABI: every header must compile as C99 on its own."""
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                            "-I", inc, os.path.join(inc, fn)], capture_output=True, text=True)
+        assert r.returncode == 0, fn + "\n" + r.stderr
+
+
+def test_complex_state_flag():
+    # complex states count twice against the limit and exclude the exact zero-order hold
+    p = _good_fwd(); p.flags = B.SS_COMPLEX_STATE | B.SS_EXACT_ZOH_B
+    assert _fwd(p) == B.SS_ERR_UNSUPPORTED
+    p = _good_fwd(); p.flags = B.SS_COMPLEX_STATE; p.dstate = 129
+    assert _fwd(p) == B.SS_ERR_UNSUPPORTED
+    # 16 complex states are two groups of 16 slots: checkpoints double
+    one = B.ss_workspace_bytes(2, 64, 128, 16, True, B.SS_BF16, False)
+    two = B.ss_workspace_bytes(2, 64, 128, 16, True, B.SS_BF16, False, complex_state=True)
+    assert two > one and two - one == (128 // 16) * 2 * 64 * 16 * 4
