@@ -660,17 +660,27 @@ __global__ void copy_dh_kernel(const float* __restrict__ src, float* __restrict_
     if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
+// The backward kernel's LDS tiles exceed the default dynamic limit; raising it is needed once per
+// kernel and per device; `done` is the calling launcher's table for its kernel, indexed by device.
+constexpr int MAX_DEVICES = 64;
+template <typename K>
+static bool allow_backward_lds_once(K kern, bool (&done)[MAX_DEVICES])
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return false;
+    if (done[dev]) return true;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(BwdSmem)) != hipSuccess)
+        return false;
+    done[dev] = true;
+    return true;
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX>
 static int launch_scan_bwd_fixed(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
-    static bool configured = false;  // raising the dynamic LDS limit is needed once per kernel
     auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH, BCFIX>;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)sizeof(BwdSmem)) != hipSuccess)
-            return -1;
-        configured = true;
-    }
+    static bool lds_ok[MAX_DEVICES] = {};   // this launcher is instantiated once per kernel
+    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok)) return -1;
     kern<<<dim3(grid.x, 1u), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -679,14 +689,9 @@ static int launch_scan_bwd_fixed(const BwdArgs& a, dim3 grid, hipStream_t stream
 template <typename T, bool VEC, bool FULLN, int BCFIX>
 static int launch_scan_bwd_complex(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
-    static bool configured = false;  // raising the dynamic LDS limit is needed once per kernel
     auto kern = scan_bwd_kernel<T, VEC, FULLN, false, BCFIX, true>;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)sizeof(BwdSmem)) != hipSuccess)
-            return -1;
-        configured = true;
-    }
+    static bool lds_ok[MAX_DEVICES] = {};   // this launcher is instantiated once per kernel
+    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok)) return -1;
     if (a.f.nseg > 1) {   // only with selective B and C (the planner does not split the others)
         adjoint_agg_kernel<T, VEC, FULLN, true><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
         const long n = (long)a.f.B * a.f.D * NPAD;
@@ -711,14 +716,9 @@ static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
     if (bcfix == 1) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 1>(a, grid, stream);
     if (bcfix == 2) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 2>(a, grid, stream);
     if (bcfix == 3) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 3>(a, grid, stream);
-    static bool configured = false;  // raising the dynamic LDS limit is needed once per kernel
     auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH>;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)sizeof(BwdSmem)) != hipSuccess)
-            return -1;
-        configured = true;
-    }
+    static bool lds_ok[MAX_DEVICES] = {};   // this launcher is instantiated once per kernel
+    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok)) return -1;
     if (a.f.nseg > 1) {
         adjoint_agg_kernel<T, VEC, FULLN><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
         const long n = (long)a.f.B * a.f.D * NPAD;
