@@ -57,14 +57,14 @@ SegPlan plan_segments(int B, int D, int L, uint32_t flags)
     SegPlan s{1, (L + 31) / 32 * 32};
     if (s.seg_len == 0) s.seg_len = 32;
     if (flags & (SS_B_FIXED | SS_C_FIXED)) return s;   // the time-invariant variants are not split
-    if (L < 2048) return s;
+    if (L < 128) return s;
     // Pick the number of segments that the model says finishes first: the main pass over
     // wgs * nseg workgroups plus the aggregate pass over wgs * (nseg - 1) of them, which costs
     // about 0.31 of a main pass per step (measured over forward + backward).  Segments stay
-    // at least 512 steps long so that the carry kernels remain negligible.
+    // at least 64 steps long (two forward chunks).
     double best = launch_cost(wgs, s.seg_len);
     long best_n = 1;
-    const long most = L / 512 < 4096 ? L / 512 : 4096;
+    const long most = L / 64 < 4096 ? L / 64 : 4096;
     for (long want = 2; want <= most; ++want) {
         const long len = segment_length(L, want);
         const long n = (L + len - 1) / len;   // what that length really gives
