@@ -99,7 +99,10 @@ size_t ss_layer_step_scratch_bytes(const ss_layer_step_params *p);
 
 /* One token of the layer in recurrent mode (Section 2): the conv window slides by one sample,
  * the projections become (B, D) x (D, R+2N) and (B, R) x (R, D) products, and Eq. 2a/2b are
- * applied once; constant time and memory per token. */
+ * applied once; constant time and memory per token.  bf16 calls with D % 32 == 0, R % 8 == 0,
+ * R <= 256, N <= 16 and 16-byte aligned W_x, W_dt and h run on hand-written kernels only
+ * (deterministic; no backend library is loaded); other calls use the GEMM backend and can
+ * return SS_ERR_BACKEND. */
 int ss_layer_step(const ss_layer_step_params *p, void *stream);
 
 #ifdef __cplusplus

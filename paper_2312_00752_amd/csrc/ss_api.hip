@@ -318,7 +318,7 @@ int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
 }
 
 
-int step_strided(const ss_step_params* p, long bc_stride, void* stream)
+static int step_impl(const ss_step_params* p, long bc_stride, const float* P, const void* W_dt, int R, int ldp, void* stream)
 {
     if (!p) return SS_ERR_NULL;
     if (p->batch < 1 || p->dim < 1 || p->dstate < 1) return SS_ERR_SHAPE;
@@ -326,7 +326,8 @@ int step_strided(const ss_step_params* p, long bc_stride, void* stream)
     if ((p->flags & SS_COMPLEX_STATE) && (p->flags & SS_EXACT_ZOH_B)) return SS_ERR_UNSUPPORTED;
     if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
     if (p->flags & ~kStepFlags) return SS_ERR_UNSUPPORTED;
-    if (!p->h || !p->u_t || !p->delta_t || !p->B_t || !p->C_t || !p->A || !p->out_t) return SS_ERR_NULL;
+    if (!p->h || !p->u_t || !p->A || !p->out_t) return SS_ERR_NULL;
+    if (!P && (!p->delta_t || !p->B_t || !p->C_t)) return SS_ERR_NULL;
     if ((p->flags & SS_HAS_Z) && !p->z_t) return SS_ERR_NULL;
     if ((p->flags & SS_HAS_D) && !p->Dskip) return SS_ERR_NULL;
     if ((p->flags & SS_HAS_DELTA_BIAS) && !p->delta_bias) return SS_ERR_NULL;
@@ -335,17 +336,32 @@ int step_strided(const ss_step_params* p, long bc_stride, void* stream)
     const void* io[] = {p->u_t, p->delta_t, p->z_t, p->out_t};
     for (const void* q : io)
         if (q && !aligned(q, esz)) return SS_ERR_ALIGN;
-    if (!aligned(p->B_t, (p->flags & SS_B_FIXED) ? 4 : esz) || !aligned(p->C_t, (p->flags & SS_C_FIXED) ? 4 : esz))
+    if (!P && (!aligned(p->B_t, (p->flags & SS_B_FIXED) ? 4 : esz) || !aligned(p->C_t, (p->flags & SS_C_FIXED) ? 4 : esz)))
         return SS_ERR_ALIGN;
+    if (P && (!aligned(P, 16) || !aligned(W_dt, 16) || !aligned(p->h, 16) || R % 8 != 0 || ldp % 4 != 0)) return SS_ERR_ALIGN;
     const void* f32[] = {p->A, p->Dskip, p->delta_bias};
     for (const void* q : f32)
         if (q && !aligned(q, 4)) return SS_ERR_ALIGN;
     ss::StepArgs a{};
     a.B = p->batch; a.D = p->dim; a.N = slots(p); a.flags = p->flags;
     a.h = p->h; a.u_t = p->u_t; a.delta_t = p->delta_t; a.z_t = p->z_t;
-    a.B_t = p->B_t; a.C_t = p->C_t; a.bc_stride = bc_stride; a.A = p->A; a.Dskip = p->Dskip; a.bias = p->delta_bias;
+    a.B_t = P ? nullptr : p->B_t; a.C_t = P ? nullptr : p->C_t; a.bc_stride = bc_stride;
+    a.P = P; a.W_dt = W_dt; a.R = R; a.ldp = ldp; a.A = p->A; a.Dskip = p->Dskip; a.bias = p->delta_bias;
     a.out_t = p->out_t;
+    if (P) return ss::launch_step_projected(a, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
     return ss::launch_step(a, p->io_dtype, static_cast<hipStream_t>(stream)) == 0 ? SS_OK : SS_ERR_LAUNCH;
+}
+
+int step_strided(const ss_step_params* p, long bc_stride, void* stream)
+{
+    return step_impl(p, bc_stride, nullptr, nullptr, 0, 0, stream);
+}
+
+int step_projected(const ss_step_params* p, const float* P, const void* W_dt, int R, int ldp, void* stream)
+{
+    if (!P || !W_dt) return SS_ERR_NULL;
+    if (p->io_dtype != SS_BF16 || R > 256 || p->dstate > 16 || ldp > 256 + 2 * 16) return SS_ERR_UNSUPPORTED;
+    return step_impl(p, 0, P, W_dt, R, ldp, stream);
 }
 
 }  // namespace ss

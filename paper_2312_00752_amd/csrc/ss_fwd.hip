@@ -399,6 +399,174 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     }
 }
 
+// Single-token step of the layer's decode (bf16 I/O): as step_kernel, but delta_t, B_t and C_t come
+// from the float32 output P = [r; B; C] of the projection (the sum of STEP_NPARTS partial results,
+// rounded to bf16 as the layer stores it) and delta_t = W_dt r_t + bias is formed here.  A workgroup
+// owns 64 channels and a tile of 16 batch entries.  It stages the tile's rows of P in LDS; four of
+// its eight waves then form the 16 x 64 block of W_dt r_t on the matrix cores (one 16 x 16 tile per
+// wave, W_dt rows straight from global memory) and leave softplus(. + bias) in LDS, once per (b, d)
+// instead of once per quarter; after that a thread is (channel d, quarter q, half of the batch tile)
+// as in step_kernel and walks its eight batch entries.  The state, u and z of those entries are
+// requested before anything else, so that their latency overlaps the projection.  Real, first-order,
+// selective B / C only; R <= 256 and a multiple of 8, N <= 16.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+constexpr int SP_BT = 16;                         // batch entries per workgroup: the rows of the MFMA tile
+constexpr int SP_THREADS = 512;                   // 64 channels x 4 quarters x 2 halves of the batch tile
+constexpr int SP_PER = SP_BT / 2;                 // batch entries per thread
+constexpr int STEP_MAX_LDP = 256 + 2 * NPAD;      // R <= 256 and N <= 16 on this path
+constexpr int SP_LDP = STEP_MAX_LDP + 4;          // row stride of the staged P in floats: 16-byte rows, off the banks
+
+template <bool FULLN>
+__global__ void __launch_bounds__(SP_THREADS) step_proj_kernel(const StepArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float s_p[SP_BT][SP_LDP];
+    __shared__ float s_dt[SP_BT][64];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = tid & 3, dl = (tid >> 2) & 63, half = tid >> 8;
+    const int d0 = blockIdx.x * 64;
+    const bool d_ok = d0 + dl < a.D;
+    const int d = d_ok ? d0 + dl : a.D - 1;
+    const int N = a.N, R = a.R;
+    const int b0 = blockIdx.y * SP_BT;
+    const int nbt = min(SP_BT, a.B - b0);            // batch entries of this tile
+    const bf16_t* u_t = static_cast<const bf16_t*>(a.u_t);
+    const bf16_t* z_t = static_cast<const bf16_t*>(a.z_t);
+    auto as_stored = [](float v) -> float { return bf16_to_f32(bf16_t(f32_to_bf16_bits(v))); };
+
+    const int sq = q * STATES_PER_LANE;               // this quarter's first state
+    float hv[SP_PER][STATES_PER_LANE], ub[SP_PER], zb[SP_PER];
+#pragma unroll
+    for (int i = 0; i < SP_PER; ++i) {
+        const int b = min(b0 + half * SP_PER + i, a.B - 1);
+        const long row = (long)b * a.D + d;
+        const float* hp = a.h + row * N + sq;
+        if constexpr (FULLN) {
+            const float4 h4 = *reinterpret_cast<const float4*>(hp);
+            hv[i][0] = h4.x; hv[i][1] = h4.y; hv[i][2] = h4.z; hv[i][3] = h4.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k) hv[i][k] = (sq + k < N) ? hp[k] : 0.0f;
+        }
+        ub[i] = bf16_to_f32(u_t[row]);
+        zb[i] = (a.flags & F_HAS_Z) ? bf16_to_f32(z_t[row]) : 0.0f;
+    }
+    float Av[STATES_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < STATES_PER_LANE; ++k) Av[k] = (sq + k < N) ? a.A[(long)d * N + sq + k] * LOG2E : 0.0f;
+    const float Dsk = (a.flags & F_HAS_D) ? a.Dskip[d] : 0.0f;
+
+    {
+        // P of the tile: all loads first (STEP_NPARTS x STAGE_ITEMS per thread, independent), then
+        // the parts added in a fixed order and rounded as stored
+        constexpr int STAGE_ITEMS = (SP_BT * STEP_MAX_LDP + SP_THREADS - 1) / SP_THREADS;
+        const long part = (long)a.B * a.ldp;   // floats between partial results
+        const int count = nbt * a.ldp;
+        float v[STAGE_ITEMS][STEP_NPARTS];
+#pragma unroll
+        for (int j = 0; j < STAGE_ITEMS; ++j) {
+            const int i = tid + SP_THREADS * j;
+            const long g = (long)b0 * a.ldp + min(i, count - 1);
+#pragma unroll
+            for (int k = 0; k < STEP_NPARTS; ++k) v[j][k] = a.P[k * part + g];
+        }
+#pragma unroll
+        for (int j = 0; j < STAGE_ITEMS; ++j) {
+            const int i = tid + SP_THREADS * j;
+            float s = v[j][0];
+#pragma unroll
+            for (int k = 1; k < STEP_NPARTS; ++k) s += v[j][k];
+            if (i < count) s_p[i / a.ldp][i % a.ldp] = as_stored(s);
+        }
+    }
+    __syncthreads();
+
+    if (wave < 4) {
+        // tile (batch entries) x (channels d0 + 16 * wave ..+15) of r W_dt^T.  Operand layout of the
+        // 16x16x32 bf16 MFMA: lane l holds row (column) l % 16 of the first (second) operand at
+        // contraction indices 8 * (l / 16) ..+7; accumulator element i of lane l is row
+        // 4 * (l / 16) + i, column l % 16.
+        const int arow = min(lane & 15, nbt - 1);             // rows past the end shadow the last one
+        const int dcol = 16 * wave + (lane & 15);
+        const int wrow = min(d0 + dcol, a.D - 1);
+        const int ksub = 8 * (lane >> 4);
+        const bf16_t* wp = static_cast<const bf16_t*>(a.W_dt) + (long)wrow * R + ksub;
+        const float* pp = &s_p[arow][ksub];
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < R; k += 32) {
+            union { unsigned short s[8]; bf16x8_t v; } av, bv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { av.s[e] = 0; bv.s[e] = 0; }
+            if (k + ksub < R) {                               // R is a multiple of 8
+                const float4 p0 = *reinterpret_cast<const float4*>(pp + k);
+                const float4 p1 = *reinterpret_cast<const float4*>(pp + k + 4);
+                const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) av.s[e] = (unsigned short)(__float_as_uint(pv[e]) >> 16);   // exact: rounded above
+                bv.v = *reinterpret_cast<const bf16x8_t*>(wp + k);
+            }
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.v, bv.v, acc, 0, 0, 0);
+        }
+        const float bias = (a.flags & F_HAS_DELTA_BIAS) ? a.bias[wrow] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float x = as_stored(acc[i]) + bias, dt = x, sg;
+            if (a.flags & F_DELTA_SOFTPLUS) softplus_sigmoid(x, dt, sg);
+            s_dt[4 * (lane >> 4) + i][dcol] = dt;
+        }
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int i = 0; i < SP_PER; ++i) {
+        const int bl = half * SP_PER + i;
+        if (bl >= nbt) break;
+        const long row = (long)(b0 + bl) * a.D + d;
+        const float* pb = s_p[bl];
+        const float dt = s_dt[bl][dl];
+        const float u = ub[i];
+        const float du = dt * u;
+        float Bq[STATES_PER_LANE], Cq[STATES_PER_LANE];
+        if constexpr (FULLN) {
+            const float4 b4 = *reinterpret_cast<const float4*>(pb + R + sq);
+            const float4 c4 = *reinterpret_cast<const float4*>(pb + R + NPAD + sq);
+            Bq[0] = b4.x; Bq[1] = b4.y; Bq[2] = b4.z; Bq[3] = b4.w;
+            Cq[0] = c4.x; Cq[1] = c4.y; Cq[2] = c4.z; Cq[3] = c4.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k) {
+                const bool ok = sq + k < N;
+                Bq[k] = ok ? pb[R + sq + k] : 0.0f;
+                Cq[k] = ok ? pb[R + N + sq + k] : 0.0f;
+            }
+        }
+        float y = 0.0f;
+#pragma unroll
+        for (int k = 0; k < STATES_PER_LANE; ++k) {
+            const float abar = exp2_fast(dt * Av[k]);          // Eq. 4
+            hv[i][k] = fmaf(abar, hv[i][k], du * Bq[k]);       // Eq. 2a
+            y = fmaf(Cq[k], hv[i][k], y);                      // Eq. 2b
+        }
+        if (d_ok) {
+            float* hp = a.h + row * N + sq;
+            if constexpr (FULLN) {
+                *reinterpret_cast<float4*>(hp) = make_float4(hv[i][0], hv[i][1], hv[i][2], hv[i][3]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < STATES_PER_LANE; ++k)
+                    if (sq + k < N) hp[k] = hv[i][k];
+            }
+        }
+        y += __shfl_xor(y, 1);
+        y += __shfl_xor(y, 2);
+        y = fmaf(Dsk, u, y);
+        if (a.flags & F_HAS_Z) y *= zb[i] * sigmoid_fast(zb[i]);
+        if (d_ok && q == 0) static_cast<bf16_t*>(a.out_t)[row] = bf16_t(f32_to_bf16_bits(y));
+    }
+}
+
 // h_last for an empty sequence: h0 or zero
 __global__ void copy_state_kernel(const float* __restrict__ src, float* __restrict__ dst, long n)
 {
@@ -505,6 +673,14 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
         else { if (zoh) SS_LAUNCH_STEP(bf16_t, false, true); else SS_LAUNCH_STEP(bf16_t, false, false); }
     }
 #undef SS_LAUNCH_STEP
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_step_projected(const StepArgs& a, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((a.D + 63) / 64), (unsigned)((a.B + SP_BT - 1) / SP_BT));
+    if (a.N == NPAD) step_proj_kernel<true><<<grid, dim3(SP_THREADS), 0, stream>>>(a);
+    else step_proj_kernel<false><<<grid, dim3(SP_THREADS), 0, stream>>>(a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

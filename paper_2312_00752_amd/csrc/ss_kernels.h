@@ -59,12 +59,21 @@ struct BwdArgs {
     float *dA, *dD, *dbias;     // final outputs of the reduction kernel
 };
 
+constexpr int STEP_NPARTS = 4;   // partial results the layer's decode projection leaves for the step kernel
+
 struct StepArgs {
     int B, D, N;   // N: all states (the step kernels loop over them; no groups)
     uint32_t flags;
     float* h;
     const void *u_t, *delta_t, *z_t, *B_t, *C_t;
     long bc_stride;  // elements between consecutive batch rows of B_t and C_t (N when dense)
+    // Layer decode: instead of delta_t, B_t, C_t the kernel takes the float32 projection output
+    // P (B, ldp) = [r (R); B (N); C (N)], given as the sum of STEP_NPARTS partial results B * ldp
+    // floats apart, and W_dt (D, R) in the io dtype; it adds the parts, rounds to the io dtype (the
+    // layer stores its projection so) and forms delta_t = W_dt r itself.  Null: not used.
+    const float* P;
+    const void* W_dt;
+    int R, ldp;
     const float *A, *Dskip, *bias;
     void* out_t;
 };
@@ -73,6 +82,7 @@ struct StepArgs {
 int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream);
 int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream);
 int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream);
+int launch_step_projected(const StepArgs& a, hipStream_t stream);   // bf16 I/O only
 
 // The public scan entry points with one extra degree of freedom: B and C of batch entry b
 // start b * bc_bstride elements after Bmat / Cmat (the public calls pass dstate * seqlen).
@@ -82,4 +92,7 @@ int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream);
 // ss_step with B_t / C_t rows bc_stride elements apart (the public call passes dstate).
 int step_strided(const ss_step_params* p, long bc_stride, void* stream);
 
+// ss_step for the layer's decode: delta_t, B_t, C_t come from the float32 projection output
+// P (B, ldp) = [r; B; C] and W_dt (D, R) (see StepArgs); p's delta_t, B_t, C_t are ignored.
+int step_projected(const ss_step_params* p, const float* P, const void* W_dt, int R, int ldp, void* stream);
 }  // namespace ss

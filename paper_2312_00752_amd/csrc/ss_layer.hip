@@ -111,6 +111,68 @@ __global__ void sum_partials_kernel(const T* __restrict__ part, int nb, long n, 
     out[i] = acc;
 }
 
+// ---- decode: [r;B;C]_t = u_t @ W_x^T on the matrix cores --------------------------------------------
+// P (nb, nm) float32 = u (nb, D) @ W (nm, D)^T, both operands bf16 with the contraction index
+// contiguous, which is exactly how v_mfma_f32_16x16x32_bf16 wants its fragments: lane l supplies row
+// l % 16 of either operand and the 8 consecutive k starting at 8 * (l / 16), one 16-byte load each, no
+// staging.  The product is tiny (64 x 160 x 4096 for the headline layer) and bound by the latency of
+// getting W and u on chip, so it is spread thin: workgroup (x, y, z) owns the 16 x 16 tile (x, y) of P
+// over the z-th part of the contraction index and spreads that part over its eight waves (k-steps of
+// 32, four per wave); the waves' accumulators are added through LDS in a fixed order and written to
+// the z-th partial result, P + z * nb * nm.  The consumer adds the few partial results, again in a
+// fixed order, so the outcome does not depend on timing (atomics across workgroups would make it
+// so).  Requires D % 32 == 0.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+constexpr int XP_WAVES = 8;
+constexpr int XP_NPARTS = ss::STEP_NPARTS;   // partial results (fixed, so that the consumer can unroll over them)
+
+__global__ void __launch_bounds__(64 * XP_WAVES) xproj_decode_kernel(const ss::bf16_t* __restrict__ u,
+                                                                     const ss::bf16_t* __restrict__ W,
+                                                                     float* __restrict__ P, int nb, int nm, int D)
+{
+    __shared__ f32x4_t part[XP_WAVES - 1][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int row0 = blockIdx.x * 16, col0 = blockIdx.y * 16;   // tile of P; its columns are rows of W
+    const int urow = min(row0 + (lane & 15), nb - 1);           // rows past the end shadow the last one
+    const int wrow = min(col0 + (lane & 15), nm - 1);
+    const int ksub = 8 * (lane >> 4);
+    const ss::bf16_t* up = u + (size_t)urow * D + ksub;
+    const ss::bf16_t* wp = W + (size_t)wrow * D + ksub;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int STRIDE = 32 * XP_WAVES;
+    const int kpart = ((D + XP_NPARTS - 1) / XP_NPARTS + 31) / 32 * 32;   // contraction elements per part
+    const int kend = min(D, (int)(blockIdx.z + 1) * kpart);
+    int k = blockIdx.z * kpart + 32 * wave;
+    for (; k + 3 * STRIDE < kend; k += 4 * STRIDE) {   // four k-steps' loads in flight together
+        bf16x8_t a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i] = *reinterpret_cast<const bf16x8_t*>(up + k + i * STRIDE);
+            b[i] = *reinterpret_cast<const bf16x8_t*>(wp + k + i * STRIDE);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[i], acc, 0, 0, 0);
+    }
+    for (; k < kend; k += STRIDE)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(up + k),
+                                                     *reinterpret_cast<const bf16x8_t*>(wp + k), acc, 0, 0, 0);
+    if (wave > 0) part[wave - 1][lane] = acc;
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < XP_WAVES - 1; ++w) acc += part[w][lane];
+        // accumulator element r of lane l is row 4 * (l / 16) + r, column l % 16 of the tile
+        const int col = col0 + (lane & 15);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + 4 * (lane >> 4) + r;
+            if (row < nb && col < nm) P[((size_t)blockIdx.z * nb + row) * nm + col] = acc[r];
+        }
+    }
+}
+
 // ---- buffers -------------------------------------------------------------------------------------
 struct Shape {
     size_t B, D, L, N, R, Mx, esz;
@@ -382,7 +444,8 @@ size_t ss_layer_step_scratch_bytes(const ss_layer_step_params* p)
     if (!p || p->batch < 1 || p->dim < 1 || p->dstate < 1 || p->dt_rank < 1) return 0;
     const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
     const size_t B = p->batch, D = p->dim, Mx = (size_t)p->dt_rank + 2 * (size_t)p->dstate;
-    return 2 * round_up(B * D * esz, 256) + round_up(B * Mx * esz, 256);   // u_t, delta_t, [r;B;C]_t
+    // u_t, delta_t, [r;B;C]_t in the io dtype, and the float32 partial results of the bf16 path's projection
+    return 2 * round_up(B * D * esz, 256) + round_up(B * Mx * esz, 256) + round_up(XP_NPARTS * B * Mx * sizeof(float), 256);
 }
 
 int ss_layer_step(const ss_layer_step_params* p, void* stream)
@@ -399,8 +462,6 @@ int ss_layer_step(const ss_layer_step_params* p, void* stream)
     if (!p->scratch || p->scratch_bytes < ss_layer_step_scratch_bytes(p)) return SS_ERR_WORKSPACE;
     if (!aligned_to(p->scratch, 256)) return SS_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rocblas_handle h = blas_handle(st);
-    if (!h) return SS_ERR_BACKEND;
     const bool bf16 = p->io_dtype == SS_BF16;
     const size_t esz = bf16 ? 2 : 4;
     const int B = p->batch, D = p->dim, N = p->dstate, R = p->dt_rank, Mx = R + 2 * N;
@@ -409,23 +470,43 @@ int ss_layer_step(const ss_layer_step_params* p, void* stream)
     char* delta_t = u_t + round_up((size_t)B * D * esz, 256);
     char* P_t = delta_t + round_up((size_t)B * D * esz, 256);
 
+    float* P_acc = reinterpret_cast<float*>(P_t + round_up((size_t)B * Mx * esz, 256));
+
     ss_conv_step_params c{};
     c.batch = B; c.dim = D; c.width = p->conv_width; c.io_dtype = p->io_dtype;
     c.flags = SS_CONV_SILU | SS_CONV_HAS_BIAS;
     c.state = p->conv_state; c.x_t = p->x_t; c.w = p->conv_w; c.bias = p->conv_b; c.out_t = u_t;
+    ss_step_params s{};
+    s.batch = B; s.dim = D; s.dstate = N; s.io_dtype = p->io_dtype;
+    s.flags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z;
+    s.h = p->h; s.u_t = u_t; s.z_t = p->z_t;
+    s.A = p->A; s.Dskip = p->Dskip; s.delta_bias = p->dt_bias;
+    s.out_t = p->out_t;
+
+    // bf16 with friendly sizes: both projections on the matrix cores, delta_t = W_dt r_t inside the
+    // state-update kernel -- three launches, no library call, no atomics
+    auto aligned16 = [](const void* q) { return reinterpret_cast<uintptr_t>(q) % 16 == 0; };
+    if (bf16 && D % 32 == 0 && R % 8 == 0 && R <= 256 && N <= 16 && Mx % 4 == 0 && aligned16(p->W_x) && aligned16(p->W_dt) &&
+        aligned16(p->h)) {
+        int rc = ss_conv_step(&c, stream);
+        if (rc != SS_OK) return rc;
+        const dim3 grid((unsigned)((B + 15) / 16), (unsigned)((Mx + 15) / 16), (unsigned)XP_NPARTS);
+        hipLaunchKernelGGL(xproj_decode_kernel, grid, dim3(64 * XP_WAVES), 0, st, reinterpret_cast<const ss::bf16_t*>(u_t),
+                           static_cast<const ss::bf16_t*>(p->W_x), P_acc, B, Mx, D);
+        if (hipGetLastError() != hipSuccess) return SS_ERR_LAUNCH;
+        return ss::step_projected(&s, P_acc, p->W_dt, R, Mx, stream);
+    }
+
+    rocblas_handle h = blas_handle(st);
+    if (!h) return SS_ERR_BACKEND;
     int rc = ss_conv_step(&c, stream);
     if (rc != SS_OK) return rc;
     // [r;B;C]_t (B, Mx) = u_t (B, D) @ W_x^T;   delta_t (B, D) = r_t (B, R) @ W_dt^T
     if (!gemm_rm(h, false, true, B, Mx, D, u_t, D, 0, p->W_x, D, 0, 0.0f, P_t, Mx, 0, 1, bf16)) return SS_ERR_BACKEND;
     if (!gemm_rm(h, false, true, B, D, R, P_t, Mx, 0, p->W_dt, R, 0, 0.0f, delta_t, D, 0, 1, bf16)) return SS_ERR_BACKEND;
-    ss_step_params s{};
-    s.batch = B; s.dim = D; s.dstate = N; s.io_dtype = p->io_dtype;
-    s.flags = SS_DELTA_SOFTPLUS | SS_HAS_DELTA_BIAS | SS_HAS_D | SS_HAS_Z;
-    s.h = p->h; s.u_t = u_t; s.delta_t = delta_t; s.z_t = p->z_t;
+    s.delta_t = delta_t;
     s.B_t = P_t + (size_t)R * esz;
     s.C_t = P_t + (size_t)(R + N) * esz;
-    s.A = p->A; s.Dskip = p->Dskip; s.delta_bias = p->dt_bias;
-    s.out_t = p->out_t;
     return ss::step_strided(&s, Mx, stream);
 }
 
