@@ -415,6 +415,7 @@ constexpr int SP_BT = 16;                         // batch entries per workgroup
 constexpr int SP_THREADS = 512;                   // 64 channels x 4 quarters x 2 halves of the batch tile
 constexpr int SP_PER = SP_BT / 2;                 // batch entries per thread
 constexpr int STEP_MAX_LDP = 256 + 2 * NPAD;      // R <= 256 and N <= 16 on this path
+constexpr int SP_MAX_KSTEPS = 256 / 32;             // contraction steps of the delta projection (R <= 256)
 constexpr int SP_LDP = STEP_MAX_LDP + 4;          // row stride of the staged P in floats: 16-byte rows, off the banks
 
 template <bool FULLN>
@@ -458,6 +459,26 @@ __global__ void __launch_bounds__(SP_THREADS) step_proj_kernel(const StepArgs a)
     for (int k = 0; k < STATES_PER_LANE; ++k) Av[k] = (sq + k < N) ? a.A[(long)d * N + sq + k] * LOG2E : 0.0f;
     const float Dsk = (a.flags & F_HAS_D) ? a.Dskip[d] : 0.0f;
 
+    // Waves 0-3 form the tile (batch entries) x (channels d0 + 16 * wave ..+15) of r W_dt^T after
+    // the staging below.  Operand layout of the 16x16x32 bf16 MFMA: lane l holds row (column)
+    // l % 16 of the first (second) operand at contraction indices 8 * (l / 16) ..+7; accumulator
+    // element i of lane l is row 4 * (l / 16) + i, column l % 16.  Their pieces of W_dt are
+    // requested now, with everything else.
+    const int dcol = 16 * (wave & 3) + (lane & 15);
+    const int wrow = min(d0 + dcol, a.D - 1);
+    const int ksub = 8 * (lane >> 4);
+    union WFrag { unsigned short s[8]; bf16x8_t v; } wfrag[SP_MAX_KSTEPS];
+    const float bias = (a.flags & F_HAS_DELTA_BIAS) ? a.bias[wrow] : 0.0f;
+    if (wave < 4) {
+        const bf16_t* wp = static_cast<const bf16_t*>(a.W_dt) + (long)wrow * R + ksub;
+#pragma unroll
+        for (int i = 0; i < SP_MAX_KSTEPS; ++i) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wfrag[i].s[e] = 0;
+            if (32 * i + ksub < R) wfrag[i].v = *reinterpret_cast<const bf16x8_t*>(wp + 32 * i);
+        }
+    }
+
     {
         // P of the tile: all loads first (STEP_NPARTS x STAGE_ITEMS per thread, independent), then
         // the parts added in a fixed order and rounded as stored
@@ -484,32 +505,26 @@ __global__ void __launch_bounds__(SP_THREADS) step_proj_kernel(const StepArgs a)
     __syncthreads();
 
     if (wave < 4) {
-        // tile (batch entries) x (channels d0 + 16 * wave ..+15) of r W_dt^T.  Operand layout of the
-        // 16x16x32 bf16 MFMA: lane l holds row (column) l % 16 of the first (second) operand at
-        // contraction indices 8 * (l / 16) ..+7; accumulator element i of lane l is row
-        // 4 * (l / 16) + i, column l % 16.
         const int arow = min(lane & 15, nbt - 1);             // rows past the end shadow the last one
-        const int dcol = 16 * wave + (lane & 15);
-        const int wrow = min(d0 + dcol, a.D - 1);
-        const int ksub = 8 * (lane >> 4);
-        const bf16_t* wp = static_cast<const bf16_t*>(a.W_dt) + (long)wrow * R + ksub;
         const float* pp = &s_p[arow][ksub];
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        for (int k = 0; k < R; k += 32) {
-            union { unsigned short s[8]; bf16x8_t v; } av, bv;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { av.s[e] = 0; bv.s[e] = 0; }
-            if (k + ksub < R) {                               // R is a multiple of 8
-                const float4 p0 = *reinterpret_cast<const float4*>(pp + k);
-                const float4 p1 = *reinterpret_cast<const float4*>(pp + k + 4);
-                const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        for (int i = 0; i < SP_MAX_KSTEPS; ++i) {
+            const int k = 32 * i;
+            if (k < R) {                                      // uniform
+                union { unsigned short s[8]; bf16x8_t v; } av;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) av.s[e] = (unsigned short)(__float_as_uint(pv[e]) >> 16);   // exact: rounded above
-                bv.v = *reinterpret_cast<const bf16x8_t*>(wp + k);
+                for (int e = 0; e < 8; ++e) av.s[e] = 0;
+                if (k + ksub < R) {                           // R is a multiple of 8
+                    const float4 p0 = *reinterpret_cast<const float4*>(pp + k);
+                    const float4 p1 = *reinterpret_cast<const float4*>(pp + k + 4);
+                    const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) av.s[e] = (unsigned short)(__float_as_uint(pv[e]) >> 16);   // exact: rounded above
+                }
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.v, wfrag[i].v, acc, 0, 0, 0);
             }
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.v, bv.v, acc, 0, 0, 0);
         }
-        const float bias = (a.flags & F_HAS_DELTA_BIAS) ? a.bias[wrow] : 0.0f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float x = as_stored(acc[i]) + bias, dt = x, sg;
