@@ -302,6 +302,69 @@ def paper_sweep(dev):
     return {"workload": "batch 1, D 1024, N 16, bf16 I/O", "rows": rows}
 
 
+def generation_sweep(dev):
+    """The paper's generation setting (Section 4.5 / Appendix E.5: prompt of 2048 tokens, 128
+    generated tokens, batch 1 .. 128) for ONE selective SSM layer of the 1.4B shape: the prompt in
+    parallel mode (states handed over), then 128 single-token steps replayed from a HIP graph."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    from paper_2312_00752_amd import workloads as wl
+    nd, nn, prompt, gen_tokens = 4096, 16, 2048, 128
+    rank = wl.layer_rank(nd)
+    bf = torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    rn = lambda *shape: torch.randn(*shape, device=dev, generator=gen)
+    conv_w, conv_b = rn(nd, 4) * 0.5, rn(nd) * 0.1
+    W_x = (rn(rank + 2 * nn, nd) / nd ** 0.5).to(bf)
+    W_dt = (rn(nd, rank) / rank ** 0.5).to(bf)
+    dt_bias = torch.full((nd,), -4.0, device=dev)
+    A = -torch.arange(1, nn + 1, device=dev, dtype=torch.float32).repeat(nd, 1).contiguous()
+    Dk = torch.ones(nd, device=dev)
+    weights = [conv_w, conv_b, W_x, W_dt, dt_bias, A, Dk]
+    rows = []
+    for nb in (1, 2, 4, 8, 16, 32, 64, 128):
+        x, z = rn(nb, nd, prompt).to(bf), rn(nb, nd, prompt).to(bf)
+        xs, zs = rn(8, nb, nd).to(bf), rn(8, nb, nd).to(bf)
+        scratch = torch.empty(B.ss_layer_scratch_bytes(nb, nd, prompt, nn, rank, for_backward=False), dtype=torch.uint8, device=dev)
+        sscr = torch.empty(B.ss_layer_step_scratch_bytes(nb, nd, nn, rank), dtype=torch.uint8, device=dev)
+        out = torch.empty_like(x)
+        h = torch.zeros(nb, nd, nn, device=dev)
+        cs = torch.zeros(nb, nd, 3, device=dev, dtype=bf)
+        o_t = torch.empty(nb, nd, device=dev, dtype=bf)
+
+        def prefill():
+            B.ss_layer_fwd(x, z, *weights, scratch=scratch, out=out, return_states=True, h_last=h, conv_state=cs)
+
+        def decode():
+            for i in range(gen_tokens):
+                B.ss_layer_step(h, cs, xs[i % 8], zs[i % 8], *weights, scratch=sscr, out_t=o_t)
+        prefill(); decode()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                decode()
+        torch.cuda.current_stream().wait_stream(side)
+        it = 5
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        for _ in range(it):
+            prefill()
+        ev[1].record()
+        for _ in range(it):
+            graph.replay()
+        ev[2].record()
+        torch.cuda.synchronize()
+        pre_ms, dec_ms = ev[0].elapsed_time(ev[1]) / it, ev[1].elapsed_time(ev[2]) / it
+        rows.append({"batch": nb, "prompt_ms": pre_ms, "decode_us_per_token": dec_ms * 1e3 / gen_tokens,
+                     "generated_tokens_per_s_per_layer": nb * gen_tokens / ((pre_ms + dec_ms) * 1e-3)})
+        del x, z, out, scratch
+    return {"workload": "one layer, D 4096, N 16, R %d, bf16 I/O; prompt 2048 + 128 generated tokens" % rank, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -428,6 +491,7 @@ def main():
         res["variants"] = variants_bench(dev, args.workload)
     if args.paper_sweep:
         res["paper_sweep"] = paper_sweep(dev)
+        res["generation_sweep"] = generation_sweep(dev)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, sample_dim=nd)
     print(json.dumps(res))

@@ -471,20 +471,22 @@ def _layer_params(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, saved, scr
 
 
 def ss_layer_fwd(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scratch, saved=None, out=None,
-                 return_states=False, stream=None):
+                 return_states=False, stream=None, h_last=None, conv_state=None):
     """Enqueue the layer's forward pass; ``saved`` (if given) is filled for ``ss_layer_bwd``.
-    Returns out, or (out, h_last, conv_state) with ``return_states``."""
+    Returns out, or (out, h_last, conv_state) with ``return_states`` (written into the caller's
+    ``h_last`` (B,D,N) float32 and ``conv_state`` (B,D,W-1) tensors if given)."""
     import torch
     p = _layer_params(x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, saved, scratch)
     if out is None:
         out = torch.empty_like(x)
     p.out = _ptr(out, x.dtype, x.shape, "out")
-    h_last = conv_state = None
     if return_states:
-        h_last = torch.empty((p.batch, p.dim, p.dstate), dtype=torch.float32, device=x.device)
-        conv_state = torch.empty((p.batch, p.dim, p.conv_width - 1), dtype=x.dtype, device=x.device)
-        p.h_last = _ptr(h_last, None, None, "h_last")
-        p.conv_state = _ptr(conv_state, None, None, "conv_state")
+        if h_last is None:
+            h_last = torch.empty((p.batch, p.dim, p.dstate), dtype=torch.float32, device=x.device)
+        if conv_state is None:
+            conv_state = torch.empty((p.batch, p.dim, p.conv_width - 1), dtype=x.dtype, device=x.device)
+        p.h_last = _ptr(h_last, torch.float32, (p.batch, p.dim, p.dstate), "h_last")
+        p.conv_state = _ptr(conv_state, x.dtype, (p.batch, p.dim, p.conv_width - 1), "conv_state")
     rc = lib().ss_layer_fwd(ctypes.byref(p), _stream(stream))
     if rc != SS_OK:
         raise SsError(rc)
