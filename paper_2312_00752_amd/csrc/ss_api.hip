@@ -86,10 +86,19 @@ SegPlan plan_segments(int B, int D, int L, uint32_t flags)
 //                  [seg_h][seg_sumdt][float seg_g nseg*B*D*16]                 (only when split)
 //                  [float dA partials nseg*B*D*16][float dD partials nseg*B*D][float dbias partials nseg*B*D]
 //                  [float dB partials B*D*16][float dC partials B*D*16]    (only for a time-invariant B / C)
+//   both end with: [io staged B and C, B * ceil16(slots) * Lp * 2]    (only for a real state with selective B and C)
+// where Lp is L rounded up to a whole 32-step chunk.
 struct WsLayout {
-    size_t ckpt_off, ckpt_group, y_off, segh_off, segdt_off, segg_off, dA_off, dD_off, db_off, dBf_off, dCf_off, total;
+    size_t ckpt_off, ckpt_group, y_off, segh_off, segdt_off, segg_off, dA_off, dD_off, db_off, dBf_off, dCf_off;
+    size_t bcs_off, total;
+    int Lp;
     SegPlan plan;
 };
+// The forward kernels read a real state's selective B and C from a repacked copy.
+inline bool stageable(const ss_fwd_params* p)
+{
+    return !(p->flags & (SS_B_FIXED | SS_C_FIXED | SS_COMPLEX_STATE)) && p->seqlen > 0;
+}
 WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
 {
     const size_t nck = ((size_t)p->seqlen + SS_CHECKPOINT_STEPS - 1) / SS_CHECKPOINT_STEPS;
@@ -114,6 +123,8 @@ WsLayout ws_layout(const ss_fwd_params* p, bool for_bwd)
     // per-batch partial sums of the gradient of a time-invariant B / C
     w.dBf_off = take(for_bwd && (p->flags & SS_B_FIXED) ? rows * 16 * sizeof(float) : 0);
     w.dCf_off = take(for_bwd && (p->flags & SS_C_FIXED) ? rows * 16 * sizeof(float) : 0);
+    w.Lp = (p->seqlen + 31) / 32 * 32;
+    w.bcs_off = take(stageable(p) ? (size_t)p->batch * (((size_t)slots(p) + 15) / 16 * 16) * w.Lp * 2 * esz : 0);
     w.total = off;
     return w;
 }
@@ -178,6 +189,7 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
     a.seg_len = (p->seqlen + 31) / 32 * 32 + 32;
     a.seg_h = nullptr;
     a.seg_sumdt = nullptr;
+    a.bcs = nullptr; a.Lp = 0;
     return a;
 }
 
@@ -196,6 +208,7 @@ void narrow_to_group(ss::FwdArgs& a, const ss_fwd_params* p, int g, size_t ckpt_
     a.h_last = at(a.h_last, n0);
     a.Bm = (p->flags & SS_B_FIXED) ? at_bytes(a.Bm, (size_t)n0 * 4) : at_bytes(a.Bm, (size_t)n0 * p->seqlen * esz);
     a.Cm = (p->flags & SS_C_FIXED) ? at_bytes(a.Cm, (size_t)n0 * 4) : at_bytes(a.Cm, (size_t)n0 * p->seqlen * esz);
+    a.bcs = at_bytes(a.bcs, (size_t)(n0 / 4) * (a.Lp / 4) * 32 * esz);   // the group's first packed piece
     if (a.ckpt) a.ckpt = reinterpret_cast<float*>(reinterpret_cast<char*>(a.ckpt) + (size_t)g * ckpt_group_bytes);
     if (g > 0) {
         a.flags &= ~(uint32_t)SS_HAS_D;   // the skip term enters once
@@ -215,8 +228,15 @@ int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
     char* ws = static_cast<char*>(p->workspace);
     const int groups = p->seqlen == 0 ? 1 : (slots(p) + 15) / 16;
     size_t ckpt_group = 0;
+    auto stage = [&](const WsLayout& w) {
+        a.Lp = w.Lp;
+        if (ss::launch_stage_bc(a, ws + w.bcs_off, p->io_dtype, static_cast<hipStream_t>(stream)) != 0) return false;
+        a.bcs = ws + w.bcs_off;
+        return true;
+    };
     if (p->flags & SS_SAVE_FOR_BWD) {
         const WsLayout w = ws_layout(p, true);
+        if (stageable(p) && !stage(w)) return SS_ERR_LAUNCH;
         ckpt_group = w.ckpt_group;
         a.ckpt = reinterpret_cast<float*>(ws + w.ckpt_off);
         a.ysave = (p->flags & SS_HAS_Z) ? ws + w.y_off : nullptr;
@@ -229,6 +249,7 @@ int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
         // a plain forward call splits the sequence only if the caller lent the scratch for it
         const WsLayout w = ws_layout(p, false);
         const bool lent = ws && p->workspace_bytes >= w.total && aligned(ws, 256);
+        if (stageable(p) && lent && !stage(w)) return SS_ERR_LAUNCH;
         if (groups > 1 && (p->flags & SS_HAS_Z)) a.ysave = ws + w.y_off;   // checked to be there
         if (w.plan.nseg > 1 && lent) {
             a.nseg = w.plan.nseg; a.seg_len = w.plan.seg_len;

@@ -349,6 +349,40 @@ __device__ __forceinline__ bc_group<T> load_bc(const T* __restrict__ p, int t, i
     return g;
 }
 
+// The same from the staged, wave-packed copy (see stage_bc_kernel): everything a wave needs of
+// B and C for one group of steps is one contiguous piece, element (which * 4 + k) * 4 + j for
+// B (which = 0) or C (1), the wave's state k and step j.  One or two scalar loads, no clamp,
+// no mask, one base address per wave.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(4))) const u32x16 const_u32x16;
+constexpr int STAGE_GROUP = 2 * STATES_PER_LANE * GROUP_T;   // elements per wave and group
+template <typename T> struct bcs_group;
+template <> struct bcs_group<float> {
+    uint32_t w[STAGE_GROUP];
+    __device__ __forceinline__ float B(int k, int j) const { return __uint_as_float(w[k * GROUP_T + j]); }
+    __device__ __forceinline__ float C(int k, int j) const { return __uint_as_float(w[(STATES_PER_LANE + k) * GROUP_T + j]); }
+};
+template <> struct bcs_group<bf16_t> {
+    uint32_t w[STAGE_GROUP / 2];
+    __device__ __forceinline__ float get(int e) const { return (e & 1) ? bf16_hi(w[e >> 1]) : bf16_lo(w[e >> 1]); }
+    __device__ __forceinline__ float B(int k, int j) const { return get(k * GROUP_T + j); }
+    __device__ __forceinline__ float C(int k, int j) const { return get((STATES_PER_LANE + k) * GROUP_T + j); }
+};
+template <typename T>
+__device__ __forceinline__ bcs_group<T> load_bcs(const T* __restrict__ p)
+{
+    bcs_group<T> g;
+    const u32x16 v = *(const_u32x16*)p;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) g.w[i] = v[i];
+    if constexpr (sizeof(T) == 4) {
+        const u32x16 v2 = *(const_u32x16*)(p + 16);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) g.w[16 + i] = v2[i];
+    }
+    return g;
+}
+
 // The scalar loads above are issued only one group (4 steps) ahead, which hides an L2 hit
 // but not a trip to HBM.  When B and C are not already L2-resident (one batch entry, long
 // sequence), the wave therefore touches the lines it will need one chunk later with

@@ -26,7 +26,13 @@ namespace ss {
 // Algorithm 1 instead of the selective (B,N,L) tensor: it then sits in registers like A.
 // CPLX: the lane's four state slots are two complex states (re, im) each (Section 3.6); only
 // the recurrence and the read-out differ, everything around them sees 2N real "states".
-template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false>
+// STAGED: B and C come from the wave-packed copy a.bcs that stage_bc_kernel made: one scalar
+// load per group instead of eight, one address per wave instead of eight clamped ones, so the
+// scalar registers suffice for a whole group of prefetch and the scalar unit does little but
+// widen bf16.  (Read in place, the eight loads of the next group compete with the current
+// group's operands for scalar registers, some are issued only right before their use, and the
+// wait for those drains the whole prefetch: the loads' latency shows once per group.)
+template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -83,9 +89,27 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         Bf[k] = (BFIX && n_ok[k]) ? static_cast<const float*>(a.Bm)[(long)sd * NS + nc] : 0.0f;
         Cf[k] = (CFIX && n_ok[k]) ? static_cast<const float*>(a.Cm)[(long)sd * NS + nc] : 0.0f;
     }
+    // staged B and C: this wave's pieces, one per group of steps, consecutive in memory
+    const T* __restrict__ const sbc =
+        STAGED ? static_cast<const T*>(a.bcs) + (((long)b * ((NS + NPAD - 1) / NPAD * NWAVES) + w) * (a.Lp / GROUP_T)) * STAGE_GROUP
+               : nullptr;
     // the selective operands (if any) whose cache lines are touched one chunk ahead
     const void* const touchB = BFIX ? a.Cm : a.Bm;
     const void* const touchC = CFIX ? a.Bm : a.Cm;
+    // staged: the wave's pieces of a chunk are contiguous; a lane touches every 16th element
+    auto touch = [&](int t) -> float {
+        if constexpr (STAGED) {
+            constexpr int per_chunk = CHUNK_T / GROUP_T * STAGE_GROUP;
+            float v = 0.0f;
+            if (lane * 16 < per_chunk && t >= 0 && t < a.Lp) {
+                const T* q = sbc + (long)(t / GROUP_T) * STAGE_GROUP + lane * 16;
+                if constexpr (sizeof(T) == 2) v = bf16_to_f32(*q); else v = *q;
+            }
+            return v;
+        } else {
+            return touch_bc<T>(touchB, touchC, b, a.bc_bstride, N, L, w, lane, t);
+        }
+    };
     float sum_dt = 0.0f;  // AGG: this thread's share of the segment's sum of step sizes
 
     typename io8<T>::raw ru, rd, rz;
@@ -98,12 +122,12 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     };
     issue_loads(c_begin);
     float touched = 0.0f;
-    if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, a.bc_bstride, N, L, w, lane, c_begin * CHUNK_T);
+    if (BCFIX != 3) touched = touch(c_begin * CHUNK_T);
 
     for (int c = c_begin; c < c_end; ++c) {
         float u8[SLICE], z8[SLICE], v8[SLICE];
         consume_touch(touched);
-        if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, a.bc_bstride, N, L, w, lane, (c + 1) * CHUNK_T);
+        if (BCFIX != 3) touched = touch((c + 1) * CHUNK_T);
         const int tc = c * CHUNK_T;
         const int t0 = tc + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);
@@ -142,22 +166,50 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         // ---- B: sequential recurrence over the chunk ---------------------------------
         constexpr int NG = CHUNK_T / GROUP_T;
         bc_group<T> Bg[2][STATES_PER_LANE], Cg[2][STATES_PER_LANE];
+        constexpr int FB = 1;            // staged: groups fetched together (two gain nothing and spill scalar registers)
+        bcs_group<T> Sg[2 * FB];
+        const T* __restrict__ const sbc_chunk = STAGED ? sbc + (long)(tc / GROUP_T) * STAGE_GROUP : nullptr;
         auto fetch_bc = [&](int g, int slot) {
+            if constexpr (STAGED) {
+                Sg[slot] = load_bcs<T>(sbc_chunk + g * STAGE_GROUP);
+            } else {
 #pragma unroll
-            for (int k = 0; k < STATES_PER_LANE; ++k) {
-                if (!BFIX) Bg[slot][k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
-                if (!CFIX && !AGG) Cg[slot][k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+                for (int k = 0; k < STATES_PER_LANE; ++k) {
+                    if (!BFIX) Bg[slot][k] = load_bc<T, VEC, !FULLN>(gB[k], tc + g * GROUP_T, L, n_ok[k]);
+                    if (!CFIX && !AGG) Cg[slot][k] = load_bc<T, VEC, !FULLN>(gC[k], tc + g * GROUP_T, L, n_ok[k]);
+                }
             }
         };
-        fetch_bc(0, 0);
+        auto Bval = [&](int slot, int k, int j) -> float {
+            if constexpr (STAGED) return Sg[slot].B(k, j); else return BFIX ? Bf[k] : Bg[slot][k].get(j);
+        };
+        auto Cval = [&](int slot, int k, int j) -> float {
+            if constexpr (STAGED) return Sg[slot].C(k, j); else return CFIX ? Cf[k] : Cg[slot][k].get(j);
+        };
+        // Scalar loads return out of order and share their counter with LDS reads, so a wait
+        // for either drains both: the step sizes of the whole chunk are read from LDS before
+        // the loop, and inside it only the scalar loads of the next group are outstanding.
+        float4 dtc[NG], duc[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
-            const int cur = g & 1;
-            if (g + 1 < NG) fetch_bc(g + 1, cur ^ 1);  // in flight while group g is consumed
+            dtc[g] = *reinterpret_cast<const float4*>(&s_dt[lane][g * GROUP_T]);
+            duc[g] = *reinterpret_cast<const float4*>(&s_du[lane][g * GROUP_T]);
+        }
+        if constexpr (STAGED) {
+#pragma unroll
+            for (int i = 0; i < FB; ++i) fetch_bc(i, i);
+        } else {
+            fetch_bc(0, 0);
+        }
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int cur = STAGED ? g % (2 * FB) : (g & 1);
+            if constexpr (!STAGED) {
+                if (g + 1 < NG) fetch_bc(g + 1, cur ^ 1);  // in flight while group g is consumed
+            }
             const int tl = g * GROUP_T;  // step within the chunk
+            const float4 dt4 = dtc[g], du4 = duc[g];
             if (g > 0 && tl % CKPT_T == 0) save_ckpt((tc + tl) / CKPT_T);
-            const float4 dt4 = *reinterpret_cast<const float4*>(&s_dt[lane][tl]);
-            const float4 du4 = *reinterpret_cast<const float4*>(&s_du[lane][tl]);
             float yp[GROUP_T];
 #pragma unroll
             for (int j = 0; j < GROUP_T; ++j) {
@@ -167,28 +219,39 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 #pragma unroll
                     for (int k = 0; k < STATES_PER_LANE; k += 2) {
                         const cplx ab = complex_decay(dt, A2[k], An[k + 1]);         // Eq. 4 over C
-                        const float br = du * (BFIX ? Bf[k] : Bg[cur][k].get(j));
-                        const float bi = du * (BFIX ? Bf[k + 1] : Bg[cur][k + 1].get(j));
+                        const float br = du * Bval(cur, k, j);
+                        const float bi = du * Bval(cur, k + 1, j);
                         const float hr = fmaf(ab.re, h[k], fmaf(-ab.im, h[k + 1], br));  // Eq. 2a over C
                         const float hi = fmaf(ab.im, h[k], fmaf(ab.re, h[k + 1], bi));
                         h[k] = hr;
                         h[k + 1] = hi;
                         if (!AGG) {                                                  // Re(C h)
-                            y = fmaf(CFIX ? Cf[k] : Cg[cur][k].get(j), hr, y);
-                            y = fmaf(-(CFIX ? Cf[k + 1] : Cg[cur][k + 1].get(j)), hi, y);
+                            y = fmaf(Cval(cur, k, j), hr, y);
+                            y = fmaf(-Cval(cur, k + 1, j), hi, y);
                         }
                     }
                 } else {
 #pragma unroll
                     for (int k = 0; k < STATES_PER_LANE; ++k) {
                         const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
-                        float bu = du * (BFIX ? Bf[k] : Bg[cur][k].get(j));
+                        float bu = du * Bval(cur, k, j);
                         if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
                         h[k] = fmaf(abar, h[k], bu);                                 // Eq. 2a
-                        if (!AGG) y = fmaf(CFIX ? Cf[k] : Cg[cur][k].get(j), h[k], y);  // Eq. 2b
+                        if (!AGG) y = fmaf(Cval(cur, k, j), h[k], y);                         // Eq. 2b
                     }
                 }
                 yp[j] = y;
+                if constexpr (STAGED) {
+                    // The next group's load is issued after this group's first step, i.e. after
+                    // the wait for this group's own operands, so that that wait does not drain
+                    // it; the scheduling barriers keep the compiler from moving it either way.
+                    if (j == 0 && g % FB == 0 && g + FB < NG) {
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int i = 0; i < FB; ++i) fetch_bc(g + FB + i, (g + FB + i) % (2 * FB));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
             if (!AGG)
                 *reinterpret_cast<float4*>(&s_yp[w][lane][tl]) = make_float4(yp[0], yp[1], yp[2], yp[3]);
@@ -589,6 +652,46 @@ __global__ void copy_state_kernel(const float* __restrict__ src, float* __restri
     if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
+// Wave-packed copy of the selective B and C for the forward kernels (layout: FwdArgs::bcs).
+// A thread writes the four steps of one (batch entry, state, group of steps, B or C).
+template <typename T>
+__global__ void stage_bc_kernel(const T* __restrict__ Bm, const T* __restrict__ Cm, long bstride, T* __restrict__ dst,
+                                int B, int NS, int L, int Lp)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int tgroups = Lp / GROUP_T, sgroups = (NS + NPAD - 1) / NPAD * NWAVES;   // every wave of every pass has a piece
+    if (i >= (long)B * sgroups * tgroups * 2 * STATES_PER_LANE) return;
+    const int r = (int)(i % (2 * STATES_PER_LANE));            // which * 4 + k
+    const long piece = i / (2 * STATES_PER_LANE);
+    const int tg = (int)(piece % tgroups);
+    const int sg = (int)((piece / tgroups) % sgroups);
+    const int b = (int)(piece / ((long)tgroups * sgroups));
+    const int n = sg * STATES_PER_LANE + (r % STATES_PER_LANE), t = tg * GROUP_T;
+    const T* src = (r >= STATES_PER_LANE ? Cm : Bm) + (long)b * bstride + (long)n * L + t;
+    T v[GROUP_T];
+#pragma unroll
+    for (int j = 0; j < GROUP_T; ++j) v[j] = (n < NS && t + j < L) ? src[j] : T(0);
+    T* out = dst + i * GROUP_T;
+    if constexpr (sizeof(T) == 2) {
+        *reinterpret_cast<uint2*>(out) = make_uint2(uint32_t(v[0]) | (uint32_t(v[1]) << 16), uint32_t(v[2]) | (uint32_t(v[3]) << 16));
+    } else {
+        *reinterpret_cast<float4*>(out) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+int launch_stage_bc(const FwdArgs& a, void* bcs, int io_dtype, hipStream_t stream)
+{
+    const long n = (long)a.B * ((a.NS + NPAD - 1) / NPAD * NWAVES) * (a.Lp / GROUP_T) * 2 * STATES_PER_LANE;
+    const dim3 grid((unsigned)((n + 255) / 256));
+    if (io_dtype == 0)
+        stage_bc_kernel<float><<<grid, dim3(256), 0, stream>>>(static_cast<const float*>(a.Bm), static_cast<const float*>(a.Cm),
+                                                               a.bc_bstride, static_cast<float*>(bcs), a.B, a.NS, a.L, a.Lp);
+    else
+        stage_bc_kernel<bf16_t><<<grid, dim3(256), 0, stream>>>(static_cast<const bf16_t*>(a.Bm), static_cast<const bf16_t*>(a.Cm),
+                                                                a.bc_bstride, static_cast<bf16_t*>(bcs), a.B, a.NS, a.L, a.Lp);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX>
 static void launch_fwd_fixed(const FwdArgs& a, hipStream_t stream)
 {
@@ -629,11 +732,15 @@ static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
     if (bcfix == 2) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 2>(a, stream);
     if (bcfix == 3) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 3>(a, stream);
     if (a.nseg > 1) {
-        scan_fwd_kernel<T, VEC, FULLN, true, ZOH><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
+        // a split needs the caller's scratch, which holds the staged copy as well
+        scan_fwd_kernel<T, VEC, FULLN, true, ZOH, 0, false, true><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
         const long n = (long)a.B * a.D * NPAD;
         carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
     }
-    scan_fwd_kernel<T, VEC, FULLN, false, ZOH><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+    if (a.bcs)
+        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+    else
+        scan_fwd_kernel<T, VEC, FULLN, false, ZOH><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
 }
 
 int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)

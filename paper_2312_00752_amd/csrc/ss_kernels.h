@@ -30,6 +30,12 @@ struct FwdArgs {
     int vec_ok;  // L % 8 == 0: every row starts 16-byte aligned and 8-step slices are whole or empty
     const void *u, *delta, *z, *Bm, *Cm;
     long bc_bstride;  // elements between consecutive batch entries of Bm and Cm (N * L when dense)
+    // Staged copy of the selective B and C for the forward kernels, or null.  In the io dtype,
+    // packed per wave: [B][4 * ceil(NS / 16)][Lp / 4][B: 4 states x 4 steps | C: 4 states x 4 steps],
+    // Lp = L rounded up to a whole chunk, zeros for states past NS and steps past L.  What one
+    // wave needs for a group of 4 steps is then one contiguous 64- (bf16) or 128-byte piece.
+    const void* bcs;
+    int Lp;
     const float *A, *Dskip, *bias, *h0;
     void* out;
     float* h_last;  // may be null
@@ -80,6 +86,8 @@ struct StepArgs {
 
 // Each returns 0, or -1 if the runtime refused a launch.  io_dtype: 0 = float, 1 = bf16.
 int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream);
+// fills the staged copy `bcs` (all NS states) from a.Bm and a.Cm
+int launch_stage_bc(const FwdArgs& a, void* bcs, int io_dtype, hipStream_t stream);
 int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream);
 int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream);
 int launch_step_projected(const StepArgs& a, hipStream_t stream);   // bf16 I/O only

@@ -83,22 +83,27 @@ def test_forward_rejections():
 
 
 def test_workspace_size_formula():
+    # the repacked copy of B and C that the forward kernels read: B * ceil16(N) * (L rounded up to 32) * 2 elements
+    def staged(batch, seqlen, dstate, esz=4):
+        return -(-batch * (-(-dstate // 16) * 16) * (-(-seqlen // 32) * 32) * 2 * esz // 256) * 256
     # 96 steps: too short for the sequence to be split across workgroups
-    assert B.ss_workspace_bytes(2, 64, 96, 16, for_backward=False) == 0
+    assert B.ss_workspace_bytes(2, 64, 96, 16, for_backward=False) == staged(2, 96, 16)
     need = B.ss_workspace_bytes(2, 64, 96, 16)
     rows, chunks = 2 * 64, 96 // B.SS_CHECKPOINT_STEPS
-    assert need >= (chunks * rows * 16 + rows * 96 + rows * 16 + 2 * rows) * 4
-    assert B.ss_workspace_bytes(2, 64, 96, 16, io_dtype=B.SS_BF16) == need - rows * 96 * 2
+    assert need >= (chunks * rows * 16 + rows * 96 + rows * 16 + 2 * rows) * 4 + staged(2, 96, 16)
+    assert B.ss_workspace_bytes(2, 64, 96, 16, io_dtype=B.SS_BF16) == need - rows * 96 * 2 - staged(2, 96, 16, 2)
     assert B.ss_workspace_bytes(2, 64, 96, 16, has_z=False) == need - rows * 96 * 4
     assert need % 256 == 0
     assert B.ss_workspace_bytes(2, 64, 97, 16) > need          # a ragged tail adds a chunk
     assert B.ss_workspace_bytes(1, 1, 0, 1) % 256 == 0
+    # no copy for a time-invariant B or C
+    assert B.ss_workspace_bytes(2, 64, 96, 16, for_backward=False, b_fixed=True) == 0
     # few rows and a long sequence: scratch for splitting L across workgroups, also for a plain forward
-    assert B.ss_workspace_bytes(1, 256, 1 << 20, 16, for_backward=False) >= 100 * 256 * 17 * 4
-    assert B.ss_workspace_bytes(8, 4096, 2048, 16, for_backward=False) == 0      # two workgroups per compute unit: never split
-    assert B.ss_workspace_bytes(8, 2048, 2048, 16, for_backward=False) > 0       # one row tile per compute unit: split
-    assert B.ss_workspace_bytes(1, 1024, 1024, 16, for_backward=False) > 0       # few row tiles: split even when short
-    assert B.ss_workspace_bytes(1, 256, 96, 16, for_backward=False) == 0         # too short to split
+    assert B.ss_workspace_bytes(1, 256, 1 << 20, 16, for_backward=False) >= 100 * 256 * 17 * 4 + staged(1, 1 << 20, 16)
+    assert B.ss_workspace_bytes(8, 4096, 2048, 16, for_backward=False) == staged(8, 2048, 16)  # two workgroups per compute unit: never split
+    assert B.ss_workspace_bytes(8, 2048, 2048, 16, for_backward=False) > staged(8, 2048, 16)   # one row tile per compute unit: split
+    assert B.ss_workspace_bytes(1, 1024, 1024, 16, for_backward=False) > staged(1, 1024, 16)   # few row tiles: split even when short
+    assert B.ss_workspace_bytes(1, 256, 96, 16, for_backward=False) == staged(1, 96, 16)       # too short to split
 
 
 def test_backward_rejections():
@@ -267,7 +272,8 @@ def test_time_invariant_bc_flags():
     assert B.ss_workspace_bytes(1, 256, 1 << 16, 16, False, B.SS_F32, True) > 0
     assert B.ss_workspace_bytes(1, 256, 1 << 16, 16, False, B.SS_F32, True, b_fixed=True) == 0
     small = B.ss_workspace_bytes(2, 64, 96, 16, True, B.SS_BF16, True)
-    assert B.ss_workspace_bytes(2, 64, 96, 16, True, B.SS_BF16, True, b_fixed=True) == small + 2 * 64 * 16 * 4
+    # ... and there is no repacked copy of B and C (2 * 16 * 96 * 2 bf16 values)
+    assert B.ss_workspace_bytes(2, 64, 96, 16, True, B.SS_BF16, True, b_fixed=True) == small + 2 * 64 * 16 * 4 - 2 * 16 * 96 * 2 * 2
     # a (D,N) float32 parameter needs only 4-byte alignment
     p = _good_fwd(); p.flags = B.SS_B_FIXED; p.Bmat = FAKE + 4
     assert _fwd(p) != B.SS_ERR_ALIGN
@@ -294,4 +300,5 @@ def test_complex_state_flag():
     # 16 complex states are two groups of 16 slots: checkpoints double
     one = B.ss_workspace_bytes(2, 64, 96, 16, True, B.SS_BF16, False)
     two = B.ss_workspace_bytes(2, 64, 96, 16, True, B.SS_BF16, False, complex_state=True)
-    assert two > one and two - one == (96 // 16) * 2 * 64 * 16 * 4
+    # (and the real variant alone carries the repacked copy of B and C: 2 * 16 * 96 * 2 bf16 values)
+    assert two > one and two - one == (96 // 16) * 2 * 64 * 16 * 4 - 2 * 16 * 96 * 2 * 2

@@ -124,6 +124,31 @@ def test_forward_is_bitwise_reproducible_and_leaves_inputs_alone():
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("dstate,seqlen", [(1, 70), (13, 96), (16, 200), (16, 37), (40, 64)])
+def test_repacked_operands_give_the_same_bits(io, dstate, seqlen):
+    """With a workspace the forward kernels read B and C from a repacked copy, without one in
+    place: same values, same order of operations, so the results must be bit-identical (the shapes
+    have enough rows that the sequence is not split, which would reorder the sums)."""
+    import torch
+    from paper_2312_00752_amd import binding as B
+    w = wl.make_scan_inputs(8, seqlen, 4096, dstate, io=io, seed=170 + dstate)
+    g = util.upload(w)
+    code = B.SS_BF16 if io == "bf16" else B.SS_F32
+    # (more than 16 states with a gate need the workspace anyway: compare its two uses only)
+    plain, h_plain = _gpu_fwd(w, g) if dstate <= 16 else (None, None)
+    nbytes = B.ss_workspace_bytes(8, 4096, seqlen, dstate, for_backward=False, io_dtype=code)
+    assert nbytes > 0
+    ws = torch.full((nbytes,), 0xff, dtype=torch.uint8, device="cuda")       # NaN-poisoned scratch
+    lent, h_lent = _gpu_fwd(w, g, workspace=ws, save_for_bwd=False)
+    if plain is None:
+        plain, h_plain = lent, h_lent
+    assert torch.equal(plain, lent) and torch.equal(h_plain, h_lent)
+    ws2 = torch.full((B.ss_workspace_bytes(8, 4096, seqlen, dstate, io_dtype=code),), 0xff, dtype=torch.uint8, device="cuda")
+    saved, h_saved = _gpu_fwd(w, g, workspace=ws2, save_for_bwd=True)
+    assert torch.equal(plain, saved) and torch.equal(h_plain, h_saved)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
 def test_step_by_step_equals_scan(io):
     """L calls of ss_step from h0 reproduce ss_scan_fwd (recurrent == parallel mode, Section 2)."""
     import torch
