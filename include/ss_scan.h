@@ -121,9 +121,11 @@ typedef struct {
  * SS_SAVE_FOR_BWD fills it and the matching backward call must get the same, untouched
  * buffer.  256-byte alignment is required.  Returns 0 when none is needed.
  * A plain forward call (for_backward == 0) never requires a workspace: the size returned
- * for it (non-zero only for few rows and a long sequence) is scratch that, if lent, lets
- * the library split the sequence across workgroups; without it the call is correct but
- * runs one workgroup per 64 rows. */
+ * for it is scratch that, if lent, lets the library read B and C from a repacked copy
+ * (selective B and C, real state) and split a long sequence with few rows across
+ * workgroups; without it the call is correct but slower and runs one workgroup per 64
+ * rows.  (More than 16 states with a gate are the exception: the pre-gate output is
+ * accumulated in the workspace, which is then required.) */
 size_t ss_workspace_bytes(const ss_fwd_params *p, int for_backward);
 
 /* Forward scan (Algorithm 2 steps 5-6 with the fusion of Appendix D).  Writes out, and
