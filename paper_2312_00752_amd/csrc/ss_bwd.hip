@@ -196,14 +196,21 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
     float touched = 0.0f;
     if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, f.bc_bstride, N, L, w, lane, (nblocks - 1) * BT);
 
+    auto load_ckpt = [&](int blk) {
+        return *(reinterpret_cast<const float4*>(f.ckpt + (((long)blk * f.B + b) * f.D + sd) * NPAD) + w);
+    };
+    float4 hck_next = load_ckpt(nblocks - 1);
     for (int blk = nblocks - 1; blk >= blk_begin; --blk) {
         const int tc = blk * BT;
         consume_touch(touched);
         if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, f.bc_bstride, N, L, w, lane, (blk - 1) * BT);
         const int t0 = tc + pq * BSL;
         const int nv = p_ok ? min(max(L - t0, 0), BSL) : 0;
-        // the state entering this block, left by the forward pass
-        const float4 hck4 = *(reinterpret_cast<const float4*>(f.ckpt + (((long)blk * f.B + b) * f.D + sd) * NPAD) + w);
+        // The state entering this block, left by the forward pass, was requested a block ago:
+        // memory operations retire in order, so a wait for a load issued here would also wait
+        // for every store and atomic of the previous block.
+        const float4 hck4 = hck_next;
+        if (blk > blk_begin) hck_next = load_ckpt(blk - 1);
 
         // ---- A: pointwise pre-processing ---------------------------------------------------
         float u4[BSL], sg4[BSL];  // u and d softplus(x)/dx, needed again in C
