@@ -176,7 +176,8 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
     a.B = p->batch; a.D = p->dim; a.L = p->seqlen; a.N = slots(p); a.NS = slots(p);
     a.acc_y = 0;
     a.flags = p->flags;
-    a.vec_ok = p->seqlen % 8 == 0;
+    // 16-byte slices, addressed through per-workgroup buffer resources (64 rows, 31-bit offsets)
+    a.vec_ok = p->seqlen % 8 == 0 && (size_t)p->seqlen * 64 * sizeof(float) < ((size_t)1 << 31);
     a.u = p->u; a.delta = p->delta; a.z = (p->flags & SS_HAS_Z) ? p->z : nullptr;
     a.Bm = p->Bmat; a.Cm = p->Cmat; a.A = p->A;
     a.bc_bstride = bc_bstride;

@@ -193,7 +193,7 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
         }
     };
     issue_group((nblocks - 1) / LG);
-    float touched = 0.0f;
+    uint32_t touched = 0u;
     if (BCFIX != 3) touched = touch_bc<T>(touchB, touchC, b, f.bc_bstride, N, L, w, lane, (nblocks - 1) * BT);
 
     auto load_ckpt = [&](int blk) {
@@ -511,7 +511,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
         if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
     };
     issue_loads(c_end - 1);
-    float touched = touch_bc<T>(f.Cm, f.Cm, b, f.bc_bstride, N, L, w, lane, (c_end - 1) * CHUNK_T);
+    uint32_t touched = touch_bc<T>(f.Cm, f.Cm, b, f.bc_bstride, N, L, w, lane, (c_end - 1) * CHUNK_T);
     for (int c = c_end - 1; c >= c_begin; --c) {
         const int tc = c * CHUNK_T;
         consume_touch(touched);

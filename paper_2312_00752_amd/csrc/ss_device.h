@@ -123,6 +123,32 @@ __device__ __forceinline__ uint4 load16_once(const void* p)
     return make_uint4(x.x, x.y, x.z, x.w);
 }
 
+// ---- buffer-addressed accesses ---------------------------------------------------------
+// Memory operations retire in order and the compiler can let younger ones stay outstanding
+// across a wait only if it can count them: a store or load inside an `if` counts as "maybe
+// zero", and a wait for an older load then degenerates to "wait for everything", i.e. for
+// the acknowledgement of stores issued a moment ago.  The hot loops therefore use buffer
+// instructions, which are issued unconditionally: the hardware drops a store, and returns
+// zero for a load, whose offset lies at or beyond the resource's size, so a lane (or a whole
+// access) is switched off with an out-of-range offset (or a size of zero) instead of a
+// branch.  Resources are built per workgroup (64 rows), which keeps offsets far below 2^31.
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+constexpr uint32_t BUF_OFF = 0x80000000u;   // an offset beyond any resource built here
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16_once(rsrc_t r, uint32_t off)   // streaming hint, as load16_once
+{
+    const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2);
+    return make_uint4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ void buf_store16(rsrc_t r, uint32_t off, uint4 v)
+{
+    const u32x4 x = {v.x, v.y, v.z, v.w};
+    __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, 0);
+}
+
 // ---- 8 consecutive io elements <-> 8 floats -------------------------------------------
 // VEC: every row starts 16-byte aligned and L is a multiple of 8, so a slice is either
 // whole (nvalid == 8, one or two 16-byte accesses) or empty.  Otherwise the `nvalid`
@@ -150,6 +176,19 @@ template <> struct io8<float> {
             r.b = make_float4(v[4], v[5], v[6], v[7]);
         }
         return r;
+    }
+    static __device__ __forceinline__ raw load_buf(rsrc_t rs, uint32_t off)   // whole slice, or zeros if off is out of range
+    {
+        const uint4 x = buf_load16_once(rs, off), y = buf_load16_once(rs, off + 16);
+        raw r;
+        r.a = make_float4(__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w));
+        r.b = make_float4(__uint_as_float(y.x), __uint_as_float(y.y), __uint_as_float(y.z), __uint_as_float(y.w));
+        return r;
+    }
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[8])
+    {
+        buf_store16(rs, off, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+        buf_store16(rs, off + 16, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
     }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[8])
     {
@@ -189,6 +228,16 @@ template <> struct io8<bf16_t> {
                              v[6] | (v[7] << 16));
         }
         return r;
+    }
+    static __device__ __forceinline__ raw load_buf(rsrc_t rs, uint32_t off)   // whole slice, or zeros if off is out of range
+    {
+        raw r;
+        r.w = buf_load16_once(rs, off);
+        return r;
+    }
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[8])
+    {
+        buf_store16(rs, off, make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])));
     }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[8])
     {
@@ -389,17 +438,18 @@ __device__ __forceinline__ bcs_group<T> load_bcs(const T* __restrict__ p)
 // ordinary vector loads: lanes 0..3 one element of each of its B rows, lanes 4..7 of its C
 // rows, at step t.  The value is only handed to `consume_touch` an iteration later.
 template <typename T>
-__device__ __forceinline__ float touch_bc(const void* Bm, const void* Cm, int b, long bstride, int N, int L, int w,
-                                           int lane, int t)
+__device__ __forceinline__ uint32_t touch_bc(const void* Bm, const void* Cm, int b, long bstride, int N, int L, int w,
+                                              int lane, int t)
 {
-    float v = 0.0f;
+    // the raw bits, untouched: any arithmetic on the value would make the wave wait for it here
+    uint32_t v = 0u;
     if (lane < 2 * STATES_PER_LANE && t >= 0 && t < L) {
         const int n = min(w * STATES_PER_LANE + (lane & 3), N - 1);
         const T* p = static_cast<const T*>(lane < STATES_PER_LANE ? Bm : Cm) + (long)b * bstride + (long)n * L + t;
-        if constexpr (sizeof(T) == 2) v = bf16_to_f32(*p); else v = *p;
+        if constexpr (sizeof(T) == 2) v = *p; else v = __float_as_uint(*p);
     }
     return v;
 }
-__device__ __forceinline__ void consume_touch(float v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void consume_touch(uint32_t v) { asm volatile("" ::"v"(v)); }
 
 }  // namespace ss

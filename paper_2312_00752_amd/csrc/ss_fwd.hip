@@ -63,6 +63,18 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     T* __restrict__ gout = static_cast<T*>(a.out) + prow * L;
     const float bias = (a.flags & F_HAS_DELTA_BIAS) ? a.bias[pd] : 0.0f;
     const float Dsk = has_D ? a.Dskip[pd] : 0.0f;
+    // VEC: buffer resources over this workgroup's rows of each tensor (a size of zero switches
+    // an optional tensor off), so that the accesses in the loop are issued unconditionally
+    const int rows_here = min(ROWS, a.D - d0);
+    const long wg_first = ((long)b * a.D + d0) * L;
+    const uint32_t wg_bytes = (uint32_t)rows_here * (uint32_t)L * (uint32_t)sizeof(T);
+    const uint32_t row_off = (uint32_t)pr * (uint32_t)L * (uint32_t)sizeof(T);   // past the resource for rows past D
+    const bool keep_y = !AGG && has_z && a.ysave;
+    const rsrc_t bu = make_rsrc(static_cast<const T*>(a.u) + wg_first, wg_bytes);
+    const rsrc_t bd = make_rsrc(static_cast<const T*>(a.delta) + wg_first, wg_bytes);
+    const rsrc_t bz = make_rsrc(static_cast<const T*>(has_z ? a.z : a.u) + wg_first, has_z ? wg_bytes : 0u);
+    const rsrc_t bo = make_rsrc(static_cast<T*>(AGG ? const_cast<void*>(a.u) : a.out) + wg_first, AGG ? 0u : wg_bytes);
+    const rsrc_t by = make_rsrc(static_cast<T*>(keep_y ? a.ysave : const_cast<void*>(a.u)) + wg_first, keep_y ? wg_bytes : 0u);
 
     // ---- state view: lane -> row, wave -> states 4w..4w+3 -------------------------------
     const bool s_ok = d0 + lane < a.D;
@@ -97,15 +109,13 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     const void* const touchB = BFIX ? a.Cm : a.Bm;
     const void* const touchC = CFIX ? a.Bm : a.Cm;
     // staged: the wave's pieces of a chunk are contiguous; a lane touches every 16th element
-    auto touch = [&](int t) -> float {
-        if constexpr (STAGED) {
+    const rsrc_t bt = make_rsrc(sbc, STAGED ? (uint32_t)(a.Lp / GROUP_T) * STAGE_GROUP * (uint32_t)sizeof(T) : 0u);
+    auto touch = [&](int t) -> uint32_t {
+        if constexpr (STAGED) {   // an unconditional buffer load; lanes with nothing to touch are out of range
             constexpr int per_chunk = CHUNK_T / GROUP_T * STAGE_GROUP;
-            float v = 0.0f;
-            if (lane * 16 < per_chunk && t >= 0 && t < a.Lp) {
-                const T* q = sbc + (long)(t / GROUP_T) * STAGE_GROUP + lane * 16;
-                if constexpr (sizeof(T) == 2) v = bf16_to_f32(*q); else v = *q;
-            }
-            return v;
+            const bool on = lane * 16 < per_chunk && t >= 0 && t < a.Lp;
+            const uint32_t off = on ? (uint32_t)((t / GROUP_T) * STAGE_GROUP + lane * 16) * (uint32_t)sizeof(T) : BUF_OFF;
+            return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(bt, (int)off, 0, 0);
         } else {
             return touch_bc<T>(touchB, touchC, b, a.bc_bstride, N, L, w, lane, t);
         }
@@ -116,18 +126,23 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     auto issue_loads = [&](int c) {
         const int t0 = c * CHUNK_T + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);
-        ru = io8<T>::template load<VEC>(gu + t0, nv);
-        rd = io8<T>::template load<VEC>(gdl + t0, nv);
-        if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
+        if constexpr (VEC) {   // slices are whole or empty
+            const uint32_t off = nv == SLICE ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
+            ru = io8<T>::load_buf(bu, off);
+            rd = io8<T>::load_buf(bd, off);
+            rz = io8<T>::load_buf(bz, off);
+        } else {
+            ru = io8<T>::template load<VEC>(gu + t0, nv);
+            rd = io8<T>::template load<VEC>(gdl + t0, nv);
+            if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
+        }
     };
     issue_loads(c_begin);
-    float touched = 0.0f;
+    uint32_t touched = 0u;
     if (BCFIX != 3) touched = touch(c_begin * CHUNK_T);
 
     for (int c = c_begin; c < c_end; ++c) {
         float u8[SLICE], z8[SLICE], v8[SLICE];
-        consume_touch(touched);
-        if (BCFIX != 3) touched = touch((c + 1) * CHUNK_T);
         const int tc = c * CHUNK_T;
         const int t0 = tc + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);
@@ -153,9 +168,21 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             pu4[0] = make_float4(du8[0], du8[1], du8[2], du8[3]);
             pu4[1] = make_float4(du8[4], du8[5], du8[6], du8[7]);
         }
+        // The touch of the next chunk's B and C goes here, after the wait for this chunk's u,
+        // delta and z: the value touched a chunk ago is older than those and costs no wait of
+        // its own.
+        consume_touch(touched);
+        if (BCFIX != 3) touched = touch((c + 1) * CHUNK_T);
         // checkpoint: the state entering every CKPT_T-step block (read back by the backward pass)
         auto save_ckpt = [&](int block) {
-            if (!AGG && a.ckpt && s_ok && block * CKPT_T < L) {
+            if constexpr (AGG) return;
+            if constexpr (VEC) {   // the block's 64 rows x 16 states; nothing is written if there is no block or no buffer
+                const bool on = a.ckpt && block * CKPT_T < L;
+                const rsrc_t bc = make_rsrc(a.ckpt + (((long)block * a.B + b) * a.D + d0) * NPAD,
+                                            on ? (uint32_t)rows_here * NPAD * (uint32_t)sizeof(float) : 0u);
+                buf_store16(bc, (uint32_t)(lane * NPAD + w * STATES_PER_LANE) * (uint32_t)sizeof(float),
+                            make_uint4(__float_as_uint(h[0]), __float_as_uint(h[1]), __float_as_uint(h[2]), __float_as_uint(h[3])));
+            } else if (a.ckpt && s_ok && block * CKPT_T < L) {
                 float4* ck = reinterpret_cast<float4*>(a.ckpt + (((long)block * a.B + b) * a.D + sd) * NPAD) + w;
                 *ck = make_float4(h[0], h[1], h[2], h[3]);
             }
@@ -277,13 +304,23 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 #pragma unroll
                 for (int j = 0; j < SLICE; ++j) y8[j] += p8[j];
             }
-            if (has_z) {
-                if (a.ysave)  // y before the gate, for the backward pass's dz
-                    io8<T>::template store<VEC>(static_cast<T*>(a.ysave) + prow * L + t0, y8, nvs);
+            const uint32_t off = nv == SLICE ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
+            if constexpr (VEC) {
+                io8<T>::store_buf(by, off, y8);   // y before the gate, for the backward pass's dz (if kept)
+                if (has_z) {
 #pragma unroll
-                for (int j = 0; j < SLICE; ++j) y8[j] *= z8[j] * sigmoid_fast(z8[j]);
+                    for (int j = 0; j < SLICE; ++j) y8[j] *= z8[j] * sigmoid_fast(z8[j]);
+                }
+                io8<T>::store_buf(bo, off, y8);
+            } else {
+                if (has_z) {
+                    if (a.ysave)  // y before the gate, for the backward pass's dz
+                        io8<T>::template store<VEC>(static_cast<T*>(a.ysave) + prow * L + t0, y8, nvs);
+#pragma unroll
+                    for (int j = 0; j < SLICE; ++j) y8[j] *= z8[j] * sigmoid_fast(z8[j]);
+                }
+                io8<T>::template store<VEC>(gout + t0, y8, nvs);
             }
-            io8<T>::template store<VEC>(gout + t0, y8, nvs);
         }
         // no barrier needed here: the next phase A writes s_dt/s_du, which every wave has
         // finished reading (barrier above), and s_yp is rewritten only after the next barrier
