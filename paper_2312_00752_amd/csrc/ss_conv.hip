@@ -76,6 +76,53 @@ __device__ __forceinline__ void load_window(const T* __restrict__ row, const T* 
     }
 }
 
+// The same for rows of whole 8-step slices (L a multiple of 8), in two halves so that all the
+// loads of a unit are issued back to back and waited for once: branch-free buffer loads (an
+// offset out of range returns zeros), where the pointer form above waits for each conditional
+// load in turn.  `next` additionally fetches the 4 samples after the slice.
+template <typename T>
+struct window_raw {
+    typename io8<T>::raw cur;
+    typename io4<T>::raw halo, next;
+    uint32_t st[HALO];
+};
+template <typename T>
+__device__ __forceinline__ uint32_t row_bytes(int L) { return (uint32_t)L * (uint32_t)sizeof(T); }   // rows below 2^31 bytes (checked by the host)
+template <typename T, bool NEXT>
+__device__ __forceinline__ window_raw<T> issue_window(rsrc_t brow, rsrc_t bstate, int t0, int L, int W)
+{
+    window_raw<T> r;
+    const uint32_t esz = (uint32_t)sizeof(T);
+    r.cur = io8<T>::load_buf(brow, t0 < L ? (uint32_t)t0 * esz : BUF_OFF);
+    // t0 is a multiple of 8, so the four samples in front of the slice are aligned
+    r.halo = io4<T>::load_buf(brow, (t0 > 0 && t0 < L) ? (uint32_t)(t0 - 4) * esz : BUF_OFF);
+    if (NEXT) r.next = io4<T>::load_buf(brow, t0 + 8 < L ? (uint32_t)(t0 + 8) * esz : BUF_OFF);
+#pragma unroll
+    for (int j = 0; j < HALO; ++j) {   // the window handed over from before the sequence, for the row's first slice
+        const int idx = j - (TAPS - W);
+        r.st[j] = buf_load_elem<T>(bstate, (t0 == 0 && idx >= 0) ? (uint32_t)idx * esz : BUF_OFF);
+    }
+    return r;
+}
+template <typename T>
+__device__ __forceinline__ float raw_to_f32(uint32_t bits)
+{
+    if constexpr (sizeof(T) == 2) return bf16_to_f32(bf16_t(bits)); else return __uint_as_float(bits);
+}
+// xs as load_window; xn[0..3] = x[t0+8..t0+11] if fetched
+template <typename T, bool NEXT>
+__device__ __forceinline__ void unpack_window(const window_raw<T>& r, int t0, float (&xs)[HALO + 8], float (&xn)[4])
+{
+    float cur[8], h[4];
+    io8<T>::unpack(r.cur, cur);
+    io4<T>::unpack(r.halo, h);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xs[HALO + j] = cur[j];
+#pragma unroll
+    for (int j = 0; j < HALO; ++j) xs[j] = t0 > 0 ? h[j + 1] : raw_to_f32<T>(r.st[j]);
+    if (NEXT) io4<T>::unpack(r.next, xn);
+}
+
 __device__ __forceinline__ float conv_at(const float (&k4)[TAPS], float bias, const float* xs)
 {
     return fmaf(k4[3], xs[3], fmaf(k4[2], xs[2], fmaf(k4[1], xs[1], fmaf(k4[0], xs[0], bias))));
@@ -103,7 +150,14 @@ __global__ __launch_bounds__(THREADS) void conv_fwd_kernel(const ConvArgs a)
     const float bias = (a.flags & SS_CONV_HAS_BIAS) ? a.bias[d] : 0.0f;
 
     float xs[HALO + 8];
-    load_window<T, VEC>(row, state_row, t0, a.L, a.W, xs);
+    if constexpr (VEC) {
+        const rsrc_t brow = make_rsrc(row, row_bytes<T>(a.L));
+        const rsrc_t bstate = make_rsrc(state_row ? state_row : row, state_row ? (uint32_t)(a.W - 1) * (uint32_t)sizeof(T) : 0u);
+        float unused[4];
+        unpack_window<T, false>(issue_window<T, false>(brow, bstate, t0, a.L, a.W), t0, xs, unused);
+    } else {
+        load_window<T, VEC>(row, state_row, t0, a.L, a.W, xs);
+    }
     float o[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -162,8 +216,22 @@ __global__ __launch_bounds__(THREADS) void conv_bwd_kernel(const ConvArgs a)
         const int nvalid = min(max(a.L - t0, 0), 8);
 
         float xs[HALO + 8], g[8], dv[8 + HALO];
-        load_window<T, VEC>(row, state_row, t0, a.L, a.W, xs);
-        io8<T>::unpack(io8<T>::template load<VEC>(grow + t0, nvalid), g);
+        float xn[4] = {0.f, 0.f, 0.f, 0.f}, gn[4] = {0.f, 0.f, 0.f, 0.f};   // VEC: x and dout of the 4 steps after the slice
+        if constexpr (VEC) {
+            const rsrc_t brow = make_rsrc(row, row_bytes<T>(a.L));
+            const rsrc_t bgrow = make_rsrc(grow, row_bytes<T>(a.L));
+            const rsrc_t bstate = make_rsrc(state_row ? state_row : row, state_row ? (uint32_t)(a.W - 1) * (uint32_t)sizeof(T) : 0u);
+            const uint32_t esz = (uint32_t)sizeof(T);
+            const window_raw<T> wr = issue_window<T, true>(brow, bstate, t0, a.L, a.W);
+            const typename io8<T>::raw rg = io8<T>::load_buf(bgrow, t0 < a.L ? (uint32_t)t0 * esz : BUF_OFF);
+            const typename io4<T>::raw rgn = io4<T>::load_buf(bgrow, t0 + 8 < a.L ? (uint32_t)(t0 + 8) * esz : BUF_OFF);
+            unpack_window<T, true>(wr, t0, xs, xn);
+            io8<T>::unpack(rg, g);
+            io4<T>::unpack(rgn, gn);
+        } else {
+            load_window<T, VEC>(row, state_row, t0, a.L, a.W, xs);
+            io8<T>::unpack(io8<T>::template load<VEC>(grow + t0, nvalid), g);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (SILU) {
@@ -184,10 +252,15 @@ __global__ __launch_bounds__(THREADS) void conv_bwd_kernel(const ConvArgs a)
         if (lane == WAVE - 1 && t0 + 8 < a.L) {
             float xe[2 * HALO];   // x[t0+5 .. t0+10]
 #pragma unroll
-            for (int j = 0; j < 2 * HALO; ++j) xe[j] = (t0 + 5 + j < a.L) ? io_to_f32<T>(row[t0 + 5 + j]) : 0.0f;
+            for (int j = 0; j < 2 * HALO; ++j) {
+                if constexpr (VEC) xe[j] = j < HALO ? xs[HALO + 5 + j] : xn[j - HALO];
+                else xe[j] = (t0 + 5 + j < a.L) ? io_to_f32<T>(row[t0 + 5 + j]) : 0.0f;
+            }
 #pragma unroll
             for (int j = 0; j < HALO; ++j) {
-                const float gj = (t0 + 8 + j < a.L) ? io_to_f32<T>(grow[t0 + 8 + j]) : 0.0f;
+                float gj;
+                if constexpr (VEC) gj = gn[j];
+                else gj = (t0 + 8 + j < a.L) ? io_to_f32<T>(grow[t0 + 8 + j]) : 0.0f;
                 if (SILU) {
                     const float v = conv_at(k4, bias, xe + j);
                     const float s = sigmoid_fast(v);
@@ -317,6 +390,8 @@ int check_conv(const ss_conv_params* p, bool for_bwd)
     if ((p->x && !aligned_to(p->x, 16)) || (!for_bwd && p->out && !aligned_to(p->out, 16))) return SS_ERR_ALIGN;
     if ((p->state_in && !aligned_to(p->state_in, esz)) || (p->state_out && !aligned_to(p->state_out, esz))) return SS_ERR_ALIGN;
     if (!aligned_to(p->w, 4) || (p->bias && !aligned_to(p->bias, 4))) return SS_ERR_ALIGN;
+    // rows are addressed through buffer resources with 31-bit offsets
+    if ((size_t)p->seqlen * sizeof(float) >= ((size_t)1 << 31)) return SS_ERR_UNSUPPORTED;
     // the forward grid is one-dimensional
     const long pieces = ((long)p->seqlen + ss::PIECE - 1) / ss::PIECE;
     if ((long)p->batch * p->dim * pieces / ss::NWAVES >= 0x7fffffffL) return SS_ERR_UNSUPPORTED;

@@ -149,6 +149,25 @@ __device__ __forceinline__ void buf_store16(rsrc_t r, uint32_t off, uint4 v)
     __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, 0);
 }
 
+__device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t off)
+{
+    const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return make_uint4(x.x, x.y, x.z, x.w);
+}
+typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 buf_load8(rsrc_t r, uint32_t off)
+{
+    const u32x2v x = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+    return make_uint2(x.x, x.y);
+}
+// one io element as raw bits (zero if off is out of range)
+template <typename T>
+__device__ __forceinline__ uint32_t buf_load_elem(rsrc_t r, uint32_t off)
+{
+    if constexpr (sizeof(T) == 2) return (uint32_t)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, 0);
+    else return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0);
+}
+
 // ---- 8 consecutive io elements <-> 8 floats -------------------------------------------
 // VEC: every row starts 16-byte aligned and L is a multiple of 8, so a slice is either
 // whole (nvalid == 8, one or two 16-byte accesses) or empty.  Otherwise the `nvalid`
@@ -282,6 +301,13 @@ template <> struct io4<float> {
         }
         return r;
     }
+    static __device__ __forceinline__ raw load_buf(rsrc_t rs, uint32_t off)   // whole slice, or zeros if off is out of range
+    {
+        const uint4 x = buf_load16(rs, off);
+        raw r;
+        r.a = make_float4(__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w));
+        return r;
+    }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
     {
         v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
@@ -314,6 +340,12 @@ template <> struct io4<bf16_t> {
             for (int j = 0; j < 4; ++j) v[j] = (j < nvalid) ? uint32_t(p[j]) : 0u;
             r.w = make_uint2(v[0] | (v[1] << 16), v[2] | (v[3] << 16));
         }
+        return r;
+    }
+    static __device__ __forceinline__ raw load_buf(rsrc_t rs, uint32_t off)   // whole slice, or zeros if off is out of range
+    {
+        raw r;
+        r.w = buf_load8(rs, off);
         return r;
     }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
