@@ -537,46 +537,50 @@ __global__ void __launch_bounds__(SP_THREADS) step_proj_kernel(const StepArgs a)
     const bf16_t* z_t = static_cast<const bf16_t*>(a.z_t);
     auto as_stored = [](float v) -> float { return bf16_to_f32(bf16_t(f32_to_bf16_bits(v))); };
 
+    // Everything the thread needs from global memory is requested here, in straight-line code
+    // with no branch between the loads (optional operands are read through a valid stand-in
+    // pointer and discarded) and no arithmetic on a loaded value: either would make the compiler
+    // wait for that load before issuing the next, one memory latency after another.
     const int sq = q * STATES_PER_LANE;               // this quarter's first state
-    float hv[SP_PER][STATES_PER_LANE], ub[SP_PER], zb[SP_PER];
+    const bool has_z = a.flags & F_HAS_Z, has_D = a.flags & F_HAS_D, has_bias = a.flags & F_HAS_DELTA_BIAS;
+    const bf16_t* zp = has_z ? z_t : u_t;
+    float hv[SP_PER][STATES_PER_LANE];
+    bf16_t ub_raw[SP_PER], zb_raw[SP_PER];
 #pragma unroll
     for (int i = 0; i < SP_PER; ++i) {
         const int b = min(b0 + half * SP_PER + i, a.B - 1);
         const long row = (long)b * a.D + d;
-        const float* hp = a.h + row * N + sq;
         if constexpr (FULLN) {
-            const float4 h4 = *reinterpret_cast<const float4*>(hp);
+            const float4 h4 = *reinterpret_cast<const float4*>(a.h + row * N + sq);
             hv[i][0] = h4.x; hv[i][1] = h4.y; hv[i][2] = h4.z; hv[i][3] = h4.w;
         } else {
 #pragma unroll
-            for (int k = 0; k < STATES_PER_LANE; ++k) hv[i][k] = (sq + k < N) ? hp[k] : 0.0f;
+            for (int k = 0; k < STATES_PER_LANE; ++k) hv[i][k] = a.h[row * N + min(sq + k, N - 1)];   // a valid element; masked below
         }
-        ub[i] = bf16_to_f32(u_t[row]);
-        zb[i] = (a.flags & F_HAS_Z) ? bf16_to_f32(z_t[row]) : 0.0f;
+        ub_raw[i] = u_t[row];
+        zb_raw[i] = zp[row];
     }
-    float Av[STATES_PER_LANE];
+    float A_raw[STATES_PER_LANE];
 #pragma unroll
-    for (int k = 0; k < STATES_PER_LANE; ++k) Av[k] = (sq + k < N) ? a.A[(long)d * N + sq + k] * LOG2E : 0.0f;
-    const float Dsk = (a.flags & F_HAS_D) ? a.Dskip[d] : 0.0f;
+    for (int k = 0; k < STATES_PER_LANE; ++k) A_raw[k] = a.A[(long)d * N + min(sq + k, N - 1)];
+    const float D_raw = (has_D ? a.Dskip : a.A)[has_D ? d : 0];
 
     // Waves 0-3 form the tile (batch entries) x (channels d0 + 16 * wave ..+15) of r W_dt^T after
     // the staging below.  Operand layout of the 16x16x32 bf16 MFMA: lane l holds row (column)
     // l % 16 of the first (second) operand at contraction indices 8 * (l / 16) ..+7; accumulator
     // element i of lane l is row 4 * (l / 16) + i, column l % 16.  Their pieces of W_dt are
-    // requested now, with everything else.
+    // requested now, with everything else (from a clamped, valid address; zeroed below where the
+    // piece lies past R).
     const int dcol = 16 * (wave & 3) + (lane & 15);
     const int wrow = min(d0 + dcol, a.D - 1);
     const int ksub = 8 * (lane >> 4);
     union WFrag { unsigned short s[8]; bf16x8_t v; } wfrag[SP_MAX_KSTEPS];
-    const float bias = (a.flags & F_HAS_DELTA_BIAS) ? a.bias[wrow] : 0.0f;
-    if (wave < 4) {
-        const bf16_t* wp = static_cast<const bf16_t*>(a.W_dt) + (long)wrow * R + ksub;
+    const float bias_raw = (has_bias ? a.bias : a.A)[has_bias ? wrow : 0];
+    {
+        const bf16_t* wp = static_cast<const bf16_t*>(a.W_dt) + (long)wrow * R;
 #pragma unroll
-        for (int i = 0; i < SP_MAX_KSTEPS; ++i) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) wfrag[i].s[e] = 0;
-            if (32 * i + ksub < R) wfrag[i].v = *reinterpret_cast<const bf16x8_t*>(wp + 32 * i);
-        }
+        for (int i = 0; i < SP_MAX_KSTEPS; ++i)
+            wfrag[i].v = *reinterpret_cast<const bf16x8_t*>(wp + min(32 * i + ksub, R - 8));   // R is a multiple of 8
     }
 
     {
@@ -627,21 +631,29 @@ __global__ void __launch_bounds__(SP_THREADS) step_proj_kernel(const StepArgs a)
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float x = as_stored(acc[i]) + bias, dt = x, sg;
+            float x = as_stored(acc[i]) + (has_bias ? bias_raw : 0.0f), dt = x, sg;
             if (a.flags & F_DELTA_SOFTPLUS) softplus_sigmoid(x, dt, sg);
             s_dt[4 * (lane >> 4) + i][dcol] = dt;
         }
     }
     __syncthreads();
 
+    float Av[STATES_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < STATES_PER_LANE; ++k) Av[k] = (sq + k < N) ? A_raw[k] * LOG2E : 0.0f;
+    const float Dsk = has_D ? D_raw : 0.0f;
 #pragma unroll
     for (int i = 0; i < SP_PER; ++i) {
         const int bl = half * SP_PER + i;
         if (bl >= nbt) break;
+        if constexpr (!FULLN) {
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k) hv[i][k] = (sq + k < N) ? hv[i][k] : 0.0f;
+        }
         const long row = (long)(b0 + bl) * a.D + d;
         const float* pb = s_p[bl];
         const float dt = s_dt[bl][dl];
-        const float u = ub[i];
+        const float u = bf16_to_f32(ub_raw[i]);
         const float du = dt * u;
         float Bq[STATES_PER_LANE], Cq[STATES_PER_LANE];
         if constexpr (FULLN) {
@@ -677,7 +689,10 @@ __global__ void __launch_bounds__(SP_THREADS) step_proj_kernel(const StepArgs a)
         y += __shfl_xor(y, 1);
         y += __shfl_xor(y, 2);
         y = fmaf(Dsk, u, y);
-        if (a.flags & F_HAS_Z) y *= zb[i] * sigmoid_fast(zb[i]);
+        if (has_z) {
+            const float z = bf16_to_f32(zb_raw[i]);
+            y *= z * sigmoid_fast(z);
+        }
         if (d_ok && q == 0) static_cast<bf16_t*>(a.out_t)[row] = bf16_t(f32_to_bf16_bits(y));
     }
 }
