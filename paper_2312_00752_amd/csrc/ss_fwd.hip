@@ -416,8 +416,33 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     auto ld = [](const T* p, long i) -> float {
         if constexpr (sizeof(T) == 2) return bf16_to_f32(p[i]); else return p[i];
     };
-    const float u = ld(u_t, row);
-    float x = ld(dl_t, row) + ((a.flags & F_HAS_DELTA_BIAS) ? a.bias[d] : 0.0f);
+    // Every global load of the thread is requested here (and, on the vector path, right below),
+    // back to back: optional operands through a valid stand-in pointer, and no arithmetic on a
+    // loaded value in between, either of which would make the compiler wait for one load before
+    // issuing the next -- four memory round trips instead of one.
+    const bool has_bias = a.flags & F_HAS_DELTA_BIAS, has_D = a.flags & F_HAS_D, has_z = a.flags & F_HAS_Z;
+    const T u_raw = u_t[row], dl_raw = dl_t[row], z_raw = (has_z ? z_t : u_t)[row];
+    const float bias_raw = (has_bias ? a.bias : a.A)[has_bias ? d : 0];
+    const float D_raw = (has_D ? a.Dskip : a.A)[has_D ? d : 0];
+    float4 h4_first = make_float4(0.f, 0.f, 0.f, 0.f), A4_first = h4_first;
+    uint4 B_first = make_uint4(0u, 0u, 0u, 0u), C_first = B_first;   // bf16: two words each; float: four
+    if constexpr (FULLN) {
+        h4_first = *reinterpret_cast<const float4*>(a.h + row * N + q * STATES_PER_LANE);
+        A4_first = *reinterpret_cast<const float4*>(a.A + (long)d * NPAD + q * STATES_PER_LANE);
+        const long bo = (long)b * a.bc_stride + q * STATES_PER_LANE;
+        if constexpr (sizeof(T) == 2) {
+            const uint2 Bw = *reinterpret_cast<const uint2*>(B_t + bo), Cw = *reinterpret_cast<const uint2*>(C_t + bo);
+            B_first.x = Bw.x; B_first.y = Bw.y; C_first.x = Cw.x; C_first.y = Cw.y;
+        } else {
+            B_first = *reinterpret_cast<const uint4*>(B_t + bo);
+            C_first = *reinterpret_cast<const uint4*>(C_t + bo);
+        }
+    }
+    auto cvt = [](T v) -> float {
+        if constexpr (sizeof(T) == 2) return bf16_to_f32(v); else return v;
+    };
+    const float u = cvt(u_raw);
+    float x = cvt(dl_raw) + (has_bias ? bias_raw : 0.0f);
     float dt = x, sg;
     if (a.flags & F_DELTA_SOFTPLUS) softplus_sigmoid(x, dt, sg);
     const float du = ZOH ? u : dt * u, dt2 = dt * LOG2E;
@@ -427,22 +452,18 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     for (int n0 = 0; n0 < (FULLN ? NPAD : N); n0 += NPAD) {
         float hv[STATES_PER_LANE], Av[STATES_PER_LANE], Bv[STATES_PER_LANE], Cv[STATES_PER_LANE];
         float* hp = a.h + row * N + n0 + q * STATES_PER_LANE;
-        if (FULLN) {
-            const float4 h4 = *reinterpret_cast<const float4*>(hp);
-            const float4 A4 = *reinterpret_cast<const float4*>(a.A + (long)d * NPAD + q * STATES_PER_LANE);
+        if (FULLN) {   // one pass; loaded above
+            const float4 h4 = h4_first, A4 = A4_first;
             hv[0] = h4.x; hv[1] = h4.y; hv[2] = h4.z; hv[3] = h4.w;
             Av[0] = A4.x; Av[1] = A4.y; Av[2] = A4.z; Av[3] = A4.w;
-            const long bo = (long)b * a.bc_stride + q * STATES_PER_LANE;
             if constexpr (sizeof(T) == 2) {
-                const uint2 Bw = *reinterpret_cast<const uint2*>(B_t + bo);
-                const uint2 Cw = *reinterpret_cast<const uint2*>(C_t + bo);
-                Bv[0] = bf16_lo(Bw.x); Bv[1] = bf16_hi(Bw.x); Bv[2] = bf16_lo(Bw.y); Bv[3] = bf16_hi(Bw.y);
-                Cv[0] = bf16_lo(Cw.x); Cv[1] = bf16_hi(Cw.x); Cv[2] = bf16_lo(Cw.y); Cv[3] = bf16_hi(Cw.y);
+                Bv[0] = bf16_lo(B_first.x); Bv[1] = bf16_hi(B_first.x); Bv[2] = bf16_lo(B_first.y); Bv[3] = bf16_hi(B_first.y);
+                Cv[0] = bf16_lo(C_first.x); Cv[1] = bf16_hi(C_first.x); Cv[2] = bf16_lo(C_first.y); Cv[3] = bf16_hi(C_first.y);
             } else {
-                const float4 B4 = *reinterpret_cast<const float4*>(B_t + bo);
-                const float4 C4 = *reinterpret_cast<const float4*>(C_t + bo);
-                Bv[0] = B4.x; Bv[1] = B4.y; Bv[2] = B4.z; Bv[3] = B4.w;
-                Cv[0] = C4.x; Cv[1] = C4.y; Cv[2] = C4.z; Cv[3] = C4.w;
+                Bv[0] = __uint_as_float(B_first.x); Bv[1] = __uint_as_float(B_first.y);
+                Bv[2] = __uint_as_float(B_first.z); Bv[3] = __uint_as_float(B_first.w);
+                Cv[0] = __uint_as_float(C_first.x); Cv[1] = __uint_as_float(C_first.y);
+                Cv[2] = __uint_as_float(C_first.z); Cv[3] = __uint_as_float(C_first.w);
             }
         } else {
 #pragma unroll
@@ -488,9 +509,9 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     // sum over the 4 lanes of the row
     y += __shfl_xor(y, 1);
     y += __shfl_xor(y, 2);
-    if (a.flags & F_HAS_D) y = fmaf(a.Dskip[d], u, y);
-    if (a.flags & F_HAS_Z) {
-        const float z = ld(z_t, row);
+    if (has_D) y = fmaf(D_raw, u, y);
+    if (has_z) {
+        const float z = cvt(z_raw);
         y *= z * sigmoid_fast(z);
     }
     if (row_ok && q == 0) {
