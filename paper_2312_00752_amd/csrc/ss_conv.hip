@@ -312,21 +312,36 @@ __global__ void conv_step_kernel(T* __restrict__ state, const T* __restrict__ x_
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= rows) return;
     const int d = r % D;
-    float k4[TAPS];
-    load_taps(w, d, W, k4);
+    // Everything is requested up front, from clamped (valid) addresses and with no arithmetic on a
+    // loaded value in between; masked afterwards.  Written with a test per load, the compiler
+    // waited for each in turn, and the window was shifted through memory: seven round trips.
+    const int lead = TAPS - W;             // unused leading slots of the right-aligned window
     T* s = state + (size_t)r * (W - 1);
-    float win[TAPS];   // right-aligned window: win[3] is the new sample
+    float kr[TAPS];
+    T sr[HALO];
 #pragma unroll
-    for (int j = 0; j < HALO; ++j) {
-        const int idx = j - (TAPS - W);
-        win[j] = idx >= 0 ? io_to_f32<T>(s[idx]) : 0.0f;
-    }
+    for (int j = 0; j < TAPS; ++j) kr[j] = w[(size_t)d * W + max(j - lead, 0)];
     const T xt = x_t[r];
+    const float braw = (bias ? bias : w)[bias ? d : 0];
+    if (W > 1) {
+#pragma unroll
+        for (int j = 0; j < HALO; ++j) sr[j] = s[max(j - lead, 0)];
+    } else {
+#pragma unroll
+        for (int j = 0; j < HALO; ++j) sr[j] = xt;
+    }
+    float k4[TAPS], win[TAPS];   // win[3] is the new sample
+#pragma unroll
+    for (int j = 0; j < TAPS; ++j) k4[j] = j >= lead ? kr[j] : 0.0f;
+#pragma unroll
+    for (int j = 0; j < HALO; ++j) win[j] = j >= lead ? io_to_f32<T>(sr[j]) : 0.0f;
     win[3] = io_to_f32<T>(xt);
-    const float v = conv_at(k4, bias ? bias[d] : 0.0f, win);
+    const float v = conv_at(k4, bias ? braw : 0.0f, win);
     out_t[r] = f32_to_io<T>(SILU ? v * sigmoid_fast(v) : v);
-    for (int idx = 0; idx < W - 2; ++idx) s[idx] = s[idx + 1];
-    if (W > 1) s[W - 2] = xt;
+    // the window slides by one sample: slot j takes slot j + 1, the last slot the new sample
+#pragma unroll
+    for (int j = 0; j < HALO; ++j)
+        if (j >= lead) s[j - lead] = j == HALO - 1 ? xt : sr[j + 1 < HALO ? j + 1 : j];
 }
 
 // ---- host ---------------------------------------------------------------------------------------
