@@ -92,6 +92,15 @@ def test_short_sequences(seqlen):
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("seqlen,dim", [(8, 70), (40, 64), (72, 130), (104, 33), (200, 257)])
+def test_whole_slices_with_ragged_chunks_and_rows(io, seqlen, dim):
+    """Lengths that are multiples of 8 take the 16-byte, buffer-addressed path; these are not multiples of
+    the 32-step chunk, and the channel counts leave a partly filled 64-row group (rows past D and steps past
+    L are switched off by out-of-range offsets, not by branches)."""
+    check_bwd(wl.make_scan_inputs(3, seqlen, dim, 16, io=io, seed=160 + seqlen))
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
 def test_initial_state_and_last_state_gradient(io):
     w = wl.make_scan_inputs(2, 150, 70, 16, io=io, seed=160)
     rng = np.random.default_rng(161)
