@@ -191,6 +191,7 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
     a.seg_h = nullptr;
     a.seg_sumdt = nullptr;
     a.bcs = nullptr; a.Lp = 0;
+    a.W_dt = nullptr; a.rT = nullptr; a.R = 0; a.Rp = 0;
     return a;
 }
 
@@ -221,11 +222,27 @@ void narrow_to_group(ss::FwdArgs& a, const ss_fwd_params* p, int g, size_t ckpt_
 
 namespace ss {
 
-int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
+// The fused projection exists for the plain bf16 kernel on an unsplit sequence of whole 8-step
+// slices, with a workspace for the repacked operands.
+bool scan_fwd_fusable(const ss_fwd_params* p, int R)
+{
+    if (!p || p->seqlen < 1 || p->io_dtype != SS_BF16 || !stageable(p) || slots(p) > 16) return false;
+    if (R < 8 || R % 8 != 0 || R > 256 || (p->flags & SS_EXACT_ZOH_B)) return false;
+    if (p->seqlen % 8 != 0 || (size_t)p->seqlen * 64 * sizeof(float) >= ((size_t)1 << 31)) return false;
+    if (plan_segments(p->batch, p->dim, p->seqlen, p->flags).nseg != 1) return false;
+    return p->workspace && aligned(p->workspace, 256) &&
+           p->workspace_bytes >= ws_layout(p, (p->flags & SS_SAVE_FOR_BWD) != 0).total;
+}
+
+static int scan_fwd_impl(const ss_fwd_params* p, long bc_bstride, const void* W_dt, int R, const void* rT, void* stream)
 {
     const int rc = check_fwd(p, false, p && bc_bstride == (long)slots(p) * p->seqlen);
     if (rc != SS_OK) return rc;
     ss::FwdArgs a = make_fwd_args(p, bc_bstride);
+    if (W_dt) {
+        if (!scan_fwd_fusable(p, R) || !aligned(W_dt, 16) || !aligned(rT, 16)) return SS_ERR_UNSUPPORTED;
+        a.W_dt = W_dt; a.rT = rT; a.R = R; a.Rp = (R + 31) / 32 * 32;
+    }
     char* ws = static_cast<char*>(p->workspace);
     const int groups = p->seqlen == 0 ? 1 : (slots(p) + 15) / 16;
     size_t ckpt_group = 0;
@@ -268,6 +285,17 @@ int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
     return SS_OK;
 }
 
+
+int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream)
+{
+    return scan_fwd_impl(p, bc_bstride, nullptr, 0, nullptr, stream);
+}
+
+int scan_fwd_fused(const ss_fwd_params* p, long bc_bstride, const void* W_dt, int R, const void* rT, void* stream)
+{
+    if (!W_dt || !rT) return SS_ERR_NULL;
+    return scan_fwd_impl(p, bc_bstride, W_dt, R, rT, stream);
+}
 
 int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream)
 {

@@ -5,6 +5,9 @@
 
 namespace ss {
 
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));   // MFMA operand and accumulator types
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
 // One workgroup = 64 rows x 4 waves.  Per chunk of CHUNK_T steps:
 //   A. (pointwise view) load 64 rows x 32 steps of u, delta, z with 16-byte accesses, form
 //      dt = softplus(delta + bias) and dt*u, park them in LDS;
@@ -32,12 +35,22 @@ namespace ss {
 // widen bf16.  (Read in place, the eight loads of the next group compete with the current
 // group's operands for scalar registers, some are issued only right before their use, and the
 // wait for those drains the whole prefetch: the loads' latency shows once per group.)
-template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false>
+// FUSED_KS > 0 (bf16, VEC, STAGED, main pass of an unsplit sequence): delta_raw = W_dt r is not
+// read but formed here, per chunk, as a 64 x 32 product over R <= 32 * FUSED_KS on the matrix
+// cores: wave w owns rows 16w..16w+15 (its pieces of W_dt stay in registers for the whole
+// kernel) and both 16-step halves of the chunk; the result goes through the dt tile in LDS to
+// the pointwise threads, rounded to bf16 as the stored delta would be.  Saves the projection
+// kernel and the write and read of a (B,D,L) tensor.
+template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false,
+          int FUSED_KS = 0>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
     __shared__ __attribute__((aligned(16))) float s_du[ROWS][TPAD];
     __shared__ __attribute__((aligned(16))) float s_yp[NWAVES][ROWS][TPAD];
+    __shared__ __attribute__((aligned(16))) float s_raw[FUSED_KS > 0 ? ROWS : 1][TPAD];   // FUSED: delta_raw of the next chunk
+    constexpr int RT_PITCH = 32 * (FUSED_KS > 0 ? FUSED_KS : 1) + 8;                     // bf16 elements; rows 16 bytes off the banks
+    __shared__ __attribute__((aligned(16))) bf16_t s_rT[FUSED_KS > 0 ? CHUNK_T : 1][RT_PITCH];   // FUSED: r of the next chunk's steps
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, provably uniform
@@ -122,6 +135,28 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     };
     float sum_dt = 0.0f;  // AGG: this thread's share of the segment's sum of step sizes
 
+    // FUSED: operand fragments of the 16x16x32 bf16 MFMA.  Lane l holds row (column) l % 16 of
+    // the first (second) operand at contraction indices 8 * (l / 16) ..+7 of each 32-wide step;
+    // accumulator element i of lane l is row 4 * (l / 16) + i, column l % 16.
+    constexpr int KS = FUSED_KS > 0 ? FUSED_KS : 1;
+    union Frag { unsigned short s[8]; bf16x8_t v; };
+    Frag wfr[KS];
+    constexpr int RLD = (KS + 1) / 2;          // 16-byte pieces of the chunk's r per thread: 32 steps x Rp / 256 threads
+    Frag rld[RLD];
+    const int fsub = 8 * (lane >> 4);
+    const int rt_t = tid >> 3, rt_col = (tid & 7) * 4 * KS;   // this thread's piece of the (32 steps, Rp) tile
+    if constexpr (FUSED_KS > 0) {
+        const bf16_t* wp = static_cast<const bf16_t*>(a.W_dt) + (long)min(d0 + 16 * w + (lane & 15), a.D - 1) * a.R;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int k = 32 * ks + fsub;
+            wfr[ks].v = *reinterpret_cast<const bf16x8_t*>(wp + min(k, a.R - 8));   // R is a multiple of 8
+            if (k >= a.R) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wfr[ks].s[e] = 0;
+            }
+        }
+    }
     typename io8<T>::raw ru, rd, rz;
     auto issue_loads = [&](int c) {
         const int t0 = c * CHUNK_T + pq * SLICE;
@@ -129,7 +164,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         if constexpr (VEC) {   // slices are whole or empty
             const uint32_t off = nv == SLICE ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
             ru = io8<T>::load_buf(bu, off);
-            rd = io8<T>::load_buf(bd, off);
+            if constexpr (FUSED_KS == 0) rd = io8<T>::load_buf(bd, off);
             rz = io8<T>::load_buf(bz, off);
         } else {
             ru = io8<T>::template load<VEC>(gu + t0, nv);
@@ -137,7 +172,58 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
         }
     };
+    // FUSED: delta_raw of a chunk from the fragments in registers: two 16 x 16 tiles per wave,
+    // into rows 16w..16w+15 of s_raw -- the rows this wave's own pointwise threads read, so the
+    // exchange needs no workgroup barrier (a wave's LDS instructions execute in order).  Called
+    // for the next chunk after the recurrence, where the matrix-core latency hides behind the
+    // pointwise post-processing.
+    auto project = [&]() {
+        if constexpr (FUSED_KS > 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // earlier reads of s_raw are done
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    if (32 * ks < a.Rp) {
+                        const bf16x8_t rv = *reinterpret_cast<const bf16x8_t*>(&s_rT[16 * nt + (lane & 15)][32 * ks + fsub]);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfr[ks].v, rv, acc, 0, 0, 0);
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_raw[16 * w + 4 * (lane >> 4) + i][16 * nt + (lane & 15)] = acc[i];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    };
+    // FUSED: r of a chunk's 32 steps (transposed and padded, so always in range) is read once per
+    // workgroup, two chunks ahead into registers, one chunk ahead into LDS
+    auto issue_r = [&](int c) {
+        if constexpr (FUSED_KS > 0) {
+            const bf16_t* rp = static_cast<const bf16_t*>(a.rT) + ((long)b * a.Lp + min(max(c, 0) * CHUNK_T, a.Lp - CHUNK_T) + rt_t) * a.Rp;
+#pragma unroll
+            for (int j = 0; j < RLD; ++j)
+                rld[j].v = *reinterpret_cast<const bf16x8_t*>(rp + min(rt_col + 8 * j, a.Rp - 8));
+        }
+    };
+    auto stage_r = [&]() {   // this thread's piece of the chunk's r, from registers to LDS
+        if constexpr (FUSED_KS > 0) {
+#pragma unroll
+            for (int j = 0; j < RLD; ++j)
+                if (rt_col + 8 * j < a.Rp) *reinterpret_cast<bf16x8_t*>(&s_rT[rt_t][rt_col + 8 * j]) = rld[j].v;
+        }
+    };
     issue_loads(c_begin);
+    if constexpr (FUSED_KS > 0) {
+        issue_r(c_begin);
+        stage_r();
+        __syncthreads();
+        project();
+        __syncthreads();   // s_rT is rewritten in the first chunk's phase A
+        issue_r(c_begin + 1);
+    }
     uint32_t touched = 0u;
     if (BCFIX != 3) touched = touch(c_begin * CHUNK_T);
 
@@ -148,7 +234,15 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         const int nv = min(max(L - t0, 0), SLICE);
         // ---- A: pointwise pre-processing --------------------------------------------
         io8<T>::unpack(ru, u8);
-        io8<T>::unpack(rd, v8);
+        if constexpr (FUSED_KS > 0) {   // delta_raw of this chunk: left in s_raw by this same wave (project)
+            const float4 d0v = *reinterpret_cast<const float4*>(&s_raw[pr][pq * SLICE]);
+            const float4 d1v = *reinterpret_cast<const float4*>(&s_raw[pr][pq * SLICE + 4]);
+            const float raw[SLICE] = {d0v.x, d0v.y, d0v.z, d0v.w, d1v.x, d1v.y, d1v.z, d1v.w};
+#pragma unroll
+            for (int j = 0; j < SLICE; ++j) v8[j] = bf16_to_f32(bf16_t(f32_to_bf16_bits(raw[j])));   // as the stored delta would be
+        } else {
+            io8<T>::unpack(rd, v8);
+        }
         if (has_z) io8<T>::unpack(rz, z8);
         {
             float dt8[SLICE], du8[SLICE];
@@ -189,6 +283,10 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         };
         save_ckpt(c * (CHUNK_T / CKPT_T));
         if (c + 1 < c_end) issue_loads(c + 1);  // in flight during the scan below
+        if constexpr (FUSED_KS > 0) {
+            stage_r();          // r of chunk c + 1, requested a chunk ago; read by project() after the recurrence
+            issue_r(c + 2);
+        }
         __syncthreads();
         // ---- B: sequential recurrence over the chunk ---------------------------------
         constexpr int NG = CHUNK_T / GROUP_T;
@@ -283,6 +381,8 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             if (!AGG)
                 *reinterpret_cast<float4*>(&s_yp[w][lane][tl]) = make_float4(yp[0], yp[1], yp[2], yp[3]);
         }
+        // delta_raw of the next chunk, before the barrier: the next phase A rewrites s_rT after it
+        if (c + 1 < c_end) project();
         __syncthreads();
         // ---- C: pointwise post-processing --------------------------------------------
         if (!AGG) {
@@ -530,8 +630,6 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
 // as in step_kernel and walks its eight batch entries.  The state, u and z of those entries are
 // requested before anything else, so that their latency overlaps the projection.  Real, first-order,
 // selective B / C only; R <= 256 and a multiple of 8, N <= 16.
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int SP_BT = 16;                         // batch entries per workgroup: the rows of the MFMA tile
 constexpr int SP_THREADS = 512;                   // 64 channels x 4 quarters x 2 halves of the batch tile
 constexpr int SP_PER = SP_BT / 2;                 // batch entries per thread
@@ -809,6 +907,15 @@ static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
         scan_fwd_kernel<T, VEC, FULLN, true, ZOH, 0, false, true><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
         const long n = (long)a.B * a.D * NPAD;
         carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    }
+    if constexpr (sizeof(T) == 2 && VEC && !ZOH) {
+        if (a.W_dt) {   // the caller has checked: unsplit, repacked B / C present, R <= 256
+            if (a.Rp <= 128)
+                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 4><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
+            else
+                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 8><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
+            return;
+        }
     }
     if (a.bcs)
         scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);

@@ -36,6 +36,11 @@ struct FwdArgs {
     // wave needs for a group of 4 steps is then one contiguous 64- (bf16) or 128-byte piece.
     const void* bcs;
     int Lp;
+    // Layer forward, bf16: instead of reading delta, the kernel forms delta_raw = W_dt r on the
+    // matrix cores.  W_dt (D, R) row-major; rT (B, Lp, Rp): r transposed, zero-padded to Rp = R
+    // rounded up to 32 and to Lp steps.  Null W_dt: delta is read from memory.
+    const void *W_dt, *rT;
+    int R, Rp;
     const float *A, *Dskip, *bias, *h0;
     void* out;
     float* h_last;  // may be null
@@ -96,6 +101,12 @@ int launch_step_projected(const StepArgs& a, hipStream_t stream);   // bf16 I/O 
 // start b * bc_bstride elements after Bmat / Cmat (the public calls pass dstate * seqlen).
 // Validation and return codes are those of ss_scan_fwd / ss_scan_bwd.
 int scan_fwd_strided(const ss_fwd_params* p, long bc_bstride, void* stream);
+// The same with delta_raw = W_dt r formed inside the scan kernel (bf16): W_dt (D, R) row-major,
+// rT (B, Lp, Rp) = r transposed and zero-padded, Lp = L rounded up to 32, Rp = R rounded up to 32;
+// p->delta is not read.  Returns SS_ERR_UNSUPPORTED, before anything is enqueued, when the call
+// does not qualify (then use scan_fwd_strided with delta in memory).
+int scan_fwd_fused(const ss_fwd_params* p, long bc_bstride, const void* W_dt, int R, const void* rT, void* stream);
+bool scan_fwd_fusable(const ss_fwd_params* p, int R);   // whether scan_fwd_fused would take the call
 int scan_bwd_strided(const ss_bwd_params* p, long bc_bstride, void* stream);
 // ss_step with B_t / C_t rows bc_stride elements apart (the public call passes dstate).
 int step_strided(const ss_step_params* p, long bc_stride, void* stream);

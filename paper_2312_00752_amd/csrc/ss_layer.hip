@@ -173,6 +173,28 @@ __global__ void __launch_bounds__(64 * XP_WAVES) xproj_decode_kernel(const ss::b
     }
 }
 
+// r (the first R rows of each batch entry of P, (B, Mx, L)) transposed and zero-padded to
+// (B, Lp, Rp), for the delta projection inside the scan kernel (see FwdArgs::rT).  32 x 32 tiles
+// through LDS; block (32, 8), grid (Lp / 32, Rp / 32, B).
+__global__ void transpose_r_kernel(const ss::bf16_t* __restrict__ P, long bstride, ss::bf16_t* __restrict__ rT, int R, int L,
+                                   int Lp, int Rp)
+{
+    __shared__ ss::bf16_t tile[32][33];
+    const int t0 = blockIdx.x * 32, r0 = blockIdx.y * 32, b = blockIdx.z;
+    const int tx = threadIdx.x, ty = threadIdx.y;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = r0 + ty + 8 * i, t = t0 + tx;
+        tile[ty + 8 * i][tx] = (r < R && t < L) ? P[(size_t)b * bstride + (size_t)r * L + t] : ss::bf16_t(0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = t0 + ty + 8 * i, r = r0 + tx;
+        rT[((size_t)b * Lp + t) * Rp + r] = tile[tx][ty + 8 * i];
+    }
+}
+
 // ---- buffers -------------------------------------------------------------------------------------
 struct Shape {
     size_t B, D, L, N, R, Mx, esz;
@@ -209,10 +231,10 @@ SavedLayout saved_layout(const ss_layer_params* p)
     return w;
 }
 
-// scratch: forward  [u][delta][P and the scan's split scratch, used if nothing is saved]
+// scratch: forward  [u][delta][P and the scan's split scratch, used if nothing is saved][r transposed and padded, bf16]
 //          backward [u][delta][du][ddelta][dP (B,Mx,L) io][dB, dC (B,N,L) f32]
 //                   [partials of dW_dt (B,D,R) io][partials of dW_x (B,Mx,D) io]
-struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, du, ddelta, dP, dB, dC, part_dt, part_x, total; };
+struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, rT, du, ddelta, dP, dB, dC, part_dt, part_x, total; };
 ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
 {
     const Shape s = shape_of(p);
@@ -227,6 +249,7 @@ ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
         const ss_fwd_params f = scan_params(p);
         w.scan_ws_bytes = ss_workspace_bytes(&f, 0);
         w.scan_ws = take(w.scan_ws_bytes);
+        w.rT = take(s.B * round_up(s.L, 32) * round_up(s.R, 32) * s.esz);
     } else {
         w.du = take(T);
         w.ddelta = take(T);
@@ -329,9 +352,6 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     // [r;B;C] = W_x @ u
     if (!gemm_rm(h, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16))
         return SS_ERR_BACKEND;
-    // delta_raw = W_dt @ r
-    if (!gemm_rm(h, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
-        return SS_ERR_BACKEND;
     ss_fwd_params f = scan_params(p);
     f.u = u; f.delta = delta; f.z = p->z;
     f.Bmat = P + (size_t)R * L * s.esz;
@@ -350,6 +370,19 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
         f.workspace = scratch + sc.scan_ws;   // lets a long sequence with few rows be split
         f.workspace_bytes = sc.scan_ws_bytes;
     }
+    // bf16: delta_raw = W_dt r is formed inside the scan kernel where that variant applies
+    if (ss::scan_fwd_fusable(&f, R)) {
+        ss::bf16_t* rT = reinterpret_cast<ss::bf16_t*>(scratch + sc.rT);
+        const int Lp = (L + 31) / 32 * 32, Rp = (R + 31) / 32 * 32;
+        hipLaunchKernelGGL(transpose_r_kernel, dim3((unsigned)(Lp / 32), (unsigned)(Rp / 32), (unsigned)B), dim3(32, 8), 0, st,
+                           reinterpret_cast<const ss::bf16_t*>(P), (long)Mx * L, rT, R, L, Lp, Rp);
+        if (hipGetLastError() != hipSuccess) return SS_ERR_LAUNCH;
+        rc = ss::scan_fwd_fused(&f, (long)Mx * L, p->W_dt, R, rT, stream);
+        if (rc != SS_ERR_UNSUPPORTED) return rc;   // otherwise nothing was enqueued: take the general path
+    }
+    // delta_raw = W_dt @ r
+    if (!gemm_rm(h, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
+        return SS_ERR_BACKEND;
     return ss::scan_fwd_strided(&f, (long)Mx * L, stream);
 }
 
