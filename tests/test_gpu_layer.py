@@ -64,6 +64,18 @@ def test_layer_small(io, shape):
     _check(make_layer_inputs(batch, seqlen, dim, dstate, io, seed=seqlen, rank=rank))
 
 
+# bf16 with R % 8 == 0 and L % 8 == 0: the forward scan projects delta itself, in contraction steps of
+# 32 over R (4 or 8 of them), on whole and on split sequences, with ragged last chunks and channel groups
+@pytest.mark.parametrize("shape", [(1, 2048, 128, 16, 160), (1, 1024, 192, 16, 256), (2, 1144, 100, 12, 136),
+                                   (1, 4096, 64, 16, 128), (5, 72, 320, 16, 64)])
+def test_layer_projection_inside_scan(shape):
+    batch, seqlen, dim, dstate, rank = shape
+    w = make_layer_inputs(batch, seqlen, dim, dstate, "bf16", seed=rank, rank=rank)
+    out, _ = _gpu(w, backward=False)
+    ref = inn.inner_fwd(rnd=_rnd("bf16"), nthreads=0, **{k: w[k] for k in PARAMS})
+    assert_close(out, ref["out"], "bf16", "out")
+
+
 def test_layer_narrow_conv_and_long_sequence():
     _check(make_layer_inputs(1, 4096, 128, 16, "bf16", seed=5, width=2))
     _check(make_layer_inputs(1, 2560, 64, 16, "f32", seed=6, width=3))
