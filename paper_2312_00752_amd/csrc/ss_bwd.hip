@@ -111,8 +111,9 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & (WAVE - 1);
     const int groups = (f.D + ROWS - 1) / ROWS;
-    const int b = blockIdx.x / groups;
-    const int d0 = (blockIdx.x % groups) * ROWS;
+    const unsigned bx = xcd_contiguous(blockIdx.x, gridDim.x);  // one batch entry's row groups per XCD (see scan_fwd_kernel)
+    const int b = bx / groups;
+    const int d0 = (bx % groups) * ROWS;
     const int L = f.L, N = f.N, NS = f.NS;
     const bool has_z = f.flags & F_HAS_Z, has_D = f.flags & F_HAS_D;
     const bool softplus = f.flags & F_DELTA_SOFTPLUS;
@@ -469,8 +470,9 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & (WAVE - 1);
     const int groups = (f.D + ROWS - 1) / ROWS;
-    const int b = blockIdx.x / groups;
-    const int d0 = (blockIdx.x % groups) * ROWS;
+    const unsigned bx = xcd_contiguous(blockIdx.x, gridDim.x);  // one batch entry's row groups per XCD (see scan_fwd_kernel)
+    const int b = bx / groups;
+    const int d0 = (bx % groups) * ROWS;
     const int L = f.L, N = f.N, NS = f.NS;
     const bool has_z = f.flags & F_HAS_Z, softplus = f.flags & F_DELTA_SOFTPLUS;
     const int seg = blockIdx.y + 1;  // segment 0 passes nothing on

@@ -123,6 +123,16 @@ __device__ __forceinline__ uint4 load16_once(const void* p)
     return make_uint4(x.x, x.y, x.z, x.w);
 }
 
+// ---- workgroup numbering ---------------------------------------------------------------
+// The dispatcher hands consecutive workgroup indices to the chip's eight XCDs in turn, and each
+// XCD has an L2 of its own.  Renumbered like this, XCD x works on indices [x*n/8, (x+1)*n/8):
+// neighbours in the index (row groups of one batch entry) share an L2.  A bijection on [0, n)
+// whenever it applies (n a multiple of 8); the identity otherwise.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned i, unsigned n)
+{
+    return (n % 8u == 0u) ? (i % 8u) * (n / 8u) + i / 8u : i;
+}
+
 // ---- buffer-addressed accesses ---------------------------------------------------------
 // Memory operations retire in order and the compiler can let younger ones stay outstanding
 // across a wait only if it can count them: a store or load inside an `if` counts as "maybe

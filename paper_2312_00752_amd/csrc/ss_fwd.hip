@@ -56,8 +56,11 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, provably uniform
     const int lane = tid & (WAVE - 1);
     const int groups = (a.D + ROWS - 1) / ROWS;
-    const int b = blockIdx.x / groups;
-    const int d0 = (blockIdx.x % groups) * ROWS;
+    // Workgroups go to the eight XCDs in turn by index; with this renumbering each XCD gets a contiguous
+    // run of row groups, i.e. one batch entry's rows, whose shared operands (B, C, r) then meet in its L2.
+    const unsigned bx = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int b = bx / groups;
+    const int d0 = (bx % groups) * ROWS;
     const int L = a.L, N = a.N, NS = a.NS;
     const bool has_z = !AGG && (a.flags & F_HAS_Z), has_D = !AGG && (a.flags & F_HAS_D);
     const bool softplus = a.flags & F_DELTA_SOFTPLUS;
