@@ -87,12 +87,14 @@ def test_layer_full_size_bf16():
 
 
 # bf16 shapes with D % 32 == 0 and R % 8 == 0 take the hand-written matrix-core decode path (ragged
-# batch tiles of 16, ragged 64-channel groups, N below 16, R off and at the limits of the 32-wide
+# batch tiles of 8 and of 16, ragged 64-channel groups, N below 16, R off and at the limits of the 32-wide
 # contraction steps); the others take the library GEMMs
 @pytest.mark.parametrize("io,shape", [("bf16", (4, 96, 256, 16, 8)), ("f32", (2, 40, 72, 5, 3)), ("bf16", (1, 33, 128, 16, 6)),
                                       ("bf16", (21, 40, 96, 8, 40)), ("bf16", (1, 20, 64, 16, 256)),
                                       ("bf16", (17, 24, 160, 12, 24)), ("bf16", (3, 20, 32, 16, 16)),
-                                      ("f32", (3, 20, 64, 16, 8))])
+                                      ("f32", (3, 20, 64, 16, 8)),
+                                      # enough (channel group, 16-entry batch tile) pairs for the wide tiles
+                                      ("bf16", (250, 13, 1056, 16, 40)), ("bf16", (244, 14, 1088, 12, 24))])
 def test_layer_prompt_then_token_by_token(io, shape):
     """Recurrent mode (Section 2): a prompt in parallel mode hands its states to single-token steps;
     the outputs must equal the parallel mode over the whole sequence."""
