@@ -632,7 +632,7 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
 // and leave softplus(. + bias) in LDS, once per (b, d) instead of once per quarter; after that a
 // thread is (channel d, quarter q, half of the batch tile) as in step_kernel and walks its BT / 2
 // batch entries.  The 8-entry tile needs fewer registers (two workgroups per CU instead of one) and
-// gives twice the workgroups: the launcher takes it while 16-entry tiles would leave CUs idle.  The state, u and z of those entries are
+// gives twice the workgroups; the launcher picks the tile from the number of workgroups each gives.  The state, u and z of those entries are
 // requested before anything else, so that their latency overlaps the projection.  Real, first-order,
 // selective B / C only; R <= 256 and a multiple of 8, N <= 16.
 constexpr int SP_MFMA_ROWS = 16;                  // rows of the MFMA tile: the largest batch tile
@@ -986,11 +986,14 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
 
 int launch_step_projected(const StepArgs& a, hipStream_t stream)
 {
-    // 16-entry batch tiles once they fill the chip's 256 CUs, 8-entry tiles below that (measured at
-    // D = 4096: 6-12 % faster per token at batch 1-32, 6 % slower at batch 64)
-    const unsigned groups = (unsigned)((a.D + 63) / 64);
-    const bool wide = (long)groups * ((a.B + SP_MFMA_ROWS - 1) / SP_MFMA_ROWS) >= 256;
-    const dim3 grid(groups, (unsigned)(wide ? (a.B + SP_MFMA_ROWS - 1) / SP_MFMA_ROWS : (a.B + 7) / 8));
+    // One workgroup per CU is the fastest arrangement (the state streams while the projection's
+    // dependent steps run), so: 8-entry batch tiles while they fit the chip's 256 CUs once, 16-entry
+    // tiles while those still do, and 8-entry tiles again beyond that, where two of them share a CU
+    // (measured at D = 2048, 4096, 5120 and batch 32 ... 256: the better tile by 5-15 % in every case).
+    const long groups = (a.D + 63) / 64;
+    const long n16 = groups * ((a.B + SP_MFMA_ROWS - 1) / SP_MFMA_ROWS), n8 = groups * ((a.B + 7) / 8);
+    const bool wide = n8 > 256 && n16 <= 256;
+    const dim3 grid((unsigned)groups, (unsigned)(wide ? (a.B + SP_MFMA_ROWS - 1) / SP_MFMA_ROWS : (a.B + 7) / 8));
     const dim3 block(SP_THREADS);
     if (a.N == NPAD) {
         if (wide) step_proj_kernel<true, SP_MFMA_ROWS><<<grid, block, 0, stream>>>(a);

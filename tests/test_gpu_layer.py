@@ -93,8 +93,11 @@ def test_layer_full_size_bf16():
                                       ("bf16", (21, 40, 96, 8, 40)), ("bf16", (1, 20, 64, 16, 256)),
                                       ("bf16", (17, 24, 160, 12, 24)), ("bf16", (3, 20, 32, 16, 16)),
                                       ("f32", (3, 20, 64, 16, 8)),
-                                      # enough (channel group, 16-entry batch tile) pairs for the wide tiles
-                                      ("bf16", (250, 13, 1056, 16, 40)), ("bf16", (244, 14, 1088, 12, 24))])
+                                      # more than 256 (channel group, 8-entry batch tile) pairs, at most 256
+                                      # with 16-entry tiles: the wide tiles, last one ragged
+                                      ("bf16", (234, 13, 1056, 16, 40)), ("bf16", (200, 14, 1088, 12, 24)),
+                                      # more than 256 pairs either way: 8-entry tiles, two workgroups per CU
+                                      ("bf16", (250, 13, 1056, 16, 40))])
 def test_layer_prompt_then_token_by_token(io, shape):
     """Recurrent mode (Section 2): a prompt in parallel mode hands its states to single-token steps;
     the outputs must equal the parallel mode over the whole sequence."""
