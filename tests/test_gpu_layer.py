@@ -66,8 +66,11 @@ def test_layer_small(io, shape):
 
 # bf16 with R % 8 == 0 and L % 8 == 0: the forward scan projects delta itself, in contraction steps of
 # 32 over R (4 or 8 of them), on whole and on split sequences, with ragged last chunks and channel groups
-@pytest.mark.parametrize("shape", [(1, 2048, 128, 16, 160), (1, 1024, 192, 16, 256), (2, 1144, 100, 12, 136),
-                                   (1, 4096, 64, 16, 128), (5, 72, 320, 16, 64)])
+# The projection runs inside the scan only on unsplit sequences: 512 or more 64-row groups, or fewer than 128 steps
+@pytest.mark.parametrize("shape", [(32, 264, 1024, 16, 160), (16, 200, 2048, 12, 256), (64, 136, 512, 16, 72),
+                                   (32, 160, 1024, 16, 8), (5, 72, 320, 16, 64),
+                                   # split sequences: the library GEMM
+                                   (1, 2048, 128, 16, 160), (2, 1144, 100, 12, 136)])
 def test_layer_projection_inside_scan(shape):
     batch, seqlen, dim, dstate, rank = shape
     w = make_layer_inputs(batch, seqlen, dim, dstate, "bf16", seed=rank, rank=rank)
