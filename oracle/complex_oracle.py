@@ -6,7 +6,7 @@ TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
 The paper keeps the state real by default and switches to a complex state for one experiment
 (Section 3.6 "Real vs. Complex"; S4D-Lin initialisation A_n = -1/2 + n i); it does not spell
 the complex case out.  This oracle takes Eq. 2a/2b/4 over the complex numbers as they stand,
-with the real part as the output (the reading listed in the design notes):
+with the real part as the output (a reading: the paper does not say how y becomes real):
 
     abar_t,n = exp(dt_t * A[d,n])                       A, abar complex        (Eq. 4)
     h_t,n    = abar_t,n * h_{t-1,n} + dt_t * B[b,n,t] * u[b,d,t]   B, h complex (Eq. 2a, first-order B-bar)
