@@ -623,6 +623,96 @@ __global__ void __launch_bounds__(256) step_kernel(const StepArgs a)
     }
 }
 
+// Single-token step, the common case at scale (N == 16, real state, first-order B-bar, selective
+// B / C, vector-aligned operands): as step_kernel, with RPT batch entries (b, b + B/RPT, ...) of the
+// same channel per thread.  A, bias and D are fetched once for them, and RPT state vectors per lane
+// are in flight at once, which a streaming kernel this short needs to fill the memory pipeline.
+template <typename T, int RPT>
+__global__ void __launch_bounds__(256) step_multi_kernel(const StepArgs a)
+{
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long rowi = gid >> 2;
+    const int q = gid & 3;
+    const int bpart = a.B / RPT;                       // the launcher checks B % RPT == 0
+    const long rows_part = (long)bpart * a.D;
+    const bool row_ok = rowi < rows_part;
+    const long row0 = row_ok ? rowi : rows_part - 1;
+    const int b0 = row0 / a.D, d = row0 % a.D;
+    const T* u_t = static_cast<const T*>(a.u_t);
+    const T* dl_t = static_cast<const T*>(a.delta_t);
+    const T* z_t = static_cast<const T*>(a.z_t);
+    const T* B_t = static_cast<const T*>(a.B_t);
+    const T* C_t = static_cast<const T*>(a.C_t);
+    const bool has_bias = a.flags & F_HAS_DELTA_BIAS, has_D = a.flags & F_HAS_D, has_z = a.flags & F_HAS_Z;
+    // all loads first, none behind a branch or behind arithmetic on a loaded value (see step_kernel)
+    float4 h4[RPT];
+    T u_raw[RPT], dl_raw[RPT], z_raw[RPT];
+    uint4 Bw[RPT], Cw[RPT];
+    long row[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int b = b0 + i * bpart;
+        row[i] = (long)b * a.D + d;
+        h4[i] = *reinterpret_cast<const float4*>(a.h + row[i] * NPAD + q * STATES_PER_LANE);
+        u_raw[i] = u_t[row[i]];
+        dl_raw[i] = dl_t[row[i]];
+        z_raw[i] = (has_z ? z_t : u_t)[row[i]];
+        const long bo = (long)b * a.bc_stride + q * STATES_PER_LANE;
+        Bw[i] = make_uint4(0u, 0u, 0u, 0u);
+        Cw[i] = Bw[i];
+        if constexpr (sizeof(T) == 2) {
+            const uint2 x = *reinterpret_cast<const uint2*>(B_t + bo), y = *reinterpret_cast<const uint2*>(C_t + bo);
+            Bw[i].x = x.x; Bw[i].y = x.y; Cw[i].x = y.x; Cw[i].y = y.y;
+        } else {
+            Bw[i] = *reinterpret_cast<const uint4*>(B_t + bo);
+            Cw[i] = *reinterpret_cast<const uint4*>(C_t + bo);
+        }
+    }
+    const float4 A4 = *reinterpret_cast<const float4*>(a.A + (long)d * NPAD + q * STATES_PER_LANE);
+    const float bias_raw = (has_bias ? a.bias : a.A)[has_bias ? d : 0];
+    const float D_raw = (has_D ? a.Dskip : a.A)[has_D ? d : 0];
+    auto cvt = [](T v) -> float {
+        if constexpr (sizeof(T) == 2) return bf16_to_f32(v); else return v;
+    };
+    const float Av[STATES_PER_LANE] = {A4.x * LOG2E, A4.y * LOG2E, A4.z * LOG2E, A4.w * LOG2E};
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const float u = cvt(u_raw[i]);
+        float x = cvt(dl_raw[i]) + (has_bias ? bias_raw : 0.0f);
+        float dt = x, sg;
+        if (a.flags & F_DELTA_SOFTPLUS) softplus_sigmoid(x, dt, sg);
+        const float du = dt * u;
+        float hv[STATES_PER_LANE] = {h4[i].x, h4[i].y, h4[i].z, h4[i].w}, Bv[STATES_PER_LANE], Cv[STATES_PER_LANE];
+        if constexpr (sizeof(T) == 2) {
+            Bv[0] = bf16_lo(Bw[i].x); Bv[1] = bf16_hi(Bw[i].x); Bv[2] = bf16_lo(Bw[i].y); Bv[3] = bf16_hi(Bw[i].y);
+            Cv[0] = bf16_lo(Cw[i].x); Cv[1] = bf16_hi(Cw[i].x); Cv[2] = bf16_lo(Cw[i].y); Cv[3] = bf16_hi(Cw[i].y);
+        } else {
+            Bv[0] = __uint_as_float(Bw[i].x); Bv[1] = __uint_as_float(Bw[i].y); Bv[2] = __uint_as_float(Bw[i].z); Bv[3] = __uint_as_float(Bw[i].w);
+            Cv[0] = __uint_as_float(Cw[i].x); Cv[1] = __uint_as_float(Cw[i].y); Cv[2] = __uint_as_float(Cw[i].z); Cv[3] = __uint_as_float(Cw[i].w);
+        }
+        float y = 0.0f;
+#pragma unroll
+        for (int k = 0; k < STATES_PER_LANE; ++k) {
+            const float abar = exp2_fast(dt * Av[k]);                       // Eq. 4
+            hv[k] = fmaf(abar, hv[k], du * Bv[k]);                          // Eq. 2a
+            y = fmaf(Cv[k], hv[k], y);                                      // Eq. 2b
+        }
+        if (row_ok)
+            *reinterpret_cast<float4*>(a.h + row[i] * NPAD + q * STATES_PER_LANE) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        y += __shfl_xor(y, 1);
+        y += __shfl_xor(y, 2);
+        if (has_D) y = fmaf(D_raw, u, y);
+        if (has_z) {
+            const float z = cvt(z_raw[i]);
+            y *= z * sigmoid_fast(z);
+        }
+        if (row_ok && q == 0) {
+            if constexpr (sizeof(T) == 2) static_cast<bf16_t*>(a.out_t)[row[i]] = bf16_t(f32_to_bf16_bits(y));
+            else static_cast<float*>(a.out_t)[row[i]] = y;
+        }
+    }
+}
+
 // Single-token step of the layer's decode (bf16 I/O): as step_kernel, but delta_t, B_t and C_t come
 // from the float32 output P = [r; B; C] of the projection (the sum of STEP_NPARTS partial results,
 // rounded to bf16 as the layer stores it) and delta_t = W_dt r_t + bias is formed here.  A workgroup
@@ -972,6 +1062,22 @@ int launch_step(const StepArgs& a, int io_dtype, hipStream_t stream)
                      reinterpret_cast<uintptr_t>(a.B_t) % va == 0 &&
                      reinterpret_cast<uintptr_t>(a.C_t) % va == 0 && reinterpret_cast<uintptr_t>(a.A) % 16 == 0;
     const bool zoh = a.flags & F_EXACT_ZOH_B;
+    // Several batch entries per thread once that still leaves every CU its 2048 threads
+    if (vec && !zoh && !(a.flags & F_COMPLEX)) {
+        const long full = 256L * 2048;
+        const int rpt = (a.B % 4 == 0 && lanes / 4 >= full) ? 4 : (a.B % 2 == 0 && lanes / 2 >= full) ? 2 : 1;
+        if (rpt > 1) {
+            const dim3 g((unsigned)((lanes / rpt + 255) / 256));
+            if (io_dtype == 0) {
+                if (rpt == 4) step_multi_kernel<float, 4><<<g, block, 0, stream>>>(a);
+                else step_multi_kernel<float, 2><<<g, block, 0, stream>>>(a);
+            } else {
+                if (rpt == 4) step_multi_kernel<bf16_t, 4><<<g, block, 0, stream>>>(a);
+                else step_multi_kernel<bf16_t, 2><<<g, block, 0, stream>>>(a);
+            }
+            return hipGetLastError() == hipSuccess ? 0 : -1;
+        }
+    }
 #define SS_LAUNCH_STEP(T, V, Z) step_kernel<T, V, Z><<<grid, block, 0, stream>>>(a)
     if (io_dtype == 0) {
         if (vec) { if (zoh) SS_LAUNCH_STEP(float, true, true); else SS_LAUNCH_STEP(float, true, false); }

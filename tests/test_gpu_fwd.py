@@ -172,6 +172,31 @@ def test_step_by_step_equals_scan(io):
     util.assert_close(h, h_last.cpu().numpy(), io, "step vs scan state")
 
 
+# From 2 x 256 x 2048 lanes on, ss_step takes 2 or 4 batch entries of a channel per thread (N = 16): both
+# counts, both dtypes, a last workgroup that is partly filled, and every optional operand absent once.
+@pytest.mark.parametrize("io,batch,dim,full", [("bf16", 132, 4000, True), ("f32", 66, 4000, True), ("bf16", 68, 3900, False)])
+def test_step_several_batch_entries_per_thread(io, batch, dim, full):
+    import torch
+    from oracle import ss_oracle as orc
+    from paper_2312_00752_amd import binding as B
+    s = wl.make_step_inputs(batch, dim, 16, 2, io=io, seed=71)
+    h_ref = np.random.default_rng(72).normal(size=(batch, dim, 16)).astype(np.float32)
+    h = torch.from_numpy(h_ref).cuda()
+    h_ref = h_ref.astype(np.float64)
+    tio = torch.bfloat16 if io == "bf16" else torch.float32
+    up = lambda a, dt: torch.from_numpy(a).cuda().to(dt)
+    for t in range(2):
+        dl = s["delta"][t] if full else np.abs(s["delta"][t])   # without softplus the step size itself: keep it non-negative
+        kw = dict(Dskip=up(s["Dskip"], torch.float32), z_t=up(s["z"][t], tio), delta_bias=up(s["delta_bias"], torch.float32)) if full else {}
+        o = B.ss_step(h, up(s["u"][t], tio), up(dl, tio), up(s["A"], torch.float32), up(s["B"][t], tio),
+                      up(s["C"][t], tio), delta_softplus=full, **kw)
+        rkw = dict(Dskip=s["Dskip"], z_t=s["z"][t], bias=s["delta_bias"]) if full else {}
+        o_ref, h_ref = orc.step(h_ref, s["u"][t], dl, s["A"], s["B"][t], s["C"][t], softplus=full, **rkw)
+        torch.cuda.synchronize()
+        util.assert_close(o, o_ref, io, "out_t")
+        util.assert_close(h, h_ref, "f32", "h")
+
+
 @pytest.mark.parametrize("dstate", [1, 5, 16])
 def test_step_state_sizes_against_oracle(dstate):
     import torch
