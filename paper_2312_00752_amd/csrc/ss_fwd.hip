@@ -292,6 +292,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         }
         __syncthreads();
         // ---- B: sequential recurrence over the chunk ---------------------------------
+        __builtin_amdgcn_s_setprio(2);   // raised wave priority for the recurrence (see scan_bwd_kernel)
         constexpr int NG = CHUNK_T / GROUP_T;
         bc_group<T> Bg[2][STATES_PER_LANE], Cg[2][STATES_PER_LANE];
         constexpr int FB = 1;            // staged: groups fetched together (two gain nothing and spill scalar registers)
@@ -388,6 +389,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         if (c + 1 < c_end) project();
         __syncthreads();
         // ---- C: pointwise post-processing --------------------------------------------
+        __builtin_amdgcn_s_setprio(0);
         if (!AGG) {
             float y8[SLICE];
 #pragma unroll
