@@ -545,6 +545,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
         }
         if (c > c_begin) issue_loads(c - 1);
         __syncthreads();
+        __builtin_amdgcn_s_setprio(2);   // as in scan_bwd_kernel: the recurrence at a raised wave priority
         constexpr int NG = CHUNK_T / GROUP_T;
 #pragma unroll
         for (int g = NG - 1; g >= 0; --g) {
@@ -572,6 +573,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
                 }
             }
         }
+        __builtin_amdgcn_s_setprio(0);
         __syncthreads();
     }
     if (s_ok) {
