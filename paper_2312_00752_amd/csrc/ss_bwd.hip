@@ -255,8 +255,8 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
 
         // ---- B1: recompute the states of the block -----------------------------------------
         // The two workgroups of a CU meet wave by wave on each SIMD.  The long state phases run at a raised
-        // wave priority and the short pointwise phases, which end in barriers, at the default one: measured
-        // 1.5 % on this kernel and 3.7 % on the forward kernel (either asymmetry helps; this one most).
+        // wave priority (the adjoint phase highest) and the short pointwise phases, which end in barriers, at the
+        // default one: measured 6-8 % on this kernel and 3.7 % on the forward kernel.
         __builtin_amdgcn_s_setprio(2);
         constexpr int NG = BT / GROUP_T;
         float hs[BT][STATES_PER_LANE], as[BT][STATES_PER_LANE];
@@ -313,6 +313,7 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
             if (!CFIX) reduce_take(red, dbc + STATES_PER_LANE * BT + (NG - 1) * GROUP_T, lane);
         }
         // ---- B2: adjoint recurrence, last step of the block first --------------------------
+        __builtin_amdgcn_s_setprio(3);   // the longest dependent chains of the block: above the recompute phase (another 4-6 %)
 #pragma unroll
         for (int g = NG - 1; g >= 0; --g) {
             bc_group<T> Bg[STATES_PER_LANE], Cg[STATES_PER_LANE];
