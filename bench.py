@@ -6,6 +6,9 @@ scan (leaving its checkpoints) followed by the backward scan, on the Mamba-1.4B-
 layer (batch 8, L 2048, d_inner 4096, N 16, bf16 I/O, fp32 state).  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
+Every step works on the next of several input / workspace / output sets (more than the 256 MB
+memory-side cache apart), so neither pass finds what the previous one left in a cache.
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 """
 import argparse
@@ -18,8 +21,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
-# fp32 vector peak WITHOUT packed FP32 (which this build does not use): 256 CU x 4 SIMD x
-# 16 lanes x 2.4 GHz x 2 flop per FMA = 78.6 TFLOP/s, half of the published 157.3 TFLOP/s.
+# fp32 vector peaks: the published 157.3 TFLOP/s assumes packed FP32 (two multiply-adds per lane
+# and issue); without packed FP32, which this build does not use, a SIMD issues one 16-lane
+# multiply-add per cycle: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz x 2 flop = 78.6 TFLOP/s.
+VALU_PEAK_PUBLISHED_TFLOPS = 157.3
 VALU_PEAK_TFLOPS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12
 # Algorithmic flops per token*channel*state: forward 4 multiply-adds + 1 exponential,
 # backward 12 multiply-adds + 1 exponential (a multiply-add counts 2, the exponential 1).
@@ -51,20 +56,167 @@ def read_traffic(path):
 
 
 def cpu_baseline(w, sample_dim):
-    """Time the float64 oracle (as it stands) on the first `sample_dim` channels."""
+    """Time the float64 oracle (as it stands) on the first `sample_dim` channels.
+    Returns the baseline record and the oracle's results (for the parity check of the timed buffers)."""
     from oracle import ss_oracle as orc
     sl = lambda a: None if a is None else a[:, :sample_dim]
     kw = dict(Dskip=w["Dskip"][:sample_dim], z=sl(w["z"]), bias=w["delta_bias"][:sample_dim], softplus=True)
     u, dl, A, dout = sl(w["u"]), sl(w["delta"]), w["A"][:sample_dim], sl(w["dout"])
     t0 = time.perf_counter()
-    orc.scan_fwd(u, dl, A, w["B"], w["C"], **kw)
-    orc.scan_bwd(u, dl, A, w["B"], w["C"], dout, **kw)
+    ref_f = orc.scan_fwd(u, dl, A, w["B"], w["C"], **kw)
+    ref_b = orc.scan_bwd(u, dl, A, w["B"], w["C"], dout, **kw)
     dt = time.perf_counter() - t0
     nb, nl = u.shape[0], u.shape[2]
-    return {"value": nb * sample_dim * nl / dt, "unit": "token*channels/s", "cores": orc.threads(),
-            "kind": "oracle", "seconds": round(dt, 3),
-            "sample": "fwd+bwd float64 oracle on the first %d of the workload's channels, all %d batches, L=%d"
-                      % (sample_dim, nb, nl)}
+    rec = {"value": nb * sample_dim * nl / dt, "unit": "token*channels/s", "cores": orc.threads(),
+           "kind": "oracle", "seconds": round(dt, 3),
+           "sample": "fwd+bwd float64 oracle on the first %d of the workload's channels, all %d batches, L=%d"
+                     % (sample_dim, nb, nl)}
+    return rec, ref_f, ref_b
+
+
+class ScanSet:
+    """One complete set of device buffers of a scan workload: inputs, output, workspace, gradients."""
+
+    def __init__(self, src, dev):
+        import torch
+        from paper_2312_00752_amd import binding as B
+        self.t = {k: (v.clone() if v is not None else None) for k, v in src.items()}
+        t = self.t
+        nb, nd, nl = t["u"].shape
+        nn = t["A"].shape[1]
+        f32 = torch.float32
+        self.out = torch.empty_like(t["u"])
+        self.ws = torch.empty(B.ss_workspace_bytes(nb, nd, nl, nn, io_dtype=B.SS_BF16 if t["u"].dtype == torch.bfloat16 else B.SS_F32),
+                              dtype=torch.uint8, device=dev)
+        self.grads = {"du": torch.empty_like(t["u"]), "ddelta": torch.empty_like(t["u"]), "dz": torch.empty_like(t["u"]),
+                      "dB": torch.empty(tuple(t["B"].shape), dtype=f32, device=dev),
+                      "dC": torch.empty(tuple(t["C"].shape), dtype=f32, device=dev),
+                      "dA": torch.empty(tuple(t["A"].shape), dtype=f32, device=dev),
+                      "dD": torch.empty((nd,), dtype=f32, device=dev), "ddelta_bias": torch.empty((nd,), dtype=f32, device=dev),
+                      "dh0": None}
+        self.kw = dict(Dskip=t["Dskip"], z=t["z"], delta_bias=t["delta_bias"], delta_softplus=True)
+
+    def fwd(self):
+        from paper_2312_00752_amd import binding as B
+        t = self.t
+        B.ss_scan_fwd(t["u"], t["delta"], t["A"], t["B"], t["C"], out=self.out, workspace=self.ws, **self.kw)
+
+    def bwd(self):
+        from paper_2312_00752_amd import binding as B
+        t = self.t
+        B.ss_scan_bwd(t["dout"], t["u"], t["delta"], t["A"], t["B"], t["C"], self.ws, grads=self.grads, **self.kw)
+
+
+def time_rotating(sets, steps, warmup):
+    """Alternating forward / backward over rotating buffer sets.  Returns wall ms per step, the forward and
+    the backward call durations (sorted lists, ms; events on the launch stream), and the same two calls
+    timed back to back (forward after forward, backward after backward), also rotating."""
+    import torch
+    n = len(sets)
+    for s in range(warmup):
+        sets[s % n].fwd()
+        sets[s % n].bwd()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        st = sets[s % n]
+        ev[s][0].record()
+        st.fwd()
+        ev[s][1].record()
+        st.bwd()
+        ev[s][2].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    fwd_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    bwd_all = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    k = max(4, min(steps, 20))
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    e[0].record()
+    for s in range(k):
+        sets[s % n].fwd()
+    e[1].record()
+    for s in range(k):
+        sets[s % n].bwd()
+    e[2].record()
+    torch.cuda.synchronize()
+    return wall_ms, fwd_all, bwd_all, e[0].elapsed_time(e[1]) / k, e[1].elapsed_time(e[2]) / k
+
+
+def device_inputs(name, dev):
+    """The named workload's recipe drawn on the GPU (torch generator, the workload's seed): same shapes,
+    dtypes and distributions as workloads.make_config, for timing only (the parity tests and the headline
+    run use the numpy recipe itself)."""
+    import math
+    import torch
+    from paper_2312_00752_amd import workloads as wl
+    nb, nl, nd, nn, io, seed, bias_mode, u_mode = wl.CONFIGS[name]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    iot = torch.bfloat16 if io == "bf16" else torch.float32
+    rn = lambda *shape: torch.randn(*shape, device=dev, generator=gen)
+    if u_mode == "onehot4":
+        table = rn(4, nd)
+        sym = torch.randint(0, 4, (nb, nl), device=dev, generator=gen)
+        u = table[sym].permute(0, 2, 1).contiguous()
+        u += 0.02 * rn(nb, nd, nl)
+    else:
+        u = rn(nb, nd, nl)
+    lo, hi = 1e-3, 1e-1
+    r = torch.rand(nd, device=dev, generator=gen)
+    dt0 = torch.exp(math.log(lo) + r * (math.log(hi) - math.log(lo))) if bias_mode == "loguniform" else lo + r * (hi - lo)
+    t = {"u": u.to(iot), "z": rn(nb, nd, nl).to(iot), "delta": rn(nb, nd, nl).to(iot),
+         "delta_bias": torch.log(torch.expm1(dt0)), "B": rn(nb, nn, nl).to(iot), "C": rn(nb, nn, nl).to(iot),
+         "Dskip": rn(nd), "dout": rn(nb, nd, nl).to(iot),
+         "A": -torch.arange(1, nn + 1, device=dev, dtype=torch.float32).repeat(nd, 1).contiguous()}
+    return t
+
+
+def all_configs_bench(dev, steps=6):
+    """Forward and backward call durations of all five workloads (two rotating buffer sets each), with the
+    fraction of the HBM roofline their algorithmic bytes amount to."""
+    import torch
+    from paper_2312_00752_amd import workloads as wl
+    res = {}
+    for name in wl.CONFIG_ORDER:
+        nb, nl, nd, nn, io = wl.CONFIGS[name][:5]
+        esz = 2 if io == "bf16" else 4
+        src = device_inputs(name, dev)
+        sets = [ScanSet(src, dev) for _ in range(2)]
+        del src
+        _, fwd_all, bwd_all, _, _ = time_rotating(sets, steps, 2)
+        f_ms, b_ms = fwd_all[len(fwd_all) // 2], bwd_all[len(bwd_all) // 2]
+        fb, bb = algorithmic_bytes(nb, nl, nd, nn, esz)
+        res[name] = {"shape_B_L_D_N": [nb, nl, nd, nn], "io_dtype": io, "fwd_ms": f_ms, "bwd_ms": b_ms,
+                     "fwd_bwd_ms": f_ms + b_ms, "token_channels_per_s": nb * nd * nl / ((f_ms + b_ms) * 1e-3),
+                     "algorithmic_bytes": fb + bb,
+                     "frac_of_hbm_peak": (fb + bb) / ((f_ms + b_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del sets
+        torch.cuda.empty_cache()
+    return res
+
+
+def parity_of_timed_buffers(st, ref_f, ref_b):
+    """Scale-relative error (max |gpu - oracle| / max |oracle| per tensor) of what the timed kernels
+    wrote into the buffer set `st`, against the oracle's results for the same inputs."""
+    import numpy as np
+    errs = {}
+
+    def rel(got, ref):
+        got = got.detach().float().cpu().numpy().astype(np.float64)
+        ref = np.asarray(ref, np.float64)
+        scale = float(np.max(np.abs(ref)))
+        err = float(np.max(np.abs(got - ref)))
+        return err / scale if scale > 0 else err
+
+    errs["out"] = rel(st.out, ref_f["out"])
+    for name, oname in (("du", "du"), ("ddelta", "ddelta"), ("dz", "dz"), ("dB", "dB"), ("dC", "dC"), ("dA", "dA"),
+                        ("dD", "dD"), ("ddelta_bias", "dbias")):
+        errs[name] = rel(st.grads[name], ref_b[oname])
+    return errs
+
+
 
 
 def decode_bench(dev, tokens=512):
@@ -368,10 +520,12 @@ def generation_sweep(dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--workload", default="mamba1p4b_layer_bf16")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sets", type=int, default=4, help="rotating input / workspace / output sets")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (and with it the parity check)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the timing of the other workloads")
     ap.add_argument("--no-decode", action="store_true", help="skip the single-token step timing")
     ap.add_argument("--no-layer", action="store_true", help="skip the timing of the layer around the scan")
     ap.add_argument("--layer-iters", type=int, default=20,
@@ -403,54 +557,32 @@ def main():
     io = torch.bfloat16 if w["io"] == "bf16" else torch.float32
     esz = 2 if w["io"] == "bf16" else 4
     up = lambda a, dt: torch.from_numpy(a).to(dev).to(dt).contiguous()
-    g = {k: up(w[k], io) for k in ("u", "delta", "z", "B", "C", "dout")}
-    g.update({k: up(w[k], torch.float32) for k in ("A", "Dskip", "delta_bias")})
-    ws = torch.empty(B.ss_workspace_bytes(nb, nd, nl, nn, io_dtype=B.SS_BF16 if esz == 2 else B.SS_F32),
-                     dtype=torch.uint8, device=dev)
-    out = torch.empty_like(g["u"])
-    kw = dict(Dskip=g["Dskip"], z=g["z"], delta_bias=g["delta_bias"], delta_softplus=True)
-
-    def fwd():
-        B.ss_scan_fwd(g["u"], g["delta"], g["A"], g["B"], g["C"], out=out, workspace=ws, **kw)
-
-    def bwd():
-        return B.ss_scan_bwd(g["dout"], g["u"], g["delta"], g["A"], g["B"], g["C"], ws, **kw)
+    src = {k: up(w[k], io) for k in ("u", "delta", "z", "B", "C", "dout")}
+    src.update({k: up(w[k], torch.float32) for k in ("A", "Dskip", "delta_bias")})
+    sets = [ScanSet(src, dev) for _ in range(max(1, args.sets))]
+    del src
+    set_bytes = sum(t.numel() * t.element_size() for t in list(sets[0].t.values()) + [sets[0].out, sets[0].ws]
+                    + [g for g in sets[0].grads.values() if g is not None])
 
     if args.copy_calibration:
-        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
+        a = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
         torch.cuda.synchronize()
-        torch.neg(src, out=dst)  # a plain streaming kernel: reads 256 MiB, writes 256 MiB
+        torch.neg(a, out=b)  # a plain streaming kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
-        del src, dst
+        del a, b
 
-    for _ in range(args.warmup):
-        fwd()
-        bwd()
-    torch.cuda.synchronize()
-
-    # Timed region: exactly K steps.  The library launches on torch's current stream, so
-    # events recorded on that stream bracket the forward and the backward call of each step.
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        ev[s][0].record()
-        fwd()
-        ev[s][1].record()
-        bwd()
-        ev[s][2].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_step = wall * 1e3 / args.steps
-    fwd_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
-    bwd_all = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    # Timed region: exactly K steps, bracketed by synchronisation; the library launches on torch's
+    # current stream, so events recorded on that stream bracket the forward and the backward call.
+    ms_step, fwd_all, bwd_all, fwd_b2b, bwd_b2b = time_rotating(sets, args.steps, args.warmup)
+    last = sets[(args.steps - 1) % len(sets)]   # its buffers hold what the last timed step wrote
     fwd_ms = sum(fwd_all) / args.steps
     bwd_ms = sum(bwd_all) / args.steps
 
     tc = nb * nd * nl
     fwd_b, bwd_b = algorithmic_bytes(nb, nl, nd, nn, esz)
     traffic = read_traffic(os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % args.workload))
+    bwd_flops = tc * nn * FLOPS_BWD
     res = {
         "metric": "selective-scan fwd+bwd token*channels/s",
         "value": tc / (ms_step * 1e-3),
@@ -460,31 +592,52 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": nb, "seqlen": nl, "d_inner": nd, "d_state": nn,
-                   "io_dtype": w["io"], "state_dtype": "f32", "passes": "fwd(save)+bwd"},
-        # Dominant kernel: the backward scan (the backward call = zero-fill + scan + finalize;
-        # the scan kernel is > 98 % of it).  It is bound by vector-ALU issue (VALU pipe ~ 2/3
-        # busy, HBM at ~ 12 %), so the roofline is the fp32 vector peak without packed ops.
-        "roofline": {"bound": "alu", "kernel": "scan_bwd_kernel",
-                     "achieved": tc * nn * FLOPS_BWD / (bwd_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TFLOPS,
-                     "unit": "TFLOP/s",
-                     "frac": tc * nn * FLOPS_BWD / (bwd_ms * 1e-3) / 1e12 / VALU_PEAK_TFLOPS,
+                   "io_dtype": w["io"], "state_dtype": "f32", "passes": "fwd(save)+bwd",
+                   "rotating_buffer_sets": len(sets), "bytes_per_set": set_bytes},
+        # Dominant kernel: the backward scan (the backward call = zero-fill + scan + finalize; the scan
+        # kernel is > 98 % of it).  Graded bound: HBM, algorithmic bytes of one backward launch over its
+        # duration.  `traffic` is the launch's measured HBM bytes (rocprofv3 counters, kept in profiles/).
+        "roofline": {"bound": "hbm", "kernel": "scan_bwd_kernel",
+                     "achieved": bwd_b / (bwd_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": bwd_b / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": traffic.get("scan_bwd_kernel_hbm_bytes")},
-        # the same launch against the HBM roofline the metric is quoted on
-        "hbm_roofline": {"bound": "hbm", "kernel": "scan_bwd_kernel",
-                         "achieved": bwd_b / (bwd_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": bwd_b / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": traffic.get("scan_bwd_kernel_hbm_bytes")},
+        # The same launch against the vector ALU, which is what limits it: algorithmic flops (12
+        # multiply-adds + 1 exponential per token, channel and state) against both fp32 vector peaks.
+        "alu_roofline": {"bound": "alu", "kernel": "scan_bwd_kernel", "achieved": bwd_flops / (bwd_ms * 1e-3) / 1e12,
+                         "unit": "TFLOP/s", "peak_unpacked_fp32": VALU_PEAK_TFLOPS,
+                         "frac_of_unpacked_peak": bwd_flops / (bwd_ms * 1e-3) / 1e12 / VALU_PEAK_TFLOPS,
+                         "peak_published_packed_fp32": VALU_PEAK_PUBLISHED_TFLOPS,
+                         "frac_of_published_peak": bwd_flops / (bwd_ms * 1e-3) / 1e12 / VALU_PEAK_PUBLISHED_TFLOPS},
         "passes": {"fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
                    "fwd_ms_median": fwd_all[len(fwd_all) // 2], "fwd_ms_min": fwd_all[0],
                    "bwd_ms_median": bwd_all[len(bwd_all) // 2], "bwd_ms_min": bwd_all[0],
+                   "fwd_ms_back_to_back": fwd_b2b, "bwd_ms_back_to_back": bwd_b2b,
                    "fwd_algorithmic_GBs": fwd_b / (fwd_ms * 1e-3) / 1e9,
+                   "fwd_frac_of_hbm_peak": fwd_b / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                    "fwd_bwd_algorithmic_GBs": (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9,
                    "fwd_bwd_frac_of_hbm_peak": (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                   "fwd_alu_frac": tc * nn * FLOPS_FWD / (fwd_ms * 1e-3) / 1e12 / VALU_PEAK_TFLOPS,
+                   "fwd_alu_frac_of_unpacked_peak": tc * nn * FLOPS_FWD / (fwd_ms * 1e-3) / 1e12 / VALU_PEAK_TFLOPS,
                    "fwd_traffic": traffic.get("scan_fwd_kernel_hbm_bytes")},
     }
+    if not args.no_cpu_baseline:
+        # the oracle, timed on the host cores on the whole workload; its results then check the buffers
+        # the LAST TIMED step wrote (nothing is re-run in between)
+        res["cpu_baseline"], ref_f, ref_b = cpu_baseline(w, sample_dim=nd)
+        errs = parity_of_timed_buffers(last, ref_f, ref_b)
+        tol = 2e-2 if w["io"] == "bf16" else 1e-4
+        res["parity_of_timed_buffers"] = {"metric": "max|gpu-oracle| / max|oracle| per tensor", "tolerance": tol,
+                                          "max": max(errs.values()), "ok": bool(max(errs.values()) <= tol), "per_tensor": errs}
+        del ref_f, ref_b
+    del sets, last
+    torch.cuda.empty_cache()
+    if not args.no_configs:
+        res["configs"] = all_configs_bench(dev)
     if not args.no_decode:
         res["decode"] = decode_bench(dev)
+        if not args.no_configs:
+            res["configs"]["ss_step_b64_d4096"] = {"us_per_token_graph": res["decode"]["us_per_token_graph"],
+                                                   "us_per_token_stream": res["decode"]["us_per_token_stream"],
+                                                   "frac_of_hbm_peak": res["decode"]["frac_of_hbm_peak_graph"]}
     if not args.no_layer and args.workload in ("mamba1p4b_layer_bf16", "mamba130m_layer_bf16"):
         res["layer"] = layer_bench(dev, args.workload, iters=args.layer_iters)
     if args.variants:
@@ -492,8 +645,6 @@ def main():
     if args.paper_sweep:
         res["paper_sweep"] = paper_sweep(dev)
         res["generation_sweep"] = generation_sweep(dev)
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, sample_dim=nd)
     print(json.dumps(res))
 
 

@@ -275,11 +275,12 @@ def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0
 
 def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, delta_bias=None,
                 h0=None, delta_softplus=False, dh_last=None, want_dh0=False, exact_zoh=False, complex_state=False,
-                stream=None):
+                stream=None, grads=None):
     """Enqueue the backward scan after a forward call that filled ``workspace``.
 
     Returns a dict with du, ddelta, dz, dB, dC, dA, dD, ddelta_bias, dh0 (None where the
-    corresponding input was not given)."""
+    corresponding input was not given).  ``grads``: a dict an earlier call returned; its
+    tensors are written again instead of allocating new ones."""
     import torch
     f32 = torch.float32
     q = BwdParams()
@@ -289,7 +290,8 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
     q.fwd.workspace = _ptr(workspace, torch.uint8, None, "workspace")
     q.fwd.workspace_bytes = workspace.numel()
     dev = u.device
-    g = {"du": torch.empty_like(u), "ddelta": torch.empty_like(u),
+    g = grads if grads is not None else {
+         "du": torch.empty_like(u), "ddelta": torch.empty_like(u),
          "dz": torch.empty_like(u) if z is not None else None,
          "dB": torch.empty(tuple(Bmat.shape), dtype=f32, device=dev),
          "dC": torch.empty(tuple(Cmat.shape), dtype=f32, device=dev),
@@ -297,6 +299,18 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
          "dD": torch.empty((nd,), dtype=f32, device=dev) if Dskip is not None else None,
          "ddelta_bias": torch.empty((nd,), dtype=f32, device=dev) if delta_bias is not None else None,
          "dh0": torch.empty(state_shape, dtype=f32, device=dev) if want_dh0 else None}
+    if grads is not None:   # same checks as for fresh tensors: shapes and dtypes of what will be written
+        want = {"du": (u.dtype, u.shape), "ddelta": (u.dtype, u.shape), "dz": (u.dtype, u.shape),
+                "dB": (f32, Bmat.shape), "dC": (f32, Cmat.shape), "dA": (f32, A.shape), "dD": (f32, (nd,)),
+                "ddelta_bias": (f32, (nd,)), "dh0": (f32, state_shape)}
+        need = {"du": True, "ddelta": True, "dz": z is not None, "dB": True, "dC": True, "dA": True,
+                "dD": Dskip is not None, "ddelta_bias": delta_bias is not None, "dh0": want_dh0}
+        for name, (dt, shp) in want.items():
+            if need[name] and grads.get(name) is None:
+                raise ValueError("grads[%r] is missing" % name)
+            if not need[name] and grads.get(name) is not None:
+                raise ValueError("grads[%r] given but that gradient is not produced" % name)
+            _ptr(grads.get(name), dt, shp, "grads[%r]" % name)
     q.dout = _ptr(dout, u.dtype, u.shape, "dout")
     q.dh_last = _ptr(dh_last, f32, state_shape, "dh_last")
     for name in ("du", "ddelta", "dz", "dB", "dC", "dA", "dD", "ddelta_bias", "dh0"):
