@@ -114,7 +114,10 @@ typedef struct {
 
 /* Bytes of workspace a call with these sizes needs: for_backward == 0 for a plain
  * ss_scan_fwd, 1 for ss_scan_fwd with SS_SAVE_FOR_BWD and the ss_scan_bwd that follows
- * it.  Only batch, dim, seqlen, dstate, io_dtype and the SS_HAS_Z flag are read.  The
+ * it.  Read: batch, dim, seqlen, dstate, io_dtype and the flags SS_HAS_Z, SS_B_FIXED,
+ * SS_C_FIXED and SS_COMPLEX_STATE (they change the number of state slots, add partial-sum
+ * blocks for a time-invariant operand's gradient, and decide whether B and C are repacked and
+ * the sequence split), so pass the flags of the call the workspace is for.  The
  * content is opaque (state checkpoints every SS_CHECKPOINT_STEPS steps, the pre-gate
  * output when there is a gate, per-segment carries when a long sequence with few rows is
  * split across workgroups, and partial sums of the backward pass); a forward call with
@@ -131,6 +134,23 @@ size_t ss_workspace_bytes(const ss_fwd_params *p, int for_backward);
 /* Forward scan (Algorithm 2 steps 5-6 with the fusion of Appendix D).  Writes out, and
  * h_last / checkpoints according to the flags. */
 int ss_scan_fwd(const ss_fwd_params *p, void *stream);
+
+/* The plain forward scan for callers that cannot allocate device memory and have no workspace
+ * to lend: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments and results as ss_scan_fwd without SS_SAVE_FOR_BWD, but the scratch
+ * that ss_workspace_bytes(p, 0) describes (repacked B and C, per-segment states of a split
+ * sequence, the pre-gate accumulator of more than 16 states) is a fixed array of
+ * SS_STATIC_SCRATCH_BYTES in the library's own device image instead of p->workspace, which is
+ * ignored.  The call allocates nothing and frees nothing; the array's device address is looked up
+ * once per device, on the first call there.
+ *  - SS_SAVE_FOR_BWD is rejected with SS_ERR_UNSUPPORTED (the backward pass needs a workspace
+ *    that outlives the call), a problem whose scratch exceeds SS_STATIC_SCRATCH_BYTES with
+ *    SS_ERR_WORKSPACE; both before anything is enqueued.
+ *  - Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different
+ *    streams, or graphs replayed concurrently) race.  Calls in stream order are safe; nothing
+ *    in the array has to survive from one call to the next. */
+#define SS_STATIC_SCRATCH_BYTES (64u << 20)
+int ss_scan_fwd_static(const ss_fwd_params *p, void *stream);
 
 typedef struct {
     ss_fwd_params fwd;        /* the forward call's inputs, flags and filled workspace;

@@ -19,6 +19,7 @@ SS_OK, SS_ERR_NULL, SS_ERR_SHAPE, SS_ERR_UNSUPPORTED = 0, -1, -2, -3
 SS_ERR_ALIGN, SS_ERR_WORKSPACE, SS_ERR_LAUNCH = -4, -5, -6
 SS_MAX_DSTATE = 256
 SS_CHECKPOINT_STEPS = 16
+SS_STATIC_SCRATCH_BYTES = 64 << 20
 
 _vp = ctypes.c_void_p
 
@@ -105,6 +106,8 @@ def lib():
         l.ss_workspace_bytes.argtypes = [ctypes.POINTER(FwdParams), ctypes.c_int]
         l.ss_scan_fwd.restype = ctypes.c_int
         l.ss_scan_fwd.argtypes = [ctypes.POINTER(FwdParams), _vp]
+        l.ss_scan_fwd_static.restype = ctypes.c_int
+        l.ss_scan_fwd_static.argtypes = [ctypes.POINTER(FwdParams), _vp]
         l.ss_scan_bwd.restype = ctypes.c_int
         l.ss_scan_bwd.argtypes = [ctypes.POINTER(BwdParams), _vp]
         l.ss_step.restype = ctypes.c_int
@@ -268,6 +271,23 @@ def ss_scan_fwd(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0
         if save_for_bwd:
             p.flags |= SS_SAVE_FOR_BWD
     rc = lib().ss_scan_fwd(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return out, h_last
+
+
+def ss_scan_fwd_static(u, delta, A, Bmat, Cmat, Dskip=None, z=None, delta_bias=None, h0=None,
+                       delta_softplus=False, *, out, h_last=None, exact_zoh=False, complex_state=False, stream=None):
+    """Enqueue the plain forward scan with the library's own static device scratch: the call
+    allocates nothing, so ``out`` (and ``h_last`` if wanted) must be given.  Returns (out, h_last)."""
+    import torch
+    p = _fwd_params(u, delta, A, Bmat, Cmat, Dskip, z, delta_bias, h0, delta_softplus, exact_zoh, complex_state)
+    state_shape = (p.batch, p.dim, p.dstate) + ((2,) if complex_state else ())
+    p.out = _ptr(out, u.dtype, u.shape, "out")
+    if h_last is not None:
+        p.h_last = _ptr(h_last, torch.float32, state_shape, "h_last")
+        p.flags |= SS_WRITE_H_LAST
+    rc = lib().ss_scan_fwd_static(ctypes.byref(p), _stream(stream))
     if rc != SS_OK:
         raise SsError(rc)
     return out, h_last

@@ -1,9 +1,16 @@
 // C-ABI entry points: host-side validation and dispatch only (see include/ss_scan.h).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "ss_kernels.h"
 #include "ss_layer.h"
 #include "ss_scan.h"
+
+// Scratch of ss_scan_fwd_static: lives in the library's device image, one copy per GPU.  In host
+// code this name is only a handle for hipGetSymbolAddress; the device address it yields is what
+// every kernel argument below uses.
+static __device__ __align__(256) unsigned char scratch[SS_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -223,6 +230,22 @@ void narrow_to_group(ss::FwdArgs& a, const ss_fwd_params* p, int g, size_t ckpt_
     }
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+int static_scratch(void** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SS_ERR_LAUNCH;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SS_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // the same value from every thread
+    }
+    *out = ptr;
+    return SS_OK;
+}
+
 }  // namespace
 
 namespace ss {
@@ -433,6 +456,25 @@ int ss_scan_fwd(const ss_fwd_params* p, void* stream)
 {
     if (!p) return SS_ERR_NULL;
     return ss::scan_fwd_strided(p, (long)slots(p) * p->seqlen, stream);
+}
+
+int ss_scan_fwd_static(const ss_fwd_params* p, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    if (p->flags & SS_SAVE_FOR_BWD) return SS_ERR_UNSUPPORTED;
+    ss_fwd_params q = *p;
+    q.workspace = nullptr;
+    q.workspace_bytes = 0;
+    // everything else is checked first, so that an invalid call reports its own error
+    const int rc = check_fwd(&q, false);
+    if (rc != SS_OK && rc != SS_ERR_WORKSPACE) return rc;
+    if (ws_layout(&q, false).total > (size_t)SS_STATIC_SCRATCH_BYTES) return SS_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    const int rs = static_scratch(&ptr);
+    if (rs != SS_OK) return rs;
+    q.workspace = ptr;
+    q.workspace_bytes = SS_STATIC_SCRATCH_BYTES;
+    return ss::scan_fwd_strided(&q, (long)slots(&q) * q.seqlen, stream);
 }
 
 int ss_scan_bwd(const ss_bwd_params* p, void* stream)

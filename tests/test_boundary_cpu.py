@@ -305,3 +305,24 @@ def test_complex_state_flag():
     two = B.ss_workspace_bytes(2, 64, 96, 16, True, B.SS_BF16, False, complex_state=True)
     # (and the real variant alone carries the repacked copy of B and C: 2 * 16 * 96 * 2 bf16 values)
     assert two > one and two - one == (96 // 16) * 2 * 64 * 16 * 4 - 2 * 16 * 96 * 2 * 2
+
+
+def test_static_scratch_forward_rejections():
+    """ss_scan_fwd_static validates like ss_scan_fwd, refuses the backward-saving mode and
+    problems whose scratch exceeds its fixed array -- all on the host, before any device call."""
+    f = B.lib().ss_scan_fwd_static
+    assert f(None, None) == B.SS_ERR_NULL
+    p = _good_fwd(); p.u = None
+    assert f(ctypes.byref(p), None) == B.SS_ERR_NULL
+    p = _good_fwd(); p.batch = 0
+    assert f(ctypes.byref(p), None) == B.SS_ERR_SHAPE
+    p = _good_fwd(); p.out = FAKE + 2
+    assert f(ctypes.byref(p), None) == B.SS_ERR_ALIGN
+    p = _good_fwd(); p.flags = B.SS_SAVE_FOR_BWD
+    assert f(ctypes.byref(p), None) == B.SS_ERR_UNSUPPORTED
+    # float32 I/O, one batch entry, 2^20 steps: the repacked B and C alone are 128 MiB
+    p = _good_fwd(); p.io_dtype = B.SS_F32; p.batch, p.dim, p.seqlen = 1, 256, 1 << 20
+    assert B.ss_workspace_bytes(1, 256, 1 << 20, 16, for_backward=False, io_dtype=B.SS_F32, has_z=False) > B.SS_STATIC_SCRATCH_BYTES
+    assert f(ctypes.byref(p), None) == B.SS_ERR_WORKSPACE
+    hdr = open(os.path.join(ROOT, "include", "ss_scan.h")).read()
+    assert "#define SS_STATIC_SCRATCH_BYTES (64u << 20)" in hdr
