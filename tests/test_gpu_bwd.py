@@ -139,12 +139,11 @@ def test_backward_leaves_inputs_and_workspace_reusable():
     a = B.ss_scan_bwd(g["dout"], g["u"], g["delta"], g["A"], g["B"], g["C"], ws, **kw)
     b = B.ss_scan_bwd(g["dout"], g["u"], g["delta"], g["A"], g["B"], g["C"], ws, **kw)
     torch.cuda.synchronize()
-    for k in ("dA", "dD"):
+    # everything but dB / dC is summed in a fixed order (register accumulators, share tiles added
+    # in wave order, partial sums finished by one kernel): bit-identical from run to run
+    for k in ("dA", "dD", "ddelta_bias", "du", "ddelta", "dz"):
         assert torch.equal(a[k], b[k]), k
-    for k in ("du", "ddelta", "dz"):
-        # sums over n go through LDS float atomics in wave order: equal up to rounding
-        assert util.rel_err(a[k], b[k].float().cpu().numpy()) < 1e-2, k
-    for k in ("dB", "dC", "ddelta_bias"):
+    for k in ("dB", "dC"):   # float atomics across the workgroups of a batch entry: order varies
         assert util.rel_err(a[k], b[k].cpu().numpy()) < 1e-5, k
     for k, v in keep.items():
         assert torch.equal(v, g[k]), k

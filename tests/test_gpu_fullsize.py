@@ -28,17 +28,20 @@ def test_full_size_forward_and_backward(name):
     grads = B.ss_scan_bwd(g["dout"], g["u"], g["delta"], g["A"], g["B"], g["C"], ws, want_dh0=True, **kw)
     torch.cuda.synchronize()
     del g, ws
-    errs = {}
+    errs, elem = {}, {}
     ref = util.oracle_fwd(w)
-    errs["out"] = util.assert_close(out, ref["out"], io, "out")
-    errs["h_last"] = util.assert_close(h_last, ref["h_last"], io, "h_last")
+    for k, got in (("out", out), ("h_last", h_last)):
+        errs[k] = util.assert_close(got, ref[k], io, k)
+        elem[k] = util.elem_err(got, ref[k])
     del ref, out, h_last
     gc.collect()
     ref = util.oracle_bwd(w)
     for k in GRADS:
         errs[k] = util.assert_close(grads[k], ref[ORACLE_NAME.get(k, k)], io, k)
+        elem[k] = util.elem_err(grads[k], ref[ORACLE_NAME.get(k, k)])
         grads[k] = None
-    print(name, {k: "%.1e" % v for k, v in errs.items()})
+    print(name, "max|diff|/max|ref|:", {k: "%.1e" % v for k, v in errs.items()})
+    print(name, "max_i |diff_i| / (|ref_i| + %.2f max|ref|):" % util.ELEM_FLOOR, {k: "%.1e" % v for k, v in elem.items()})
 
 
 def test_full_size_decode_steps():

@@ -3,7 +3,16 @@ import numpy as np
 
 from oracle import ss_oracle as orc
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}   # max |gpu - oracle| / max |oracle| per tensor
+# Tolerances of the benchmark spec, per output tensor: max |gpu - oracle| / max |oracle| at most
+# 1e-4 for float32 I/O and 2e-2 for bf16 I/O (float32 state).  A tensor the library produces in
+# float32 (h_last, dB, dC, dA, dD, ddelta_bias, dh0) is held to 1e-4 in a bf16 workload too: the
+# bf16 inputs are exact for the oracle, and state and sums are float32 on both sides.
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+# Element-wise criterion beside it: |gpu - oracle| <= tol * (|oracle| + ELEM_FLOOR * max |oracle|)
+# for every element, so that elements far below the tensor's peak are checked against their own
+# size down to a floor (sums of terms of the peak's size cancel to small values whose float32
+# error is relative to the terms; the floor leaves room for that).
+ELEM_FLOOR = 0.05
 
 
 def upload(w, device="cuda"):
@@ -31,9 +40,13 @@ def oracle_bwd(w, nthreads=0):
                         nthreads=nthreads)
 
 
+def _as_f64(got):
+    return got.detach().float().cpu().numpy().astype(np.float64) if hasattr(got, "detach") else np.asarray(got, np.float64)
+
+
 def rel_err(got, ref):
     """Scale-relative error of a tensor: max |got - ref| / max |ref|."""
-    got = got.detach().float().cpu().numpy().astype(np.float64) if hasattr(got, "detach") else np.asarray(got, np.float64)
+    got = _as_f64(got)
     ref = np.asarray(ref, np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
     if ref.size == 0:
@@ -45,7 +58,36 @@ def rel_err(got, ref):
     return float(err / scale) if scale > 0 else float(err)
 
 
-def assert_close(got, ref, io, name):
+def elem_err(got, ref, floor=ELEM_FLOOR):
+    """Worst element-wise error: max_i |got_i - ref_i| / (|ref_i| + floor * max |ref|)."""
+    got = _as_f64(got)
+    ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    scale = np.max(np.abs(ref))
+    if scale == 0:
+        return float(np.max(np.abs(got)))
+    ratio = np.abs(got - ref) / (np.abs(ref) + floor * scale)
+    worst = np.max(ratio)
+    return float(worst) if np.isfinite(worst) else float("inf")
+
+
+def tolerance(got, io, exact_inputs=True):
+    """The limit a produced tensor is held to (see TOL).  ``exact_inputs=False``: the operation
+    rounds intermediates to the io dtype between its kernels (the layer), so its float32 results
+    carry bf16-sized differences wherever the two sides round a value to different neighbours."""
+    import torch
+    if io == "bf16" and exact_inputs and hasattr(got, "dtype") and got.dtype == torch.float32:
+        return TOL["f32"]
+    return TOL[io]
+
+
+def assert_close(got, ref, io, name, exact_inputs=True):
+    """Both criteria (see TOL, ELEM_FLOOR); returns the scale-relative error."""
+    tol = tolerance(got, io, exact_inputs)
     e = rel_err(got, ref)
-    assert e <= TOL[io], "%s: scale-relative error %.3e exceeds %.1e" % (name, e, TOL[io])
+    assert e <= tol, "%s: scale-relative error %.3e exceeds %.1e" % (name, e, tol)
+    ee = elem_err(got, ref)
+    assert ee <= tol, "%s: element-wise error %.3e (of |ref| + %.2f max|ref|) exceeds %.1e" % (name, ee, ELEM_FLOOR, tol)
     return e
