@@ -185,7 +185,11 @@ def all_configs_bench(dev, steps=6):
         src = device_inputs(name, dev)
         sets = [ScanSet(src, dev) for _ in range(2)]
         del src
-        _, fwd_all, bwd_all, _, _ = time_rotating(sets, steps, 2)
+        # enough repetitions that the clocks have settled (a launch onto an idle chip runs ~10 % slower):
+        # about 25 ms of warm-up and as much of timed work, from a first estimate of a step
+        _, f0, b0, _, _ = time_rotating(sets, 2, 1)
+        n = int(max(steps, min(40, 25.0 / max(f0[0] + b0[0], 1e-3))))
+        _, fwd_all, bwd_all, _, _ = time_rotating(sets, n, n)
         f_ms, b_ms = fwd_all[len(fwd_all) // 2], bwd_all[len(bwd_all) // 2]
         fb, bb = algorithmic_bytes(nb, nl, nd, nn, esz)
         res[name] = {"shape_B_L_D_N": [nb, nl, nd, nn], "io_dtype": io, "fwd_ms": f_ms, "bwd_ms": b_ms,

@@ -18,6 +18,9 @@
 // dBr = gr dt u, dBi = gi dt u,   and with  P = d_abr abr + d_abi abi,  Q = -d_abr abi + d_abi abr,
 // d_abr = gr hr- + gi hi-,  d_abi = -gr hi- + gi hr-  (h- the previous state):
 // ddt += Ar P + Ai Q + (gr Br + gi Bi) u,   dAr += dt P,   dAi += dt Q,   du += dt (gr Br + gi Bi).
+#include <atomic>
+#include <type_traits>
+
 #include "ss_kernels.h"
 #include "ss_device.h"
 
@@ -461,6 +464,368 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
     }
 }
 
+// ---- the common case: B and C as quad-broadcast operands ---------------------------------------
+// Real state, first-order B-bar, selective B and C, rows of whole 16-byte pieces (L % 8 == 0): the
+// same decomposition and phases as scan_bwd_kernel, but B and C do not come through the scalar
+// path.  They are staged once per workgroup and block, widened to float, into a small LDS tile
+// [4-step group][state][step], from which lane l of wave w reads, per group, one float4 holding
+// state 4w + l % 4 at the group's four steps.  Such a register has the same four values in every
+// group of four lanes, and a DPP operand with quad_perm [k,k,k,k] hands state k's value to all
+// lanes at no cost: `v_mul_f32_dpp` / `v_fmac_f32_dpp` take B or C as their first operand exactly
+// as the scalar-operand forms did.  What this removes: the scalar loads (which return out of order
+// and share their wait counter with LDS reads, so that every LDS wait also waited for them), the
+// widening of bf16 by the scalar unit, and the scalar-register spills with their v_readlane /
+// v_writelane traffic on the vector ALU.  The compiler folds such a broadcast into a multiply only
+// now and then and never into a multiply-add with an accumulator, so these instructions are written
+// out (input_step_dpp, adjoint_step_dpp).
+// All (B,D,L) tensors are addressed through per-workgroup buffer resources with ONE per-thread
+// offset (they share the layout), B and C through one resource per batch entry: no 64-bit pointer
+// registers, and an out-of-range offset switches a load (zeros) or a store off without a branch.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+struct BwdSmemDpp {
+    float dt[ROWS][BPAD];
+    float du[ROWS][BPAD];
+    float dy[ROWS][BPAD];
+    float pdd[NWAVES][ROWS][BPAD];
+    float psb[NWAVES][ROWS][BPAD];
+    float red[NWAVES][RED_VALUES][RED_PITCH];
+    float dbc[NWAVES][2][STATES_PER_LANE][BT];
+    float bcp[2][BT / GROUP_T][NPAD][GROUP_T];   // B (0) and C (1) of the block
+};
+
+// The input term of Eq. 2a for a lane's four states: bu[k] = B_k * du, with Bq holding B of the
+// wave's four states in every group of four lanes (state k in lane k).  Written out for the same
+// reason as adjoint_step_dpp, with the same leading wait state.
+__device__ __forceinline__ void input_step_dpp(float (&bu)[STATES_PER_LANE], float Bq, float du)
+{
+    asm("s_nop 1\n\t"
+        "v_mul_f32_dpp %0, %4, %5 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf\n\t"
+        "v_mul_f32_dpp %1, %4, %5 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_mul_f32_dpp %2, %4, %5 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_mul_f32_dpp %3, %4, %5 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf"
+        : "=&v"(bu[0]), "=&v"(bu[1]), "=&v"(bu[2]), "=&v"(bu[3])
+        : "v"(Bq), "v"(du));
+}
+
+// One step of the adjoint recurrence for a lane's four states.  On entry g[k] = abar+ g+ of state k;
+// Cq / Bq hold C / B of the wave's four states in every group of four lanes (state k in lane k).
+//     g[k] += C_k dy            (the gradient reaching h_t)          sb = sum_k B_k g[k]
+// The leading wait state covers a DPP operand the compiler might have copied with a vector move
+// just before (a DPP read needs two wait states after a vector write of the same register).
+__device__ __forceinline__ void adjoint_step_dpp(f32x4_t& g, float& sb, float Cq, float Bq, float dy)
+{
+    float g0 = g[0], g1 = g[1], g2 = g[2], g3 = g[3];
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %5, %7 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %5, %7 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %5, %7 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %5, %7 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf\n\t"
+        "v_mul_f32_dpp %4, %6, %0 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %4, %6, %1 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %4, %6, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %4, %6, %3 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf"
+        : "+v"(g0), "+v"(g1), "+v"(g2), "+v"(g3), "=&v"(sb)
+        : "v"(Cq), "v"(Bq), "v"(dy));
+    g[0] = g0; g[1] = g1; g[2] = g2; g[3] = g3;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    BwdSmemDpp& sm = *reinterpret_cast<BwdSmemDpp*>(smem_raw);
+
+    const FwdArgs& f = a.f;
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & (WAVE - 1);
+    const int groups = (f.D + ROWS - 1) / ROWS;
+    const unsigned bx = xcd_contiguous(blockIdx.x, gridDim.x);  // one batch entry's row groups per XCD (see scan_fwd_kernel)
+    const int b = bx / groups;
+    const int d0 = (bx % groups) * ROWS;
+    const int L = f.L, N = f.N, NS = f.NS;
+    const bool has_z = f.flags & F_HAS_Z, has_D = f.flags & F_HAS_D;
+    const bool softplus = f.flags & F_DELTA_SOFTPLUS;
+    const int seg = blockIdx.y;  // segment of the sequence (see scan_fwd_kernel)
+    const int blk_begin = seg * (f.seg_len / BT);
+    const int blk_end = min((L + BT - 1) / BT, (seg + 1) * (f.seg_len / BT));
+    const long seg_rows = (long)seg * f.B * f.D;
+
+    // ---- pointwise view: thread -> (row pr, 4-step slice pq) -----------------------------
+    const int pr = tid >> 2, pq = tid & 3;
+    const bool p_ok = d0 + pr < f.D;
+    const int pd = p_ok ? d0 + pr : f.D - 1;
+    const long prow = (long)b * f.D + pd;
+    const float bias = (f.flags & F_HAS_DELTA_BIAS) ? f.bias[pd] : 0.0f;
+    const float Dsk = has_D ? f.Dskip[pd] : 0.0f;
+    float dD_acc = 0.0f, db_acc = 0.0f;
+    const int rows_here = min(ROWS, f.D - d0);
+    const long wg_first = ((long)b * f.D + d0) * L;
+    const uint32_t wg_bytes = (uint32_t)rows_here * (uint32_t)L * (uint32_t)sizeof(T);
+    const uint32_t row_off = (uint32_t)pr * (uint32_t)L * (uint32_t)sizeof(T);   // past the resource for rows past D
+    auto wg_rsrc = [&](const void* base, bool on) {
+        return make_rsrc(static_cast<const T*>(on ? base : f.u) + wg_first, on ? wg_bytes : 0u);
+    };
+    const rsrc_t bu_ = wg_rsrc(f.u, true), bd_ = wg_rsrc(f.delta, true), bo_ = wg_rsrc(a.dout, true);
+    const rsrc_t bz_ = wg_rsrc(f.z, has_z), by_ = wg_rsrc(f.ysave, has_z);
+    const rsrc_t bdu_ = wg_rsrc(a.du, true), bdd_ = wg_rsrc(a.ddelta, true), bdz_ = wg_rsrc(a.dz, has_z && a.dz);
+    // staging view: waves 0, 1 stage B, waves 2, 3 stage C; thread -> (state s_n, pair of steps s_tp) of the block
+    const int s_which = w >> 1, s_n = (tid >> 3) & (NPAD - 1), s_tp = tid & 7;
+    const rsrc_t bbc_ = make_rsrc(static_cast<const T*>(s_which ? f.Cm : f.Bm) + (long)b * f.bc_bstride,
+                                  (uint32_t)N * (uint32_t)L * (uint32_t)sizeof(T));
+    const uint32_t bc_row_off = s_n < N ? (uint32_t)s_n * (uint32_t)L * (uint32_t)sizeof(T) : BUF_OFF;
+
+    // ---- state view: lane -> row, wave -> states 4w..4w+3 --------------------------------
+    const bool s_ok = d0 + lane < f.D;
+    const int sd = s_ok ? d0 + lane : f.D - 1;
+    const long srow = (long)b * f.D + sd;
+    float A2[STATES_PER_LANE], dA[STATES_PER_LANE];
+    f32x4_t ag4;
+    bool n_ok[STATES_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < STATES_PER_LANE; ++k) {
+        const int n = w * STATES_PER_LANE + k;
+        n_ok[k] = n < N;
+        const int nc = n_ok[k] ? n : 0;
+        A2[k] = (n_ok[k] ? f.A[(long)sd * NS + nc] : 0.0f) * LOG2E;
+        if (seg == f.nseg - 1) ag4[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * NS + nc] : 0.0f;  // abar_L g_L := dh_last
+        else ag4[k] = a.seg_g[(seg_rows + srow) * NPAD + w * STATES_PER_LANE + k];
+        dA[k] = 0.0f;
+    }
+    float* const dbc = &sm.dbc[w][0][0][0];
+    float (*const red)[RED_PITCH] = sm.red[w];
+    const int pat = (w * STATES_PER_LANE + (lane & 3)) * GROUP_T;   // this lane's state in a group's [state][step] tile
+
+    const int nblocks = blk_end;
+    // Loads are issued for 64 bytes of a row at a time (an aligned pair of bf16 blocks, one float
+    // block), so that neighbouring pieces of a cache line are requested together.  slot = block index mod LG.
+    constexpr int LG = 64 / (BT * (int)sizeof(T));
+    typename io4<T>::raw ru[LG], rd[LG], rz[LG], ro[LG], ry[LG];
+    typedef typename std::conditional<sizeof(T) == 2, uint32_t, uint2>::type bcpair_t;   // two steps of B or C
+    bcpair_t rbc[LG];
+    auto issue_group = [&](int grp) {
+#pragma unroll
+        for (int s = 0; s < LG; ++s) {
+            const int blk = grp * LG + s;
+            const int t0 = blk * BT + pq * BSL;
+            // slices are whole or empty; rows past D lie beyond the resource
+            const uint32_t off = t0 < L ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
+            ru[s] = io4<T>::load_buf(bu_, off);
+            rd[s] = io4<T>::load_buf(bd_, off);
+            ro[s] = io4<T>::load_buf(bo_, off);
+            rz[s] = io4<T>::load_buf(bz_, off);
+            ry[s] = io4<T>::load_buf(by_, off);
+            const int ts = blk * BT + 2 * s_tp;
+            const uint32_t boff = ts < L ? bc_row_off + (uint32_t)ts * (uint32_t)sizeof(T) : BUF_OFF;
+            if constexpr (sizeof(T) == 2) rbc[s] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(bbc_, (int)boff, 0, 0);
+            else rbc[s] = buf_load8(bbc_, boff);
+        }
+    };
+    issue_group((nblocks - 1) / LG);
+
+    auto load_ckpt = [&](int blk) {
+        return *(reinterpret_cast<const float4*>(f.ckpt + (((long)blk * f.B + b) * f.D + sd) * NPAD) + w);
+    };
+    float4 hck_next = load_ckpt(nblocks - 1);
+    for (int blk = nblocks - 1; blk >= blk_begin; --blk) {
+        const int tc = blk * BT;
+        const int t0 = tc + pq * BSL;
+        const bool live = p_ok && t0 < L;
+        const uint32_t off = t0 < L ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
+        // the state entering this block was requested a block ago (see scan_bwd_kernel)
+        const float4 hck4 = hck_next;
+        if (blk > blk_begin) hck_next = load_ckpt(blk - 1);
+
+        // ---- A: pointwise pre-processing ---------------------------------------------------
+        float u4[BSL], sg4[BSL];  // u and d softplus(x)/dx, needed again in C
+        {
+            float v4[BSL], o4[BSL], dt4[BSL], du4[BSL], dy4[BSL];
+            float z4[BSL], y4[BSL];
+            bcpair_t bcw{};
+            const int slot = blk & (LG - 1);  // uniform
+#pragma unroll
+            for (int s = 0; s < LG; ++s) {  // unrolled so the register arrays stay statically indexed
+                if (slot == s) {
+                    io4<T>::unpack(ru[s], u4); io4<T>::unpack(rd[s], v4); io4<T>::unpack(ro[s], o4);
+                    if (has_z) { io4<T>::unpack(rz[s], z4); io4<T>::unpack(ry[s], y4); }
+                    bcw = rbc[s];
+                }
+            }
+            // An empty slice reads as zeros; its steps must run with dt = 0 (the identity of the
+            // recurrence) and contribute nothing: a bias of -1e30 makes softplus and its derivative
+            // exactly 0 there, without a select per element.
+            const float bias_eff = live ? bias : (softplus ? -1e30f : 0.0f);
+            const float sg_lin = live ? 1.0f : 0.0f;
+#pragma unroll
+            for (int j = 0; j < BSL; ++j) {
+                const float x = v4[j] + bias_eff;
+                float sp, sg;
+                if (softplus) softplus_sigmoid(x, sp, sg); else { sp = x; sg = sg_lin; }
+                dt4[j] = sp;
+                sg4[j] = sg;
+                du4[j] = sp * u4[j];
+                dy4[j] = o4[j];
+            }
+            if (has_z) {
+                float dz4[BSL];
+#pragma unroll
+                for (int j = 0; j < BSL; ++j) {
+                    const float s = sigmoid_fast(z4[j]);
+                    const float zs = z4[j] * s;
+                    dy4[j] = o4[j] * zs;
+                    dz4[j] = (o4[j] * y4[j]) * fmaf(zs, 1.0f - s, s);   // dout y d[z sigmoid(z)]/dz
+                }
+                io4<T>::store_buf(bdz_, off, dz4);   // switched off for all but the first state group
+            }
+            *reinterpret_cast<float4*>(&sm.dt[pr][pq * BSL]) = make_float4(dt4[0], dt4[1], dt4[2], dt4[3]);
+            *reinterpret_cast<float4*>(&sm.du[pr][pq * BSL]) = make_float4(du4[0], du4[1], du4[2], du4[3]);
+            *reinterpret_cast<float4*>(&sm.dy[pr][pq * BSL]) = make_float4(dy4[0], dy4[1], dy4[2], dy4[3]);
+            float2 bc2;
+            if constexpr (sizeof(T) == 2) bc2 = make_float2(bf16_lo(bcw), bf16_hi(bcw));
+            else bc2 = make_float2(__uint_as_float(bcw.x), __uint_as_float(bcw.y));
+            *reinterpret_cast<float2*>(&sm.bcp[s_which][s_tp >> 1][s_n][(s_tp & 1) * 2]) = bc2;
+        }
+        if ((blk & (LG - 1)) == 0 && blk > blk_begin) issue_group(blk / LG - 1);  // in flight during the sweeps below
+        __syncthreads();
+
+        // ---- B1: recompute the states of the block -----------------------------------------
+        __builtin_amdgcn_s_setprio(2);
+        constexpr int NG = BT / GROUP_T;
+        f32x4_t as4[BT], hs4[BT];   // abar_t and h_t
+        {
+            f32x4_t h4 = {hck4.x, hck4.y, hck4.z, hck4.w};
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                const int tl = g * GROUP_T;
+                const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[lane][tl]);
+                const float4 du4 = *reinterpret_cast<const float4*>(&sm.du[lane][tl]);
+                const float4 dy4 = *reinterpret_cast<const float4*>(&sm.dy[lane][tl]);
+                const float4 Bp = *reinterpret_cast<const float4*>(&sm.bcp[0][g][0][0] + pat);
+                float dCv[RED_VALUES];
+#pragma unroll
+                for (int j = 0; j < GROUP_T; ++j) {
+                    const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
+                    float bu[STATES_PER_LANE];
+                    input_step_dpp(bu, f4_get(Bp, j), du);
+                    f32x4_t ab;
+#pragma unroll
+                    for (int k = 0; k < STATES_PER_LANE; ++k) {
+                        ab[k] = exp2_fast(dt * A2[k]);                    // Eq. 4
+                        h4[k] = fmaf(ab[k], h4[k], bu[k]);                // Eq. 2a
+                    }
+                    as4[tl + j] = ab;
+                    hs4[tl + j] = h4;
+#pragma unroll
+                    for (int k = 0; k < STATES_PER_LANE; ++k) dCv[j * STATES_PER_LANE + k] = dy * h4[k];
+                }
+                if (g > 0) reduce_take(red, dbc + STATES_PER_LANE * BT + tl - GROUP_T, lane);  // previous group
+                reduce_put(dCv, red, lane);
+            }
+            reduce_take(red, dbc + STATES_PER_LANE * BT + (NG - 1) * GROUP_T, lane);
+        }
+        // ---- B2: adjoint recurrence, last step of the block first --------------------------
+        __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+        for (int g = NG - 1; g >= 0; --g) {
+            const int tl = g * GROUP_T;
+            const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[lane][tl]);
+            const float4 du4 = *reinterpret_cast<const float4*>(&sm.du[lane][tl]);
+            const float4 dy4 = *reinterpret_cast<const float4*>(&sm.dy[lane][tl]);
+            const float4 Bp = *reinterpret_cast<const float4*>(&sm.bcp[0][g][0][0] + pat);
+            const float4 Cp = *reinterpret_cast<const float4*>(&sm.bcp[1][g][0][0] + pat);
+            float dBv[RED_VALUES], dd[GROUP_T], sb[GROUP_T];
+#pragma unroll
+            for (int j = GROUP_T - 1; j >= 0; --j) {
+                const int t = tl + j;
+                const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
+                f32x4_t g4 = ag4;
+                adjoint_step_dpp(g4, sb[j], f4_get(Cp, j), f4_get(Bp, j), dy);   // g = C dy + abar+ g+;  sb = sum_k B_k g_k
+                dd[j] = 0.0f;
+#pragma unroll
+                for (int k = 0; k < STATES_PER_LANE; ++k) {
+                    ag4[k] = as4[t][k] * g4[k];                         // flows on to h_{t-1}
+                    const float gh = ag4[k] * (t > 0 ? hs4[t > 0 ? t - 1 : 0][k] : f4_get(hck4, k));   // g abar h_{t-1}
+                    dA[k] = fmaf(gh, dt, dA[k]);
+                    dd[j] = fmaf(gh, A2[k], dd[j]);
+                    dBv[j * STATES_PER_LANE + k] = g4[k] * du;
+                }
+            }
+            *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
+            *reinterpret_cast<float4*>(&sm.psb[w][lane][tl]) = make_float4(sb[0], sb[1], sb[2], sb[3]);
+            if (g < NG - 1) reduce_take(red, dbc + tl + GROUP_T, lane);  // previous (later) group
+            reduce_put(dBv, red, lane);
+        }
+        reduce_take(red, dbc, lane);
+        // ---- flush this wave's dB/dC of the block to global memory -------------------------
+        wave_lds_fence();
+#pragma unroll
+        for (int i = 0; i < 2 * STATES_PER_LANE * BT / WAVE; ++i) {
+            const int idx = i * WAVE + lane;
+            const int which = idx / (STATES_PER_LANE * BT), k = (idx / BT) % STATES_PER_LANE, t = idx % BT;
+            const int n = w * STATES_PER_LANE + k;
+            if (n < N && tc + t < L) {
+                float* dst = (which ? a.dC : a.dB) + (long)b * a.dbc_bstride + (long)n * L + tc + t;
+                atomicAdd(dst, dbc[idx]);
+            }
+        }
+        __syncthreads();
+
+        // ---- C: pointwise post-processing ---------------------------------------------------
+        __builtin_amdgcn_s_setprio(0);
+        {
+            const float4 dt4 = *reinterpret_cast<const float4*>(&sm.dt[pr][pq * BSL]);
+            const float4 dy4 = *reinterpret_cast<const float4*>(&sm.dy[pr][pq * BSL]);
+            float dd4[BSL] = {0.f, 0.f, 0.f, 0.f}, sb4[BSL] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ww = 0; ww < NWAVES; ++ww) {
+                const float4 x = *reinterpret_cast<const float4*>(&sm.pdd[ww][pr][pq * BSL]);
+                const float4 y = *reinterpret_cast<const float4*>(&sm.psb[ww][pr][pq * BSL]);
+                dd4[0] += x.x; dd4[1] += x.y; dd4[2] += x.z; dd4[3] += x.w;
+                sb4[0] += y.x; sb4[1] += y.y; sb4[2] += y.z; sb4[3] += y.w;
+            }
+            float du4[BSL], dl4[BSL];
+#pragma unroll
+            for (int j = 0; j < BSL; ++j) {
+                const float dt = f4_get(dt4, j), dy = f4_get(dy4, j);
+                const float ddt = fmaf(u4[j], sb4[j], LN2 * dd4[j]);
+                du4[j] = fmaf(dt, sb4[j], Dsk * dy);
+                dl4[j] = ddt * sg4[j];             // 0 on an empty slice: its sg is 0
+                dD_acc = fmaf(dy, u4[j], dD_acc);
+                db_acc += dl4[j];
+            }
+            if (a.acc) {  // states beyond the first 16: add to the earlier groups' du and ddelta
+                float pu[BSL], pl[BSL];
+                io4<T>::unpack(io4<T>::load_buf(bdu_, off), pu);
+                io4<T>::unpack(io4<T>::load_buf(bdd_, off), pl);
+#pragma unroll
+                for (int j = 0; j < BSL; ++j) { du4[j] += pu[j]; dl4[j] += pl[j]; }
+            }
+            io4<T>::store_buf(bdu_, off, du4);
+            io4<T>::store_buf(bdd_, off, dl4);
+        }
+    }
+
+    // ---- per-row results --------------------------------------------------------------------
+    if (s_ok) {
+        float4* pa = reinterpret_cast<float4*>(a.dA_part + (seg_rows + srow) * NPAD) + w;
+        *pa = make_float4(dA[0], dA[1], dA[2], dA[3]);
+        if (a.dh0 && seg == 0) {
+#pragma unroll
+            for (int k = 0; k < STATES_PER_LANE; ++k)
+                if (n_ok[k]) a.dh0[srow * NS + w * STATES_PER_LANE + k] = ag4[k];
+        }
+    }
+    dD_acc += __shfl_xor(dD_acc, 1);
+    dD_acc += __shfl_xor(dD_acc, 2);
+    db_acc += __shfl_xor(db_acc, 1);
+    db_acc += __shfl_xor(db_acc, 2);
+    if (p_ok && pq == 0) {
+        a.dD_part[seg_rows + prow] = dD_acc;
+        a.db_part[seg_rows + prow] = db_acc;
+    }
+}
+
 // Adjoint aggregate of a segment, for a sequence split across workgroups: runs only the
 // adjoint recurrence g = C dy + abar+ g+ over the segment, from a zero carry (last segment:
 // from dh_last), and leaves the carry abar g at the segment's first step in seg_g.  Needs
@@ -681,14 +1046,14 @@ __global__ void copy_dh_kernel(const float* __restrict__ src, float* __restrict_
 // kernel and per device; `done` is the calling launcher's table for its kernel, indexed by device.
 constexpr int MAX_DEVICES = 64;
 template <typename K>
-static bool allow_backward_lds_once(K kern, bool (&done)[MAX_DEVICES])
+static bool allow_backward_lds_once(K kern, std::atomic<bool> (&done)[MAX_DEVICES], size_t bytes)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return false;
-    if (done[dev]) return true;
-    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(BwdSmem)) != hipSuccess)
-        return false;
-    done[dev] = true;
+    if (done[dev].load(std::memory_order_acquire)) return true;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return false;   // setting it twice from two threads is harmless
+    done[dev].store(true, std::memory_order_release);
     return true;
 }
 
@@ -696,8 +1061,8 @@ template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX>
 static int launch_scan_bwd_fixed(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
     auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH, BCFIX>;
-    static bool lds_ok[MAX_DEVICES] = {};   // this launcher is instantiated once per kernel
-    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok)) return -1;
+    static std::atomic<bool> lds_ok[MAX_DEVICES];   // this launcher is instantiated once per kernel
+    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmem))) return -1;
     kern<<<dim3(grid.x, 1u), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -707,8 +1072,8 @@ template <typename T, bool VEC, bool FULLN, int BCFIX>
 static int launch_scan_bwd_complex(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
     auto kern = scan_bwd_kernel<T, VEC, FULLN, false, BCFIX, true>;
-    static bool lds_ok[MAX_DEVICES] = {};   // this launcher is instantiated once per kernel
-    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok)) return -1;
+    static std::atomic<bool> lds_ok[MAX_DEVICES];   // this launcher is instantiated once per kernel
+    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmem))) return -1;
     if (a.f.nseg > 1) {   // only with selective B and C (the planner does not split the others)
         adjoint_agg_kernel<T, VEC, FULLN, true><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
         const long n = (long)a.f.B * a.f.D * NPAD;
@@ -733,15 +1098,22 @@ static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
     if (bcfix == 1) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 1>(a, grid, stream);
     if (bcfix == 2) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 2>(a, grid, stream);
     if (bcfix == 3) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 3>(a, grid, stream);
-    auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH>;
-    static bool lds_ok[MAX_DEVICES] = {};   // this launcher is instantiated once per kernel
-    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok)) return -1;
     if (a.f.nseg > 1) {
         adjoint_agg_kernel<T, VEC, FULLN><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
         const long n = (long)a.f.B * a.f.D * NPAD;
         carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
     }
-    kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
+    if constexpr (VEC && !ZOH) {   // real state, first-order B-bar, selective B and C, whole 16-byte pieces
+        auto kern = scan_bwd_dpp_kernel<T>;
+        static std::atomic<bool> lds_ok[MAX_DEVICES];
+        if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmemDpp))) return -1;
+        kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmemDpp), stream>>>(a);
+    } else {
+        auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH>;
+        static std::atomic<bool> lds_ok[MAX_DEVICES];   // this launcher is instantiated once per kernel
+        if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmem))) return -1;
+        kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
+    }
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -53,19 +53,21 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xffffu; }
 
-// softplus(r) = log(1 + e^r) and sigmoid(r), sharing one exponential.
-// For e^r below 2^-12 the series e - e^2/2 replaces log(1+e), which would lose the
-// low bits of e; above r = 20 softplus(r) = r to float precision.
+// softplus(r) = log(1 + e^r) and sigmoid(r), sharing one exponential and one reciprocal.
+// With w = fl(1 + e) and c = e - (w - 1), the exact rounding error of that sum,
+// log(1 + e) = log(w) + log(1 + c / w) = log(w) + c / w to float precision: accurate for every
+// e, however small, with no case split (w = 1 gives e itself).  Above r = 20 softplus(r) = r to
+// float precision (and e^r may overflow, which the select discards); the exponent is capped
+// so that the sigmoid comes out as 1 there instead of inf * 0.
 __device__ __forceinline__ void softplus_sigmoid(float r, float& sp, float& sg)
 {
-    float e = exp2_fast(r * LOG2E);
-    float one_e = 1.0f + e;
-    float big = log2_fast(one_e) * LN2;
-    float small = e - 0.5f * e * e;
-    sp = (e < 2.44140625e-4f) ? small : big;
-    sp = (r > 20.0f) ? r : sp;
-    float inv = rcp_fast(one_e);          // 1/(1+e^r)
-    sg = (r > 20.0f) ? 1.0f : e * inv;    // e^r/(1+e^r); avoids inf*0 for huge r
+    const float e = exp2_fast(fminf(r * LOG2E, 64.0f));
+    const float w = 1.0f + e;
+    const float inv = rcp_fast(w);                 // 1 / (1 + e^r)
+    const float c = e - (w - 1.0f);
+    const float lp = fmaf(log2_fast(w), LN2, c * inv);
+    sp = (r > 20.0f) ? r : lp;
+    sg = e * inv;                                  // e^r / (1 + e^r)
 }
 // Exact zero-order hold (Eq. 4): phi(dt, A) = (exp(dt A) - 1) / A multiplies B u in the
 // state update (dt itself where A == 0), and d phi / d A = (x e^x - (e^x - 1)) / A^2 with
@@ -318,6 +320,10 @@ template <> struct io4<float> {
         r.a = make_float4(__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w));
         return r;
     }
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[4])   // dropped if off is out of range
+    {
+        buf_store16(rs, off, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+    }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
     {
         v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
@@ -357,6 +363,11 @@ template <> struct io4<bf16_t> {
         raw r;
         r.w = buf_load8(rs, off);
         return r;
+    }
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[4])   // dropped if off is out of range
+    {
+        const u32x2v x = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        __builtin_amdgcn_raw_buffer_store_b64(x, rs, (int)off, 0, 0);
     }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
     {

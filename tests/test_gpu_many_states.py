@@ -46,15 +46,17 @@ def test_many_states_forward_and_backward(io, batch, seqlen, dim, dstate, zoh, g
     okw = dict(Dskip=w["Dskip"], z=w["z"] if gate else None, bias=w["delta_bias"], h0=w["h0"], softplus=True, exact_zoh=zoh)
     ref_f = orc.scan_fwd(w["u"], w["delta"], w["A"], w["B"], w["C"], **okw)
     ref_b = orc.scan_bwd(w["u"], w["delta"], w["A"], w["B"], w["C"], w["dout"], dh_last=w["dh_last"], **okw)
-    util.assert_close(out, ref_f["out"], io, "out")
+    # the io-dtype tensors that every pass of 16 states adds to (pre-gate y, du, ddelta) are rounded once per pass
+    fl = util.ELEM_FLOOR_ROUNDED if io == "bf16" else None
+    util.assert_close(out, ref_f["out"], io, "out", elem_floor=fl)
     util.assert_close(h_last, ref_f["h_last"], io, "h_last")
     for k in GRADS:
         if grads[k] is not None:
-            util.assert_close(grads[k], ref_b[ORACLE_NAME.get(k, k)], io, k)
+            util.assert_close(grads[k], ref_b[ORACLE_NAME.get(k, k)], io, k, elem_floor=fl if k in ("du", "ddelta", "dz") else None)
     # plain forward (nothing kept for backward): with a gate the workspace carries the running sum
     ws0 = torch.empty(max(256, B.ss_workspace_bytes(batch, dim, seqlen, dstate, False, code, gate)), dtype=torch.uint8, device="cuda")
     out2, _ = B.ss_scan_fwd(g["u"], g["delta"], g["A"], g["B"], g["C"], workspace=ws0, save_for_bwd=False, **kw)
-    util.assert_close(out2, ref_f["out"], io, "plain forward out")
+    util.assert_close(out2, ref_f["out"], io, "plain forward out", elem_floor=fl)
     if gate:
         with pytest.raises(B.SsError):
             B.ss_scan_fwd(g["u"], g["delta"], g["A"], g["B"], g["C"], **kw)

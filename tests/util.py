@@ -11,8 +11,11 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 # Element-wise criterion beside it: |gpu - oracle| <= tol * (|oracle| + ELEM_FLOOR * max |oracle|)
 # for every element, so that elements far below the tensor's peak are checked against their own
 # size down to a floor (sums of terms of the peak's size cancel to small values whose float32
-# error is relative to the terms; the floor leaves room for that).
+# error is relative to the terms; the floor leaves room for that).  Where io-dtype roundings lie
+# inside the operation (the layer's intermediates; the pre-gate output accumulated over the passes
+# of more than 16 states) small results carry bf16-sized errors of the terms: floor ELEM_FLOOR_ROUNDED.
 ELEM_FLOOR = 0.05
+ELEM_FLOOR_ROUNDED = 0.25
 
 
 def upload(w, device="cuda"):
@@ -83,11 +86,12 @@ def tolerance(got, io, exact_inputs=True):
     return TOL[io]
 
 
-def assert_close(got, ref, io, name, exact_inputs=True):
+def assert_close(got, ref, io, name, exact_inputs=True, elem_floor=None):
     """Both criteria (see TOL, ELEM_FLOOR); returns the scale-relative error."""
     tol = tolerance(got, io, exact_inputs)
+    floor = elem_floor if elem_floor is not None else (ELEM_FLOOR if exact_inputs else ELEM_FLOOR_ROUNDED)
     e = rel_err(got, ref)
     assert e <= tol, "%s: scale-relative error %.3e exceeds %.1e" % (name, e, tol)
-    ee = elem_err(got, ref)
-    assert ee <= tol, "%s: element-wise error %.3e (of |ref| + %.2f max|ref|) exceeds %.1e" % (name, ee, ELEM_FLOOR, tol)
+    ee = elem_err(got, ref, floor)
+    assert ee <= tol, "%s: element-wise error %.3e (of |ref| + %.2f max|ref|) exceeds %.1e" % (name, ee, floor, tol)
     return e
