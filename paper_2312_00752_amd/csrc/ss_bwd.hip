@@ -623,6 +623,18 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
         }
     };
     issue_group((nblocks - 1) / LG);
+    // Stores likewise: with bf16 a block is 32 bytes of a row, so the results of an odd block wait in
+    // registers for the even block below it (segments start at even blocks) and the two pieces of
+    // the 64-byte neighbourhood are written back to back.
+    typename io4<T>::packed keep_du{}, keep_dl{}, keep_dz{};
+    uint32_t keep_off = BUF_OFF;
+    auto store_paired = [&](rsrc_t rs, uint32_t off, typename io4<T>::packed now, typename io4<T>::packed& keep, bool odd) {
+        if constexpr (LG == 2) {
+            if (odd) { keep = now; return; }
+            io4<T>::store_packed(rs, keep_off, keep);   // switched off when nothing waits
+        }
+        io4<T>::store_packed(rs, off, now);
+    };
 
     auto load_ckpt = [&](int blk) {
         return *(reinterpret_cast<const float4*>(f.ckpt + (((long)blk * f.B + b) * f.D + sd) * NPAD) + w);
@@ -676,7 +688,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
                     dy4[j] = o4[j] * zs;
                     dz4[j] = (o4[j] * y4[j]) * fmaf(zs, 1.0f - s, s);   // dout y d[z sigmoid(z)]/dz
                 }
-                io4<T>::store_buf(bdz_, off, dz4);   // switched off for all but the first state group
+                store_paired(bdz_, off, io4<T>::pack(dz4), keep_dz, blk & 1);   // switched off for all but the first state group
             }
             *reinterpret_cast<float4*>(&sm.dt[pr][pq * BSL]) = make_float4(dt4[0], dt4[1], dt4[2], dt4[3]);
             *reinterpret_cast<float4*>(&sm.du[pr][pq * BSL]) = make_float4(du4[0], du4[1], du4[2], du4[3]);
@@ -801,8 +813,9 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
 #pragma unroll
                 for (int j = 0; j < BSL; ++j) { du4[j] += pu[j]; dl4[j] += pl[j]; }
             }
-            io4<T>::store_buf(bdu_, off, du4);
-            io4<T>::store_buf(bdd_, off, dl4);
+            store_paired(bdu_, off, io4<T>::pack(du4), keep_du, blk & 1);
+            store_paired(bdd_, off, io4<T>::pack(dl4), keep_dl, blk & 1);
+            if constexpr (LG == 2) keep_off = (blk & 1) ? off : BUF_OFF;
         }
     }
 

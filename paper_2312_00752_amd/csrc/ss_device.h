@@ -320,10 +320,13 @@ template <> struct io4<float> {
         r.a = make_float4(__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w));
         return r;
     }
-    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[4])   // dropped if off is out of range
+    typedef uint4 packed;   // four elements as stored
+    static __device__ __forceinline__ packed pack(const float (&v)[4])
     {
-        buf_store16(rs, off, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+        return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
     }
+    static __device__ __forceinline__ void store_packed(rsrc_t rs, uint32_t off, packed x) { buf_store16(rs, off, x); }   // dropped if off is out of range
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[4]) { store_packed(rs, off, pack(v)); }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
     {
         v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
@@ -364,11 +367,14 @@ template <> struct io4<bf16_t> {
         r.w = buf_load8(rs, off);
         return r;
     }
-    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[4])   // dropped if off is out of range
+    typedef uint2 packed;   // four elements as stored
+    static __device__ __forceinline__ packed pack(const float (&v)[4]) { return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])); }
+    static __device__ __forceinline__ void store_packed(rsrc_t rs, uint32_t off, packed p)   // dropped if off is out of range
     {
-        const u32x2v x = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        const u32x2v x = {p.x, p.y};
         __builtin_amdgcn_raw_buffer_store_b64(x, rs, (int)off, 0, 0);
     }
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[4]) { store_packed(rs, off, pack(v)); }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[4])
     {
         v[0] = bf16_lo(r.w.x); v[1] = bf16_hi(r.w.x);
