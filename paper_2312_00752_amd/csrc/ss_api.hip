@@ -182,6 +182,13 @@ int check_fwd(const ss_fwd_params* p, bool for_bwd, bool bc_dense = true)
     return SS_OK;
 }
 
+// Whether a pass over fewer than 16 states deals them out to the waves in turn (FwdArgs::il): the
+// common path only.  Forward and backward call derive it from the same arguments.
+inline bool deals_states(int vec_ok, uint32_t flags)
+{
+    return vec_ok && !(flags & (SS_EXACT_ZOH_B | SS_B_FIXED | SS_C_FIXED | SS_COMPLEX_STATE));
+}
+
 ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
 {
     ss::FwdArgs a{};
@@ -190,6 +197,7 @@ ss::FwdArgs make_fwd_args(const ss_fwd_params* p, long bc_bstride)
     a.flags = p->flags;
     // 16-byte slices, addressed through per-workgroup buffer resources (64 rows, 31-bit offsets)
     a.vec_ok = p->seqlen % 8 == 0 && (size_t)p->seqlen * 64 * sizeof(float) < ((size_t)1 << 31);
+    a.il = deals_states(a.vec_ok, p->flags) && a.N < 16;
     a.u = p->u; a.delta = p->delta; a.z = (p->flags & SS_HAS_Z) ? p->z : nullptr;
     a.Bm = p->Bmat; a.Cm = p->Cmat; a.A = p->A;
     a.bc_bstride = bc_bstride;
@@ -217,6 +225,7 @@ void narrow_to_group(ss::FwdArgs& a, const ss_fwd_params* p, int g, size_t ckpt_
     const int n0 = g * 16;
     const size_t esz = p->io_dtype == SS_BF16 ? 2 : 4;
     a.N = slots(p) - n0 < 16 ? slots(p) - n0 : 16;
+    a.il = deals_states(a.vec_ok, p->flags) && a.N < 16;
     a.A = at(a.A, n0);
     a.h0 = at(a.h0, n0);
     a.h_last = at(a.h_last, n0);

@@ -83,6 +83,34 @@ __device__ __forceinline__ void reduce_take(float (*red)[RED_PITCH], float* acc,
     if (p == 0) acc[(vi & 3) * BT + (vi >> 2)] = s;
     wave_lds_fence();
 }
+// The same for a kernel built for SPL slots per lane: a group of steps then yields 4 * SPL values, and the
+// 16-value tile takes 4 / SPL groups before it is summed.  Value row = (group within the tile) * 4 SPL +
+// step j * SPL + slot k; the totals of slot k at step t of the block go to acc[k * BT + t].
+template <int SPL>
+__device__ __forceinline__ void reduce_put_n(const float (&v)[RED_VALUES], float (*red)[RED_PITCH], int lane, int g)
+{
+    constexpr int GPT = STATES_PER_LANE / SPL;   // groups per tile
+    const int base = (g % GPT) * GROUP_T * SPL;
+#pragma unroll
+    for (int j = 0; j < GROUP_T; ++j)
+#pragma unroll
+        for (int k = 0; k < SPL; ++k) red[base + j * SPL + k][lane] = v[j * STATES_PER_LANE + k];
+    wave_lds_fence();
+}
+template <int SPL>
+__device__ __forceinline__ void reduce_take_n(float (*red)[RED_PITCH], float* acc, int lane, int g_first)   // g_first: lowest group in the tile
+{
+    constexpr int GPT = STATES_PER_LANE / SPL;
+    const int p = lane >> 4, vi = lane & 15;
+    const float4* src = reinterpret_cast<const float4*>(&red[vi][16 * p]);
+    const float4 a0 = src[0], a1 = src[1], a2 = src[2], a3 = src[3];
+    float s = ((a0.x + a0.y) + (a0.z + a0.w)) + ((a1.x + a1.y) + (a1.z + a1.w)) +
+              ((a2.x + a2.y) + (a2.z + a2.w)) + ((a3.x + a3.y) + (a3.z + a3.w));
+    s = sum_over_lane_quarters(s);
+    const int gi = vi / (GROUP_T * SPL), j = (vi % (GROUP_T * SPL)) / SPL, k = vi % SPL;
+    if (p == 0) acc[k * BT + (g_first + gi) * GROUP_T + j] = s;
+    wave_lds_fence();
+}
 
 // Same decomposition as the forward kernel (64 rows x 4 waves; wave w owns states
 // 4w..4w+3 of every row), walking blocks of BT steps from last to first.  Per block:
@@ -494,43 +522,69 @@ struct BwdSmemDpp {
     float bcp[2][BT / GROUP_T][NPAD][GROUP_T];   // B (0) and C (1) of the block
 };
 
-// The input term of Eq. 2a for a lane's four states: bu[k] = B_k * du, with Bq holding B of the
-// wave's four states in every group of four lanes (state k in lane k).  Written out for the same
+// The input term of Eq. 2a for a lane's SPL states: bu[k] = B_k * du, with Bq holding B of the
+// wave's states in every group of four lanes (slot k in lane k).  Written out for the same
 // reason as adjoint_step_dpp, with the same leading wait state.
+#define SS_QP(k) " quad_perm:[" #k "," #k "," #k "," #k "] row_mask:0xf bank_mask:0xf"
+template <int SPL>
 __device__ __forceinline__ void input_step_dpp(float (&bu)[STATES_PER_LANE], float Bq, float du)
 {
-    asm("s_nop 1\n\t"
-        "v_mul_f32_dpp %0, %4, %5 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf\n\t"
-        "v_mul_f32_dpp %1, %4, %5 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf\n\t"
-        "v_mul_f32_dpp %2, %4, %5 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf\n\t"
-        "v_mul_f32_dpp %3, %4, %5 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf"
-        : "=&v"(bu[0]), "=&v"(bu[1]), "=&v"(bu[2]), "=&v"(bu[3])
-        : "v"(Bq), "v"(du));
+    if constexpr (SPL == 4)
+        asm("s_nop 1\n\t"
+            "v_mul_f32_dpp %0, %4, %5" SS_QP(0) "\n\t"
+            "v_mul_f32_dpp %1, %4, %5" SS_QP(1) "\n\t"
+            "v_mul_f32_dpp %2, %4, %5" SS_QP(2) "\n\t"
+            "v_mul_f32_dpp %3, %4, %5" SS_QP(3)
+            : "=&v"(bu[0]), "=&v"(bu[1]), "=&v"(bu[2]), "=&v"(bu[3]) : "v"(Bq), "v"(du));
+    else if constexpr (SPL == 2)
+        asm("s_nop 1\n\t"
+            "v_mul_f32_dpp %0, %2, %3" SS_QP(0) "\n\t"
+            "v_mul_f32_dpp %1, %2, %3" SS_QP(1)
+            : "=&v"(bu[0]), "=&v"(bu[1]) : "v"(Bq), "v"(du));
+    else
+        asm("s_nop 1\n\t"
+            "v_mul_f32_dpp %0, %1, %2" SS_QP(0)
+            : "=&v"(bu[0]) : "v"(Bq), "v"(du));
 }
 
-// One step of the adjoint recurrence for a lane's four states.  On entry g[k] = abar+ g+ of state k;
-// Cq / Bq hold C / B of the wave's four states in every group of four lanes (state k in lane k).
+// One step of the adjoint recurrence for a lane's SPL states.  On entry g[k] = abar+ g+ of slot k;
+// Cq / Bq hold C / B of the wave's states in every group of four lanes (slot k in lane k).
 //     g[k] += C_k dy            (the gradient reaching h_t)          sb = sum_k B_k g[k]
 // The leading wait state covers a DPP operand the compiler might have copied with a vector move
 // just before (a DPP read needs two wait states after a vector write of the same register).
+template <int SPL>
 __device__ __forceinline__ void adjoint_step_dpp(f32x4_t& g, float& sb, float Cq, float Bq, float dy)
 {
     float g0 = g[0], g1 = g[1], g2 = g[2], g3 = g[3];
-    asm("s_nop 1\n\t"
-        "v_fmac_f32_dpp %0, %5, %7 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %1, %5, %7 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %5, %7 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %5, %7 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf\n\t"
-        "v_mul_f32_dpp %4, %6, %0 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %4, %6, %1 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %4, %6, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %4, %6, %3 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf"
-        : "+v"(g0), "+v"(g1), "+v"(g2), "+v"(g3), "=&v"(sb)
-        : "v"(Cq), "v"(Bq), "v"(dy));
+    if constexpr (SPL == 4)
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %5, %7" SS_QP(0) "\n\t"
+            "v_fmac_f32_dpp %1, %5, %7" SS_QP(1) "\n\t"
+            "v_fmac_f32_dpp %2, %5, %7" SS_QP(2) "\n\t"
+            "v_fmac_f32_dpp %3, %5, %7" SS_QP(3) "\n\t"
+            "v_mul_f32_dpp %4, %6, %0" SS_QP(0) "\n\t"
+            "v_fmac_f32_dpp %4, %6, %1" SS_QP(1) "\n\t"
+            "v_fmac_f32_dpp %4, %6, %2" SS_QP(2) "\n\t"
+            "v_fmac_f32_dpp %4, %6, %3" SS_QP(3)
+            : "+v"(g0), "+v"(g1), "+v"(g2), "+v"(g3), "=&v"(sb) : "v"(Cq), "v"(Bq), "v"(dy));
+    else if constexpr (SPL == 2)
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %3, %5" SS_QP(0) "\n\t"
+            "v_fmac_f32_dpp %1, %3, %5" SS_QP(1) "\n\t"
+            "v_mul_f32_dpp %2, %4, %0" SS_QP(0) "\n\t"
+            "v_fmac_f32_dpp %2, %4, %1" SS_QP(1)
+            : "+v"(g0), "+v"(g1), "=&v"(sb) : "v"(Cq), "v"(Bq), "v"(dy));
+    else
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %2, %4" SS_QP(0) "\n\t"
+            "v_mul_f32_dpp %1, %3, %0" SS_QP(0)
+            : "+v"(g0), "=&v"(sb) : "v"(Cq), "v"(Bq), "v"(dy));
     g[0] = g0; g[1] = g1; g[2] = g2; g[3] = g3;
 }
+#undef SS_QP
 
-template <typename T>
+// SPL: slots per lane the state phases are built for (see scan_fwd_kernel).
+template <typename T, int SPL>
 __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -585,8 +639,8 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
     bool n_ok[STATES_PER_LANE];
 #pragma unroll
     for (int k = 0; k < STATES_PER_LANE; ++k) {
-        const int n = w * STATES_PER_LANE + k;
-        n_ok[k] = n < N;
+        const int n = slot_state(w, k, f.il);
+        n_ok[k] = n < N && k < SPL;
         const int nc = n_ok[k] ? n : 0;
         A2[k] = (n_ok[k] ? f.A[(long)sd * NS + nc] : 0.0f) * LOG2E;
         if (seg == f.nseg - 1) ag4[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * NS + nc] : 0.0f;  // abar_L g_L := dh_last
@@ -595,7 +649,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
     }
     float* const dbc = &sm.dbc[w][0][0][0];
     float (*const red)[RED_PITCH] = sm.red[w];
-    const int pat = (w * STATES_PER_LANE + (lane & 3)) * GROUP_T;   // this lane's state in a group's [state][step] tile
+    const int pat = slot_state(w, lane & 3, f.il) * GROUP_T;   // in a group's [state][step] tile: the state of slot lane % 4
 
     const int nblocks = blk_end;
     // Loads are issued for 64 bytes of a row at a time (an aligned pair of bf16 blocks, one float
@@ -704,6 +758,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
         // ---- B1: recompute the states of the block -----------------------------------------
         __builtin_amdgcn_s_setprio(2);
         constexpr int NG = BT / GROUP_T;
+        constexpr int GPT = STATES_PER_LANE / SPL;   // groups of steps per tile of the cross-row reduction
         f32x4_t as4[BT], hs4[BT];   // abar_t and h_t
         {
             f32x4_t h4 = {hck4.x, hck4.y, hck4.z, hck4.w};
@@ -719,22 +774,23 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
                 for (int j = 0; j < GROUP_T; ++j) {
                     const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
                     float bu[STATES_PER_LANE];
-                    input_step_dpp(bu, f4_get(Bp, j), du);
-                    f32x4_t ab;
+                    input_step_dpp<SPL>(bu, f4_get(Bp, j), du);
+                    f32x4_t ab = {1.f, 1.f, 1.f, 1.f};
 #pragma unroll
-                    for (int k = 0; k < STATES_PER_LANE; ++k) {
+                    for (int k = 0; k < SPL; ++k) {
                         ab[k] = exp2_fast(dt * A2[k]);                    // Eq. 4
                         h4[k] = fmaf(ab[k], h4[k], bu[k]);                // Eq. 2a
                     }
                     as4[tl + j] = ab;
                     hs4[tl + j] = h4;
 #pragma unroll
-                    for (int k = 0; k < STATES_PER_LANE; ++k) dCv[j * STATES_PER_LANE + k] = dy * h4[k];
+                    for (int k = 0; k < SPL; ++k) dCv[j * STATES_PER_LANE + k] = dy * h4[k];
                 }
-                if (g > 0) reduce_take(red, dbc + STATES_PER_LANE * BT + tl - GROUP_T, lane);  // previous group
-                reduce_put(dCv, red, lane);
+                // the tile of the previous GPT groups is summed a group later, before this group's values go in
+                if (g > 0 && g % GPT == 0) reduce_take_n<SPL>(red, dbc + STATES_PER_LANE * BT, lane, g - GPT);
+                reduce_put_n<SPL>(dCv, red, lane, g);
             }
-            reduce_take(red, dbc + STATES_PER_LANE * BT + (NG - 1) * GROUP_T, lane);
+            reduce_take_n<SPL>(red, dbc + STATES_PER_LANE * BT, lane, NG - GPT);
         }
         // ---- B2: adjoint recurrence, last step of the block first --------------------------
         __builtin_amdgcn_s_setprio(3);
@@ -752,10 +808,10 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
                 const int t = tl + j;
                 const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
                 f32x4_t g4 = ag4;
-                adjoint_step_dpp(g4, sb[j], f4_get(Cp, j), f4_get(Bp, j), dy);   // g = C dy + abar+ g+;  sb = sum_k B_k g_k
+                adjoint_step_dpp<SPL>(g4, sb[j], f4_get(Cp, j), f4_get(Bp, j), dy);   // g = C dy + abar+ g+;  sb = sum_k B_k g_k
                 dd[j] = 0.0f;
 #pragma unroll
-                for (int k = 0; k < STATES_PER_LANE; ++k) {
+                for (int k = 0; k < SPL; ++k) {
                     ag4[k] = as4[t][k] * g4[k];                         // flows on to h_{t-1}
                     const float gh = ag4[k] * (t > 0 ? hs4[t > 0 ? t - 1 : 0][k] : f4_get(hck4, k));   // g abar h_{t-1}
                     dA[k] = fmaf(gh, dt, dA[k]);
@@ -765,18 +821,18 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
             }
             *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
             *reinterpret_cast<float4*>(&sm.psb[w][lane][tl]) = make_float4(sb[0], sb[1], sb[2], sb[3]);
-            if (g < NG - 1) reduce_take(red, dbc + tl + GROUP_T, lane);  // previous (later) group
-            reduce_put(dBv, red, lane);
+            if (g < NG - 1 && (g + 1) % GPT == 0) reduce_take_n<SPL>(red, dbc, lane, g + 1);  // the tile of the GPT groups above
+            reduce_put_n<SPL>(dBv, red, lane, g);
         }
-        reduce_take(red, dbc, lane);
+        reduce_take_n<SPL>(red, dbc, lane, 0);
         // ---- flush this wave's dB/dC of the block to global memory -------------------------
         wave_lds_fence();
 #pragma unroll
         for (int i = 0; i < 2 * STATES_PER_LANE * BT / WAVE; ++i) {
             const int idx = i * WAVE + lane;
             const int which = idx / (STATES_PER_LANE * BT), k = (idx / BT) % STATES_PER_LANE, t = idx % BT;
-            const int n = w * STATES_PER_LANE + k;
-            if (n < N && tc + t < L) {
+            const int n = slot_state(w, k, f.il);
+            if (k < SPL && n < N && tc + t < L) {
                 float* dst = (which ? a.dC : a.dB) + (long)b * a.dbc_bstride + (long)n * L + tc + t;
                 atomicAdd(dst, dbc[idx]);
             }
@@ -826,7 +882,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
         if (a.dh0 && seg == 0) {
 #pragma unroll
             for (int k = 0; k < STATES_PER_LANE; ++k)
-                if (n_ok[k]) a.dh0[srow * NS + w * STATES_PER_LANE + k] = ag4[k];
+                if (n_ok[k]) a.dh0[srow * NS + slot_state(w, k, f.il)] = ag4[k];
         }
     }
     dD_acc += __shfl_xor(dD_acc, 1);
@@ -844,7 +900,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
 // from dh_last), and leaves the carry abar g at the segment's first step in seg_g.  Needs
 // no states, so it is the forward kernel's loop structure walked backwards: 32-step chunks,
 // dt and dy staged through LDS, C on the scalar path.
-template <typename T, bool VEC, bool FULLN, bool CPLX = false>
+template <typename T, bool VEC, bool FULLN, bool CPLX = false, int SPL = STATES_PER_LANE>
 __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -880,8 +936,8 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
     bool n_ok[STATES_PER_LANE];
 #pragma unroll
     for (int k = 0; k < STATES_PER_LANE; ++k) {
-        const int n = w * STATES_PER_LANE + k;
-        n_ok[k] = n < N;
+        const int n = slot_state(w, k, f.il);
+        n_ok[k] = n < N && k < SPL;
         const int nc = n_ok[k] ? n : 0;
         An[k] = n_ok[k] ? f.A[(long)sd * NS + nc] : 0.0f;
         A2[k] = An[k] * LOG2E;
@@ -947,7 +1003,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
                     }
                 } else {
 #pragma unroll
-                    for (int k = 0; k < STATES_PER_LANE; ++k)
+                    for (int k = 0; k < SPL; ++k)
                         ag[k] = exp2_fast(dt * A2[k]) * fmaf(Cg[k].get(j), dy, ag[k]);
                 }
             }
@@ -970,7 +1026,7 @@ __global__ void carry_bwd_kernel(const BwdArgs a)
     const long rows = (long)f.B * f.D;
     if (i >= rows * NPAD) return;
     const long row = i / NPAD;
-    const int n = i % NPAD, d = row % f.D;
+    const int n = position_state((int)(i % NPAD), f.il), d = row % f.D;   // the state this slot of the record holds
     const float A2 = n < f.N ? f.A[(long)d * f.NS + n] * LOG2E : 0.0f;
     // complex state: slots (n, n^1) are one state; the carry is multiplied by conj(exp(A sum_dt))
     const bool cplx_state = f.flags & F_COMPLEX;
@@ -1040,9 +1096,10 @@ __global__ void finalize_kernel(const BwdArgs a, int have_partials)
             if (n == 0) { sD += a.dD_part[row]; sb += a.db_part[row]; }
         }
     }
-    if (n < a.f.N) a.dA[(long)d * a.f.NS + n] = sA;
-    if (n < a.f.N && bfix) a.dB[(long)d * a.f.NS + n] = sB;
-    if (n < a.f.N && cfix) a.dC[(long)d * a.f.NS + n] = sC;
+    const int st = position_state(n, a.f.il);   // the state whose partial sums sit at slot n of the records
+    if (st < a.f.N) a.dA[(long)d * a.f.NS + st] = sA;
+    if (st < a.f.N && bfix) a.dB[(long)d * a.f.NS + st] = sB;
+    if (st < a.f.N && cfix) a.dC[(long)d * a.f.NS + st] = sC;
     if (n == 0) {
         if (a.dD) a.dD[d] = sD;   // null for all but the first state group
         if (a.dbias) a.dbias[d] = a.acc ? a.dbias[d] + sb : sb;
@@ -1096,6 +1153,22 @@ static int launch_scan_bwd_complex(const BwdArgs& a, dim3 grid, hipStream_t stre
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// the common case (scan_bwd_dpp_kernel), with the adjoint aggregates of a split sequence first
+template <typename T, bool FULLN, int SPL>
+static int launch_scan_bwd_dpp(const BwdArgs& a, dim3 grid, hipStream_t stream)
+{
+    if (a.f.nseg > 1) {
+        adjoint_agg_kernel<T, true, FULLN, false, SPL><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
+        const long n = (long)a.f.B * a.f.D * NPAD;
+        carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    }
+    auto kern = scan_bwd_dpp_kernel<T, SPL>;
+    static std::atomic<bool> lds_ok[MAX_DEVICES];   // this launcher is instantiated once per kernel
+    if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmemDpp))) return -1;
+    kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmemDpp), stream>>>(a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH>
 static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
@@ -1111,23 +1184,25 @@ static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
     if (bcfix == 1) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 1>(a, grid, stream);
     if (bcfix == 2) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 2>(a, grid, stream);
     if (bcfix == 3) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 3>(a, grid, stream);
-    if (a.f.nseg > 1) {
-        adjoint_agg_kernel<T, VEC, FULLN><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
-        const long n = (long)a.f.B * a.f.D * NPAD;
-        carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
-    }
     if constexpr (VEC && !ZOH) {   // real state, first-order B-bar, selective B and C, whole 16-byte pieces
-        auto kern = scan_bwd_dpp_kernel<T>;
-        static std::atomic<bool> lds_ok[MAX_DEVICES];
-        if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmemDpp))) return -1;
-        kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmemDpp), stream>>>(a);
+        if constexpr (!FULLN) {    // fewer than 16 states dealt out to the waves: kernels built for 1 or 2 slots per lane
+            const int spl = slots_for(a.f.N, a.f.il);
+            if (spl == 1) return launch_scan_bwd_dpp<T, FULLN, 1>(a, grid, stream);
+            if (spl == 2) return launch_scan_bwd_dpp<T, FULLN, 2>(a, grid, stream);
+        }
+        return launch_scan_bwd_dpp<T, FULLN, STATES_PER_LANE>(a, grid, stream);
     } else {
+        if (a.f.nseg > 1) {
+            adjoint_agg_kernel<T, VEC, FULLN><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
+            const long n = (long)a.f.B * a.f.D * NPAD;
+            carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+        }
         auto kern = scan_bwd_kernel<T, VEC, FULLN, ZOH>;
         static std::atomic<bool> lds_ok[MAX_DEVICES];   // this launcher is instantiated once per kernel
         if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmem))) return -1;
         kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmem), stream>>>(a);
+        return hipGetLastError() == hipSuccess ? 0 : -1;
     }
-    return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 int launch_bwd(const BwdArgs& a, int io_dtype, hipStream_t stream)

@@ -28,6 +28,13 @@ constexpr int SLICE = CHUNK_T * ROWS / THREADS;        // 8 steps per thread in 
 constexpr int SLICES = CHUNK_T / SLICE;                // 4 threads per row in the pointwise view
 constexpr int TPAD = CHUNK_T + 4;                      // LDS row pitch (floats) of (row, t) tiles
 
+// State held by slot k of wave w, and state stored at position 4w + k of a 16-float workspace
+// record: 4w + k, or 4k + w when the states are dealt out to the waves in turn (FwdArgs::il).
+__host__ __device__ __forceinline__ int slot_state(int w, int k, int il) { return il ? k * NWAVES + w : w * STATES_PER_LANE + k; }
+__host__ __device__ __forceinline__ int position_state(int pos, int il) { return slot_state(pos / STATES_PER_LANE, pos % STATES_PER_LANE, il); }
+// slots per lane a kernel is built for when the states are dealt out: 1, 2 or 4
+__host__ __device__ __forceinline__ int slots_for(int N, int il) { return !il ? STATES_PER_LANE : (N <= NWAVES ? 1 : (N <= 2 * NWAVES ? 2 : STATES_PER_LANE)); }
+
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 

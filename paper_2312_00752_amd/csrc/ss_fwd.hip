@@ -41,8 +41,10 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 // kernel) and both 16-step halves of the chunk; the result goes through the dt tile in LDS to
 // the pointwise threads, rounded to bf16 as the stored delta would be.  Saves the projection
 // kernel and the write and read of a (B,D,L) tensor.
+// SPL: slots per lane the recurrence is built for (4, or ceil(N / 4) rounded up to 1 or 2 when the
+// states are dealt out to the waves in turn, FwdArgs::il).
 template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false,
-          int FUSED_KS = 0>
+          int FUSED_KS = 0, int SPL = STATES_PER_LANE>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
@@ -104,8 +106,8 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     bool n_ok[STATES_PER_LANE];
 #pragma unroll
     for (int k = 0; k < STATES_PER_LANE; ++k) {
-        const int n = w * STATES_PER_LANE + k;
-        n_ok[k] = n < N;
+        const int n = slot_state(w, k, a.il);
+        n_ok[k] = n < N && k < SPL;
         const int nc = n_ok[k] ? n : 0;
         An[k] = n_ok[k] ? a.A[(long)sd * NS + nc] : 0.0f;
         A2[k] = An[k] * LOG2E;
@@ -361,7 +363,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                     }
                 } else {
 #pragma unroll
-                    for (int k = 0; k < STATES_PER_LANE; ++k) {
+                    for (int k = 0; k < SPL; ++k) {
                         const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
                         float bu = du * Bval(cur, k, j);
                         if (ZOH) bu *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
@@ -442,7 +444,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     } else if (a.h_last && s_ok && seg == a.nseg - 1) {
 #pragma unroll
         for (int k = 0; k < STATES_PER_LANE; ++k)
-            if (n_ok[k]) a.h_last[srow * NS + w * STATES_PER_LANE + k] = h[k];
+            if (n_ok[k]) a.h_last[srow * NS + slot_state(w, k, a.il)] = h[k];
     }
 }
 
@@ -454,7 +456,7 @@ __global__ void carry_fwd_kernel(const FwdArgs a)
     const long rows = (long)a.B * a.D;
     if (i >= rows * NPAD) return;
     const long row = i / NPAD;
-    const int n = i % NPAD, d = row % a.D;
+    const int n = position_state((int)(i % NPAD), a.il), d = row % a.D;   // the state this slot of the record holds
     const float A2 = n < a.N ? a.A[(long)d * a.NS + n] * LOG2E : 0.0f;
     // complex state: slots (n, n^1) are (re, im) of one state; the thread carries both parts
     // and writes its own (slot n even: real part)
@@ -923,9 +925,10 @@ __global__ void copy_state_kernel(const float* __restrict__ src, float* __restri
 
 // Wave-packed copy of the selective B and C for the forward kernels (layout: FwdArgs::bcs).
 // A thread writes the four steps of one (batch entry, state, group of steps, B or C).
+// deal: a last group of fewer than 16 states is dealt out to the waves in turn (FwdArgs::il).
 template <typename T>
 __global__ void stage_bc_kernel(const T* __restrict__ Bm, const T* __restrict__ Cm, long bstride, T* __restrict__ dst,
-                                int B, int NS, int L, int Lp)
+                                int B, int NS, int L, int Lp, int deal)
 {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const int tgroups = Lp / GROUP_T, sgroups = (NS + NPAD - 1) / NPAD * NWAVES;   // every wave of every pass has a piece
@@ -935,7 +938,8 @@ __global__ void stage_bc_kernel(const T* __restrict__ Bm, const T* __restrict__ 
     const int tg = (int)(piece % tgroups);
     const int sg = (int)((piece / tgroups) % sgroups);
     const int b = (int)(piece / ((long)tgroups * sgroups));
-    const int n = sg * STATES_PER_LANE + (r % STATES_PER_LANE), t = tg * GROUP_T;
+    const int grp = sg / NWAVES;
+    const int n = grp * NPAD + slot_state(sg % NWAVES, r % STATES_PER_LANE, deal && NS - grp * NPAD < NPAD), t = tg * GROUP_T;
     const T* src = (r >= STATES_PER_LANE ? Cm : Bm) + (long)b * bstride + (long)n * L + t;
     T v[GROUP_T];
 #pragma unroll
@@ -950,14 +954,16 @@ __global__ void stage_bc_kernel(const T* __restrict__ Bm, const T* __restrict__ 
 
 int launch_stage_bc(const FwdArgs& a, void* bcs, int io_dtype, hipStream_t stream)
 {
+    // a carries all NS states here; whether a partial last group is dealt out depends on the path alone
+    const int deal = a.vec_ok && !(a.flags & (F_EXACT_ZOH_B | F_B_FIXED | F_C_FIXED | F_COMPLEX));
     const long n = (long)a.B * ((a.NS + NPAD - 1) / NPAD * NWAVES) * (a.Lp / GROUP_T) * 2 * STATES_PER_LANE;
     const dim3 grid((unsigned)((n + 255) / 256));
     if (io_dtype == 0)
         stage_bc_kernel<float><<<grid, dim3(256), 0, stream>>>(static_cast<const float*>(a.Bm), static_cast<const float*>(a.Cm),
-                                                               a.bc_bstride, static_cast<float*>(bcs), a.B, a.NS, a.L, a.Lp);
+                                                               a.bc_bstride, static_cast<float*>(bcs), a.B, a.NS, a.L, a.Lp, deal);
     else
         stage_bc_kernel<bf16_t><<<grid, dim3(256), 0, stream>>>(static_cast<const bf16_t*>(a.Bm), static_cast<const bf16_t*>(a.Cm),
-                                                                a.bc_bstride, static_cast<bf16_t*>(bcs), a.B, a.NS, a.L, a.Lp);
+                                                                a.bc_bstride, static_cast<bf16_t*>(bcs), a.B, a.NS, a.L, a.Lp, deal);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -982,6 +988,33 @@ static void launch_fwd_complex(const FwdArgs& a, hipStream_t stream)
     scan_fwd_kernel<T, VEC, FULLN, false, false, BCFIX, true><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
 }
 
+// real state, selective B and C
+template <typename T, bool VEC, bool FULLN, bool ZOH, int SPL>
+static void launch_fwd_selective(const FwdArgs& a, hipStream_t stream)
+{
+    const int groups = (a.D + ROWS - 1) / ROWS;
+    const dim3 block(THREADS);
+    if (a.nseg > 1) {
+        // a split needs the caller's scratch, which holds the staged copy as well
+        scan_fwd_kernel<T, VEC, FULLN, true, ZOH, 0, false, true, 0, SPL><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
+        const long n = (long)a.B * a.D * NPAD;
+        carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    }
+    if constexpr (sizeof(T) == 2 && VEC && !ZOH && SPL == STATES_PER_LANE) {
+        if (a.W_dt) {   // the caller has checked: unsplit, repacked B / C present, R <= 256
+            if (a.Rp <= 128)
+                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 4><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
+            else
+                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 8><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
+            return;
+        }
+    }
+    if (a.bcs)
+        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 0, SPL><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+    else
+        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, false, 0, SPL><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+}
+
 template <typename T, bool VEC, bool FULLN, bool ZOH>
 static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
 {
@@ -1000,25 +1033,12 @@ static void launch_fwd_t(const FwdArgs& a, hipStream_t stream)
     if (bcfix == 1) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 1>(a, stream);
     if (bcfix == 2) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 2>(a, stream);
     if (bcfix == 3) return launch_fwd_fixed<T, VEC, FULLN, ZOH, 3>(a, stream);
-    if (a.nseg > 1) {
-        // a split needs the caller's scratch, which holds the staged copy as well
-        scan_fwd_kernel<T, VEC, FULLN, true, ZOH, 0, false, true><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
-        const long n = (long)a.B * a.D * NPAD;
-        carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
+    if constexpr (VEC && !FULLN && !ZOH) {   // fewer than 16 states dealt out to the waves: kernels built for 1 or 2 slots per lane
+        const int spl = slots_for(a.N, a.il);
+        if (spl == 1) return launch_fwd_selective<T, VEC, FULLN, ZOH, 1>(a, stream);
+        if (spl == 2) return launch_fwd_selective<T, VEC, FULLN, ZOH, 2>(a, stream);
     }
-    if constexpr (sizeof(T) == 2 && VEC && !ZOH) {
-        if (a.W_dt) {   // the caller has checked: unsplit, repacked B / C present, R <= 256
-            if (a.Rp <= 128)
-                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 4><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
-            else
-                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 8><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
-            return;
-        }
-    }
-    if (a.bcs)
-        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
-    else
-        scan_fwd_kernel<T, VEC, FULLN, false, ZOH><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+    launch_fwd_selective<T, VEC, FULLN, ZOH, STATES_PER_LANE>(a, stream);
 }
 
 int launch_fwd(const FwdArgs& a, int io_dtype, hipStream_t stream)

@@ -26,6 +26,12 @@ struct FwdArgs {
     // pointers (A, h0, h_last, Bm, Cm and the gradients) already point at the group's first state.
     int NS;
     int acc_y;  // forward: this group's C*h is added to the y an earlier group left in ysave (or in out)
+    // Fewer than 16 states on the common path (real state, first-order B-bar, selective B / C, L % 8 == 0):
+    // the states are dealt out to the waves in turn -- slot k of wave w is state 4k + w instead of
+    // 4w + k -- so that every wave (every SIMD) carries its share and the kernels can be built for
+    // ceil(N / 4) slots per lane; the cost then follows the state size (Table 10).  The 16-float records of
+    // the workspace (checkpoints, segment states and carries, dA partials) stay in slot order 4w + k.
+    int il;
     uint32_t flags;
     int vec_ok;  // L % 8 == 0: every row starts 16-byte aligned and 8-step slices are whole or empty
     const void *u, *delta, *z, *Bm, *Cm;
