@@ -283,8 +283,10 @@ static int scan_fwd_impl(const ss_fwd_params* p, long bc_bstride, const void* W_
     char* ws = static_cast<char*>(p->workspace);
     const int groups = p->seqlen == 0 ? 1 : (slots(p) + 15) / 16;
     size_t ckpt_group = 0;
+    // the repacked copy serves the scalar path only: sequences of whole 16-byte pieces stage B and C through LDS instead
     auto stage = [&](const WsLayout& w) {
         a.Lp = w.Lp;
+        if (a.vec_ok) return true;
         if (ss::launch_stage_bc(a, ws + w.bcs_off, p->io_dtype, static_cast<hipStream_t>(stream)) != 0) return false;
         a.bcs = ws + w.bcs_off;
         return true;

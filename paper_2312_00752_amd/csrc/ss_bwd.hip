@@ -509,8 +509,6 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
 // All (B,D,L) tensors are addressed through per-workgroup buffer resources with ONE per-thread
 // offset (they share the layout), B and C through one resource per batch entry: no 64-bit pointer
 // registers, and an out-of-range offset switches a load (zeros) or a store off without a branch.
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
 struct BwdSmemDpp {
     float dt[ROWS][BPAD];
     float du[ROWS][BPAD];
@@ -522,66 +520,6 @@ struct BwdSmemDpp {
     float bcp[2][BT / GROUP_T][NPAD][GROUP_T];   // B (0) and C (1) of the block
 };
 
-// The input term of Eq. 2a for a lane's SPL states: bu[k] = B_k * du, with Bq holding B of the
-// wave's states in every group of four lanes (slot k in lane k).  Written out for the same
-// reason as adjoint_step_dpp, with the same leading wait state.
-#define SS_QP(k) " quad_perm:[" #k "," #k "," #k "," #k "] row_mask:0xf bank_mask:0xf"
-template <int SPL>
-__device__ __forceinline__ void input_step_dpp(float (&bu)[STATES_PER_LANE], float Bq, float du)
-{
-    if constexpr (SPL == 4)
-        asm("s_nop 1\n\t"
-            "v_mul_f32_dpp %0, %4, %5" SS_QP(0) "\n\t"
-            "v_mul_f32_dpp %1, %4, %5" SS_QP(1) "\n\t"
-            "v_mul_f32_dpp %2, %4, %5" SS_QP(2) "\n\t"
-            "v_mul_f32_dpp %3, %4, %5" SS_QP(3)
-            : "=&v"(bu[0]), "=&v"(bu[1]), "=&v"(bu[2]), "=&v"(bu[3]) : "v"(Bq), "v"(du));
-    else if constexpr (SPL == 2)
-        asm("s_nop 1\n\t"
-            "v_mul_f32_dpp %0, %2, %3" SS_QP(0) "\n\t"
-            "v_mul_f32_dpp %1, %2, %3" SS_QP(1)
-            : "=&v"(bu[0]), "=&v"(bu[1]) : "v"(Bq), "v"(du));
-    else
-        asm("s_nop 1\n\t"
-            "v_mul_f32_dpp %0, %1, %2" SS_QP(0)
-            : "=&v"(bu[0]) : "v"(Bq), "v"(du));
-}
-
-// One step of the adjoint recurrence for a lane's SPL states.  On entry g[k] = abar+ g+ of slot k;
-// Cq / Bq hold C / B of the wave's states in every group of four lanes (slot k in lane k).
-//     g[k] += C_k dy            (the gradient reaching h_t)          sb = sum_k B_k g[k]
-// The leading wait state covers a DPP operand the compiler might have copied with a vector move
-// just before (a DPP read needs two wait states after a vector write of the same register).
-template <int SPL>
-__device__ __forceinline__ void adjoint_step_dpp(f32x4_t& g, float& sb, float Cq, float Bq, float dy)
-{
-    float g0 = g[0], g1 = g[1], g2 = g[2], g3 = g[3];
-    if constexpr (SPL == 4)
-        asm("s_nop 1\n\t"
-            "v_fmac_f32_dpp %0, %5, %7" SS_QP(0) "\n\t"
-            "v_fmac_f32_dpp %1, %5, %7" SS_QP(1) "\n\t"
-            "v_fmac_f32_dpp %2, %5, %7" SS_QP(2) "\n\t"
-            "v_fmac_f32_dpp %3, %5, %7" SS_QP(3) "\n\t"
-            "v_mul_f32_dpp %4, %6, %0" SS_QP(0) "\n\t"
-            "v_fmac_f32_dpp %4, %6, %1" SS_QP(1) "\n\t"
-            "v_fmac_f32_dpp %4, %6, %2" SS_QP(2) "\n\t"
-            "v_fmac_f32_dpp %4, %6, %3" SS_QP(3)
-            : "+v"(g0), "+v"(g1), "+v"(g2), "+v"(g3), "=&v"(sb) : "v"(Cq), "v"(Bq), "v"(dy));
-    else if constexpr (SPL == 2)
-        asm("s_nop 1\n\t"
-            "v_fmac_f32_dpp %0, %3, %5" SS_QP(0) "\n\t"
-            "v_fmac_f32_dpp %1, %3, %5" SS_QP(1) "\n\t"
-            "v_mul_f32_dpp %2, %4, %0" SS_QP(0) "\n\t"
-            "v_fmac_f32_dpp %2, %4, %1" SS_QP(1)
-            : "+v"(g0), "+v"(g1), "=&v"(sb) : "v"(Cq), "v"(Bq), "v"(dy));
-    else
-        asm("s_nop 1\n\t"
-            "v_fmac_f32_dpp %0, %2, %4" SS_QP(0) "\n\t"
-            "v_mul_f32_dpp %1, %3, %0" SS_QP(0)
-            : "+v"(g0), "=&v"(sb) : "v"(Cq), "v"(Bq), "v"(dy));
-    g[0] = g0; g[1] = g1; g[2] = g2; g[3] = g3;
-}
-#undef SS_QP
 
 // SPL: slots per lane the state phases are built for (see scan_fwd_kernel).
 template <typename T, int SPL>

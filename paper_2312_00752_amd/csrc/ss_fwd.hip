@@ -1,12 +1,13 @@
 // Forward selective scan (Algorithm 2 steps 5-6, fused as in Appendix D "Speed") and the
 // single-token recurrent step (Section 2, Eq. 2a/2b applied once).
+#include <type_traits>
+
 #include "ss_kernels.h"
 #include "ss_device.h"
 
 namespace ss {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));   // MFMA operand and accumulator types
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 // One workgroup = 64 rows x 4 waves.  Per chunk of CHUNK_T steps:
 //   A. (pointwise view) load 64 rows x 32 steps of u, delta, z with 16-byte accesses, form
@@ -43,10 +44,21 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 // kernel and the write and read of a (B,D,L) tensor.
 // SPL: slots per lane the recurrence is built for (4, or ceil(N / 4) rounded up to 1 or 2 when the
 // states are dealt out to the waves in turn, FwdArgs::il).
+// PAT (VEC, real state, selective B and C): B and C take neither scalar path.  The chunk's B and C are
+// requested with the chunk's u, delta and z by ordinary buffer loads (thread -> B or C, state, group
+// of four steps), widened to float and put into an LDS tile [group][state][step]; lane l of wave w
+// reads, per group, one float4 with the state of slot l % 4 at the group's four steps, and the
+// recurrence takes a state's value from that register as a quad-broadcast DPP operand
+// (input_step_dpp, readout_step_dpp).  No scalar loads or their waits (which also drain LDS reads and
+// vice versa), no repacking pass, no touching of cache lines ahead, and no vector-memory wait that
+// has to cover the previous chunk's stores.
 template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false,
-          int FUSED_KS = 0, int SPL = STATES_PER_LANE>
+          int FUSED_KS = 0, int SPL = STATES_PER_LANE, bool PAT = false>
 __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
 {
+    static_assert(!PAT || (VEC && BCFIX == 0 && !CPLX && !STAGED), "PAT: vector path, real state, selective B and C");
+    constexpr int NGC = CHUNK_T / GROUP_T;
+    __shared__ __attribute__((aligned(16))) float s_bc[PAT ? 2 : 1][PAT ? NGC : 1][PAT ? NPAD : 1][GROUP_T];   // PAT: B (0) and C (1) of the chunk
     __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
     __shared__ __attribute__((aligned(16))) float s_du[ROWS][TPAD];
     __shared__ __attribute__((aligned(16))) float s_yp[NWAVES][ROWS][TPAD];
@@ -93,6 +105,16 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
     const rsrc_t bz = make_rsrc(static_cast<const T*>(has_z ? a.z : a.u) + wg_first, has_z ? wg_bytes : 0u);
     const rsrc_t bo = make_rsrc(static_cast<T*>(AGG ? const_cast<void*>(a.u) : a.out) + wg_first, AGG ? 0u : wg_bytes);
     const rsrc_t by = make_rsrc(static_cast<T*>(keep_y ? a.ysave : const_cast<void*>(a.u)) + wg_first, keep_y ? wg_bytes : 0u);
+    // what the earlier state groups left (more than 16 states): prefetched like an input, so that no wait in the loop has to drain the memory pipeline
+    const bool acc_on = !AGG && a.acc_y;
+    const rsrc_t bp = make_rsrc(static_cast<const T*>(acc_on ? (has_z ? a.ysave : a.out) : a.u) + wg_first, acc_on ? wg_bytes : 0u);
+    // PAT staging view: waves 0, 1 stage B, waves 2, 3 stage C (not needed for the aggregates);
+    // thread -> (state s_n, group of four steps s_tq) of the chunk
+    const int s_which = w >> 1, s_n = (tid >> 3) & (NPAD - 1), s_tq = tid & (NGC - 1);
+    const bool s_on = PAT && !(AGG && s_which == 1);
+    const rsrc_t bbc = make_rsrc(static_cast<const T*>(s_which ? a.Cm : a.Bm) + (long)b * a.bc_bstride,
+                                 s_on ? (uint32_t)N * (uint32_t)L * (uint32_t)sizeof(T) : 0u);
+    const uint32_t bc_row_off = s_n < N ? (uint32_t)s_n * (uint32_t)L * (uint32_t)sizeof(T) : BUF_OFF;
 
     // ---- state view: lane -> row, wave -> states 4w..4w+3 -------------------------------
     const bool s_ok = d0 + lane < a.D;
@@ -162,19 +184,31 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             }
         }
     }
-    typename io8<T>::raw ru, rd, rz;
-    auto issue_loads = [&](int c) {
+    // u, delta and z are requested PF chunks ahead (slot = chunk index mod PF): the scan is not long
+    // enough to cover a memory round trip under load, and with one chunk in flight per workgroup
+    // the kernel ran at the pace of that latency whatever the state size.
+    constexpr int PF = VEC ? 2 : 1;
+    typename io8<T>::raw ru_[PF], rd_[PF], rz_[PF];
+    typename io4<T>::raw rbc_[PF];   // PAT: the thread's four steps of B or C
+    typename io8<T>::raw rp_[PF];    // VEC: the pre-gate y of the earlier state groups (zeros if there are none)
+    auto issue_loads = [&](int c, auto slot_tag) {   // chunk c into the slot given at compile time
+        constexpr int s = decltype(slot_tag)::value;
         const int t0 = c * CHUNK_T + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);
         if constexpr (VEC) {   // slices are whole or empty
-            const uint32_t off = nv == SLICE ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
-            ru = io8<T>::load_buf(bu, off);
-            if constexpr (FUSED_KS == 0) rd = io8<T>::load_buf(bd, off);
-            rz = io8<T>::load_buf(bz, off);
+            const uint32_t off = (nv == SLICE && c < c_end) ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
+            ru_[s] = io8<T>::load_buf(bu, off);
+            if constexpr (FUSED_KS == 0) rd_[s] = io8<T>::load_buf(bd, off);
+            rz_[s] = io8<T>::load_buf(bz, off);
+            rp_[s] = io8<T>::load_buf(bp, off);
+            if constexpr (PAT) {   // L % 8 == 0: a group of four steps is whole or past the end
+                const int ts = c * CHUNK_T + s_tq * GROUP_T;
+                rbc_[s] = io4<T>::load_buf(bbc, (ts < L && c < c_end) ? bc_row_off + (uint32_t)ts * (uint32_t)sizeof(T) : BUF_OFF);
+            }
         } else {
-            ru = io8<T>::template load<VEC>(gu + t0, nv);
-            rd = io8<T>::template load<VEC>(gdl + t0, nv);
-            if (has_z) rz = io8<T>::template load<VEC>(gz + t0, nv);
+            ru_[s] = io8<T>::template load<VEC>(gu + t0, nv);
+            rd_[s] = io8<T>::template load<VEC>(gdl + t0, nv);
+            if (has_z) rz_[s] = io8<T>::template load<VEC>(gz + t0, nv);
         }
     };
     // FUSED: delta_raw of a chunk from the fragments in registers: two 16 x 16 tiles per wave,
@@ -220,7 +254,8 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 if (rt_col + 8 * j < a.Rp) *reinterpret_cast<bf16x8_t*>(&s_rT[rt_t][rt_col + 8 * j]) = rld[j].v;
         }
     };
-    issue_loads(c_begin);
+    issue_loads(c_begin, std::integral_constant<int, 0>{});
+    if constexpr (PF > 1) issue_loads(c_begin + 1, std::integral_constant<int, 1>{});
     if constexpr (FUSED_KS > 0) {
         issue_r(c_begin);
         stage_r();
@@ -230,14 +265,27 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         issue_r(c_begin + 1);
     }
     uint32_t touched = 0u;
-    if (BCFIX != 3) touched = touch(c_begin * CHUNK_T);
+    if (BCFIX != 3 && !PAT) touched = touch(c_begin * CHUNK_T);
 
-    for (int c = c_begin; c < c_end; ++c) {
+    // One chunk; the slot of its prefetched inputs (chunk index from c_begin, mod PF) is a compile-time
+    // constant, so the prefetch registers are addressed statically and the loads just issued are
+    // not touched again before their chunk comes up.
+    auto do_chunk = [&](const int c, auto slot_tag) {
+        constexpr int SLOT = decltype(slot_tag)::value;
         float u8[SLICE], z8[SLICE], v8[SLICE];
         const int tc = c * CHUNK_T;
         const int t0 = tc + pq * SLICE;
         const int nv = min(max(L - t0, 0), SLICE);
         // ---- A: pointwise pre-processing --------------------------------------------
+        const typename io8<T>::raw ru = ru_[SLOT], rd = rd_[SLOT], rz = rz_[SLOT];
+        const typename io4<T>::raw rbc = rbc_[SLOT];
+        float p8[SLICE];
+        if constexpr (VEC) io8<T>::unpack(rp_[SLOT], p8);
+        if constexpr (PAT) {
+            float bc4[GROUP_T];
+            io4<T>::unpack(rbc, bc4);
+            *reinterpret_cast<float4*>(&s_bc[s_which][s_tq][s_n][0]) = make_float4(bc4[0], bc4[1], bc4[2], bc4[3]);
+        }
         io8<T>::unpack(ru, u8);
         if constexpr (FUSED_KS > 0) {   // delta_raw of this chunk: left in s_raw by this same wave (project)
             const float4 d0v = *reinterpret_cast<const float4*>(&s_raw[pr][pq * SLICE]);
@@ -270,8 +318,10 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         // The touch of the next chunk's B and C goes here, after the wait for this chunk's u,
         // delta and z: the value touched a chunk ago is older than those and costs no wait of
         // its own.
-        consume_touch(touched);
-        if (BCFIX != 3) touched = touch((c + 1) * CHUNK_T);
+        if constexpr (!PAT) {
+            consume_touch(touched);
+            if (BCFIX != 3) touched = touch((c + 1) * CHUNK_T);
+        }
         // checkpoint: the state entering every CKPT_T-step block (read back by the backward pass)
         auto save_ckpt = [&](int block) {
             if constexpr (AGG) return;
@@ -287,7 +337,7 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             }
         };
         save_ckpt(c * (CHUNK_T / CKPT_T));
-        if (c + 1 < c_end) issue_loads(c + 1);  // in flight during the scan below
+        if (VEC || c + PF < c_end) issue_loads(c + PF, slot_tag);  // in flight during the scans below (VEC: switched off past the end, not branched around)
         if constexpr (FUSED_KS > 0) {
             stage_r();          // r of chunk c + 1, requested a chunk ago; read by project() after the recurrence
             issue_r(c + 2);
@@ -301,7 +351,9 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         bcs_group<T> Sg[2 * FB];
         const T* __restrict__ const sbc_chunk = STAGED ? sbc + (long)(tc / GROUP_T) * STAGE_GROUP : nullptr;
         auto fetch_bc = [&](int g, int slot) {
-            if constexpr (STAGED) {
+            if constexpr (PAT) {
+                return;
+            } else if constexpr (STAGED) {
                 Sg[slot] = load_bcs<T>(sbc_chunk + g * STAGE_GROUP);
             } else {
 #pragma unroll
@@ -320,11 +372,16 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         // Scalar loads return out of order and share their counter with LDS reads, so a wait
         // for either drains both: the step sizes of the whole chunk are read from LDS before
         // the loop, and inside it only the scalar loads of the next group are outstanding.
-        float4 dtc[NG], duc[NG];
+        float4 dtc[NG], duc[NG], Bpc[PAT ? NG : 1], Cpc[PAT ? NG : 1];
+        const int pat = slot_state(w, lane & 3, a.il);   // PAT: the state of slot lane % 4
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             dtc[g] = *reinterpret_cast<const float4*>(&s_dt[lane][g * GROUP_T]);
             duc[g] = *reinterpret_cast<const float4*>(&s_du[lane][g * GROUP_T]);
+            if constexpr (PAT) {
+                Bpc[g] = *reinterpret_cast<const float4*>(&s_bc[0][g][pat][0]);
+                if (!AGG) Cpc[g] = *reinterpret_cast<const float4*>(&s_bc[1][g][pat][0]);
+            }
         }
         if constexpr (STAGED) {
 #pragma unroll
@@ -361,6 +418,16 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                             y = fmaf(-Cval(cur, k + 1, j), hi, y);
                         }
                     }
+                } else if constexpr (PAT) {
+                    float bu[STATES_PER_LANE];
+                    input_step_dpp<SPL>(bu, f4_get(Bpc[g], j), du);
+#pragma unroll
+                    for (int k = 0; k < SPL; ++k) {
+                        const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
+                        if (ZOH) bu[k] *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
+                        h[k] = fmaf(abar, h[k], bu[k]);                              // Eq. 2a
+                    }
+                    if (!AGG) readout_step_dpp<SPL>(y, f4_get(Cpc[g], j), h);        // Eq. 2b
                 } else {
 #pragma unroll
                     for (int k = 0; k < SPL; ++k) {
@@ -404,9 +471,11 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 y8[4] += p1.x; y8[5] += p1.y; y8[6] += p1.z; y8[7] += p1.w;
             }
             const int nvs = p_ok ? nv : 0;
-            if (a.acc_y) {  // states beyond the first 16: add to what the earlier groups left
+            if constexpr (VEC) {   // states beyond the first 16: add to what the earlier groups left (zeros otherwise)
+#pragma unroll
+                for (int j = 0; j < SLICE; ++j) y8[j] += p8[j];
+            } else if (a.acc_y) {
                 const T* prev = (has_z ? static_cast<const T*>(a.ysave) : static_cast<const T*>(a.out)) + prow * L + t0;
-                float p8[SLICE];
                 io8<T>::unpack(io8<T>::template load<VEC>(prev, nvs), p8);
 #pragma unroll
                 for (int j = 0; j < SLICE; ++j) y8[j] += p8[j];
@@ -431,6 +500,12 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
         }
         // no barrier needed here: the next phase A writes s_dt/s_du, which every wave has
         // finished reading (barrier above), and s_yp is rewritten only after the next barrier
+    };
+    for (int c = c_begin; c < c_end; c += PF) {
+        do_chunk(c, std::integral_constant<int, 0>{});
+        if constexpr (PF > 1) {
+            if (c + 1 < c_end) do_chunk(c + 1, std::integral_constant<int, 1>{});
+        }
     }
 
     if (AGG) {
@@ -994,25 +1069,28 @@ static void launch_fwd_selective(const FwdArgs& a, hipStream_t stream)
 {
     const int groups = (a.D + ROWS - 1) / ROWS;
     const dim3 block(THREADS);
+    constexpr bool PAT = VEC;          // B and C through the LDS tile; otherwise the scalar path (repacked copy if there is one)
     if (a.nseg > 1) {
-        // a split needs the caller's scratch, which holds the staged copy as well
-        scan_fwd_kernel<T, VEC, FULLN, true, ZOH, 0, false, true, 0, SPL><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
+        if (PAT || a.bcs)
+            scan_fwd_kernel<T, VEC, FULLN, true, ZOH, 0, false, !PAT, 0, SPL, PAT><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
+        else
+            scan_fwd_kernel<T, VEC, FULLN, true, ZOH, 0, false, false, 0, SPL, false><<<dim3((unsigned)(a.B * groups), (unsigned)(a.nseg - 1)), block, 0, stream>>>(a);
         const long n = (long)a.B * a.D * NPAD;
         carry_fwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
     }
     if constexpr (sizeof(T) == 2 && VEC && !ZOH && SPL == STATES_PER_LANE) {
-        if (a.W_dt) {   // the caller has checked: unsplit, repacked B / C present, R <= 256
+        if (a.W_dt) {   // the caller has checked: unsplit, R <= 256
             if (a.Rp <= 128)
-                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 4><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
+                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, false, 4, SPL, true><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
             else
-                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 8><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
+                scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, false, 8, SPL, true><<<dim3((unsigned)(a.B * groups), 1u), block, 0, stream>>>(a);
             return;
         }
     }
-    if (a.bcs)
-        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, true, 0, SPL><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+    if (PAT || a.bcs)
+        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, !PAT, 0, SPL, PAT><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
     else
-        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, false, 0, SPL><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
+        scan_fwd_kernel<T, VEC, FULLN, false, ZOH, 0, false, false, 0, SPL, false><<<dim3((unsigned)(a.B * groups), (unsigned)a.nseg), block, 0, stream>>>(a);
 }
 
 template <typename T, bool VEC, bool FULLN, bool ZOH>
