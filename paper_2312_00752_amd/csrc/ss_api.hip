@@ -38,12 +38,14 @@ struct SegPlan {
 // Modelled duration (in steps of one unsplit workgroup running alone on its compute unit) of a
 // launch of n equal workgroups of len steps each.  Two workgroups fit a compute unit and then
 // each runs at about 3/4 of the speed it has alone (measured: 256 workgroups of 2048 steps
-// take 1.01 ms, 512 take 1.35 ms), so the chip takes workgroups in rounds of 512.
+// take 1.01 ms, 512 take 1.35 ms), so the chip takes workgroups in rounds of 512.  A workgroup's
+// set-up, pipeline fill and final stores cost about as much as 32 more steps (fitted to sweeps of
+// the segment count at 160 x 16384, 192 x 2048 and 4 x 2^20 workgroups x steps).
 double launch_cost(long n, long len)
 {
-    const double pair = 1.0 / 0.75;
+    const double pair = 1.0 / 0.75, fixed = 32.0;
     const long full = n / 512, rest = n % 512;
-    return (double)len * ((double)full * pair + (rest == 0 ? 0.0 : (rest <= 256 ? 1.0 : pair)));
+    return ((double)len + fixed) * ((double)full * pair + (rest == 0 ? 0.0 : (rest <= 256 ? 1.0 : pair)));
 }
 
 long segment_length(int L, long nseg)
@@ -67,21 +69,19 @@ SegPlan plan_segments(int B, int D, int L, uint32_t flags)
     if (L < 128) return s;
     // Pick the number of segments that the model says finishes first: the main pass over
     // wgs * nseg workgroups plus the aggregate pass over wgs * (nseg - 1) of them, which costs
-    // about 0.31 of a main pass per step (measured over forward + backward).  Segments stay
-    // at least 64 steps long (two forward chunks).
+    // about 0.36 of a main pass per step (measured over forward + backward).  Segments stay
+    // at least 64 steps long (two forward chunks), and a launch within 8192 workgroups, which
+    // bounds the aggregates' workspace.
     double best = launch_cost(wgs, s.seg_len);
     long best_n = 1;
-    // ... and the launch stays within four rounds (2048 workgroups): the model has no term for a
-    // workgroup's fixed cost and would otherwise prefer thousands of 128-step segments on a very
-    // long sequence (measured at B = 1, D = 1024, L = 2^18: 2048 segments 8.4 ms, 31 segments 7.7 ms).
-    const long fit = 2048 / wgs > 2 ? 2048 / wgs : 2;
+    const long fit = 8192 / wgs > 2 ? 8192 / wgs : 2;
     const long longest = L / 64 < 4096 ? L / 64 : 4096;
     const long most = longest < fit ? longest : fit;
     for (long want = 2; want <= most; ++want) {
         const long len = segment_length(L, want);
         const long n = (L + len - 1) / len;   // what that length really gives
         if (n < 2) continue;
-        const double c = launch_cost(wgs * n, len) + 0.31 * launch_cost(wgs * (n - 1), len);
+        const double c = launch_cost(wgs * n, len) + 0.36 * launch_cost(wgs * (n - 1), len);
         if (c < best * 0.97) { best = c; best_n = want; }   // more segments only for a clear gain
     }
     if (best_n > 1) {

@@ -955,6 +955,137 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
     }
 }
 
+// The adjoint aggregate on the common path (real state, selective C, L % 8 == 0): as
+// adjoint_agg_kernel, with the chunk's C staged through an LDS tile and taken as a quad-broadcast
+// DPP operand (see scan_bwd_dpp_kernel), buffer-addressed inputs requested two chunks ahead into
+// compile-time slots, and no scalar loads.
+template <typename T, int SPL>
+__global__ void __launch_bounds__(THREADS) adjoint_agg_dpp_kernel(const BwdArgs a)
+{
+    constexpr int NGC = CHUNK_T / GROUP_T;
+    __shared__ __attribute__((aligned(16))) float s_dt[ROWS][TPAD];
+    __shared__ __attribute__((aligned(16))) float s_dy[ROWS][TPAD];
+    __shared__ __attribute__((aligned(16))) float s_c[NGC][NPAD][GROUP_T];   // C of the chunk: [group][state][step]
+    const FwdArgs& f = a.f;
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & (WAVE - 1);
+    const int groups = (f.D + ROWS - 1) / ROWS;
+    const unsigned bx = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int b = bx / groups;
+    const int d0 = (bx % groups) * ROWS;
+    const int L = f.L, N = f.N, NS = f.NS;
+    const bool has_z = f.flags & F_HAS_Z, softplus = f.flags & F_DELTA_SOFTPLUS;
+    const int seg = blockIdx.y + 1;  // segment 0 passes nothing on
+    const int c_begin = seg * (f.seg_len / CHUNK_T);
+    const int c_end = min((L + CHUNK_T - 1) / CHUNK_T, (seg + 1) * (f.seg_len / CHUNK_T));
+
+    const int pr = tid >> 2, pq = tid & 3;
+    const bool p_ok = d0 + pr < f.D;
+    const int pd = p_ok ? d0 + pr : f.D - 1;
+    const float bias = (f.flags & F_HAS_DELTA_BIAS) ? f.bias[pd] : 0.0f;
+    const int rows_here = min(ROWS, f.D - d0);
+    const long wg_first = ((long)b * f.D + d0) * L;
+    const uint32_t wg_bytes = (uint32_t)rows_here * (uint32_t)L * (uint32_t)sizeof(T);
+    const uint32_t row_off = (uint32_t)pr * (uint32_t)L * (uint32_t)sizeof(T);   // past the resource for rows past D
+    const rsrc_t bd_ = make_rsrc(static_cast<const T*>(f.delta) + wg_first, wg_bytes);
+    const rsrc_t bo_ = make_rsrc(static_cast<const T*>(a.dout) + wg_first, wg_bytes);
+    const rsrc_t bz_ = make_rsrc(static_cast<const T*>(has_z ? f.z : f.delta) + wg_first, has_z ? wg_bytes : 0u);
+    // staging view: waves 0, 1 stage C of the chunk; thread -> (state s_n, group of four steps s_tq)
+    const int s_n = (tid >> 3) & (NPAD - 1), s_tq = tid & (NGC - 1);
+    const rsrc_t bc_ = make_rsrc(static_cast<const T*>(f.Cm) + (long)b * f.bc_bstride,
+                                 w < 2 ? (uint32_t)N * (uint32_t)L * (uint32_t)sizeof(T) : 0u);
+    const uint32_t c_row_off = s_n < N ? (uint32_t)s_n * (uint32_t)L * (uint32_t)sizeof(T) : BUF_OFF;
+
+    const bool s_ok = d0 + lane < f.D;
+    const int sd = s_ok ? d0 + lane : f.D - 1;
+    const long srow = (long)b * f.D + sd;
+    float A2[STATES_PER_LANE], ag[STATES_PER_LANE];
+#pragma unroll
+    for (int k = 0; k < STATES_PER_LANE; ++k) {
+        const int n = slot_state(w, k, f.il);
+        const bool ok = n < N && k < SPL;
+        A2[k] = (ok ? f.A[(long)sd * NS + n] : 0.0f) * LOG2E;
+        ag[k] = (seg == f.nseg - 1 && ok && a.dh_last) ? a.dh_last[srow * NS + n] : 0.0f;
+    }
+    const int pat = slot_state(w, lane & 3, f.il);
+
+    constexpr int PF = 2;
+    typename io8<T>::raw rd_[PF], rz_[PF], ro_[PF];
+    typename io4<T>::raw rc_[PF];
+    auto issue_loads = [&](int c, auto slot_tag) {   // chunk c (walking down from c_end - 1) into a compile-time slot
+        constexpr int s = decltype(slot_tag)::value;
+        const int t0 = c * CHUNK_T + pq * SLICE;
+        const uint32_t off = (t0 < L && c >= c_begin) ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;   // slices are whole or empty
+        rd_[s] = io8<T>::load_buf(bd_, off);
+        ro_[s] = io8<T>::load_buf(bo_, off);
+        rz_[s] = io8<T>::load_buf(bz_, off);
+        const int ts = c * CHUNK_T + s_tq * GROUP_T;
+        rc_[s] = io4<T>::load_buf(bc_, (ts < L && c >= c_begin) ? c_row_off + (uint32_t)ts * (uint32_t)sizeof(T) : BUF_OFF);
+    };
+    issue_loads(c_end - 1, std::integral_constant<int, 0>{});
+    issue_loads(c_end - 2, std::integral_constant<int, 1>{});
+
+    auto do_chunk = [&](const int c, auto slot_tag) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        const int t0 = c * CHUNK_T + pq * SLICE;
+        const bool live = p_ok && t0 < L;
+        {
+            float v8[SLICE], o8[SLICE], z8[SLICE], dt8[SLICE], c4[GROUP_T];
+            io8<T>::unpack(rd_[SLOT], v8);
+            io8<T>::unpack(ro_[SLOT], o8);
+            if (has_z) io8<T>::unpack(rz_[SLOT], z8);
+            io4<T>::unpack(rc_[SLOT], c4);
+            const float bias_eff = live ? bias : (softplus ? -1e30f : 0.0f);   // an empty slice runs with dt = 0
+#pragma unroll
+            for (int j = 0; j < SLICE; ++j) {
+                const float x = v8[j] + bias_eff;
+                float sp, sg;
+                if (softplus) softplus_sigmoid(x, sp, sg); else sp = x;
+                dt8[j] = sp;
+                if (has_z) o8[j] *= z8[j] * sigmoid_fast(z8[j]);
+            }
+            float4* pd4 = reinterpret_cast<float4*>(&s_dt[pr][pq * SLICE]);
+            float4* py4 = reinterpret_cast<float4*>(&s_dy[pr][pq * SLICE]);
+            pd4[0] = make_float4(dt8[0], dt8[1], dt8[2], dt8[3]);
+            pd4[1] = make_float4(dt8[4], dt8[5], dt8[6], dt8[7]);
+            py4[0] = make_float4(o8[0], o8[1], o8[2], o8[3]);
+            py4[1] = make_float4(o8[4], o8[5], o8[6], o8[7]);
+            if (w < 2) *reinterpret_cast<float4*>(&s_c[s_tq][s_n][0]) = make_float4(c4[0], c4[1], c4[2], c4[3]);
+        }
+        issue_loads(c - PF, slot_tag);
+        __syncthreads();
+        __builtin_amdgcn_s_setprio(2);   // as in scan_bwd_kernel: the recurrence at a raised wave priority
+        float4 dtc[NGC], dyc[NGC], Cpc[NGC];
+#pragma unroll
+        for (int g = 0; g < NGC; ++g) {
+            dtc[g] = *reinterpret_cast<const float4*>(&s_dt[lane][g * GROUP_T]);
+            dyc[g] = *reinterpret_cast<const float4*>(&s_dy[lane][g * GROUP_T]);
+            Cpc[g] = *reinterpret_cast<const float4*>(&s_c[g][pat][0]);
+        }
+#pragma unroll
+        for (int g = NGC - 1; g >= 0; --g) {
+#pragma unroll
+            for (int j = GROUP_T - 1; j >= 0; --j) {
+                const float dt = f4_get(dtc[g], j), dy = f4_get(dyc[g], j);
+                adjoint_input_dpp<SPL>(ag, f4_get(Cpc[g], j), dy);          // g = C dy + abar+ g+
+#pragma unroll
+                for (int k = 0; k < SPL; ++k) ag[k] *= exp2_fast(dt * A2[k]);   // flows on to h_{t-1}
+            }
+        }
+        __builtin_amdgcn_s_setprio(0);
+        __syncthreads();
+    };
+    for (int c = c_end - 1; c >= c_begin; c -= PF) {
+        do_chunk(c, std::integral_constant<int, 0>{});
+        if (c - 1 >= c_begin) do_chunk(c - 1, std::integral_constant<int, 1>{});
+    }
+    if (s_ok) {
+        float4* dst = reinterpret_cast<float4*>(a.seg_g + ((long)seg * f.B * f.D + srow) * NPAD) + w;
+        *dst = make_float4(ag[0], ag[1], ag[2], ag[3]);
+    }
+}
+
 // Turns the segments' local adjoint carries into incoming ones, in place, walking the
 // segments backwards: in[nseg-2] = loc[nseg-1];  in[s-1] = exp(A * sum_dt[s]) * in[s] + loc[s].
 __global__ void carry_bwd_kernel(const BwdArgs a)
@@ -1096,7 +1227,7 @@ template <typename T, bool FULLN, int SPL>
 static int launch_scan_bwd_dpp(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
     if (a.f.nseg > 1) {
-        adjoint_agg_kernel<T, true, FULLN, false, SPL><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
+        adjoint_agg_dpp_kernel<T, SPL><<<dim3(grid.x, (unsigned)(a.f.nseg - 1)), dim3(THREADS), 0, stream>>>(a);
         const long n = (long)a.f.B * a.f.D * NPAD;
         carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
     }

@@ -585,6 +585,28 @@ __device__ __forceinline__ void adjoint_step_dpp(f32x4_t& g, float& sb, float Cq
             : "+v"(g0), "=&v"(sb) : "v"(Cq), "v"(Bq), "v"(dy));
     g[0] = g0; g[1] = g1; g[2] = g2; g[3] = g3;
 }
+// The first half of adjoint_step_dpp alone (for the adjoint aggregate of a segment): g[k] += C_k dy.
+template <int SPL>
+__device__ __forceinline__ void adjoint_input_dpp(float (&g)[STATES_PER_LANE], float Cq, float dy)
+{
+    if constexpr (SPL == 4)
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %4, %5" SS_QP(0) "\n\t"
+            "v_fmac_f32_dpp %1, %4, %5" SS_QP(1) "\n\t"
+            "v_fmac_f32_dpp %2, %4, %5" SS_QP(2) "\n\t"
+            "v_fmac_f32_dpp %3, %4, %5" SS_QP(3)
+            : "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]) : "v"(Cq), "v"(dy));
+    else if constexpr (SPL == 2)
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %2, %3" SS_QP(0) "\n\t"
+            "v_fmac_f32_dpp %1, %2, %3" SS_QP(1)
+            : "+v"(g[0]), "+v"(g[1]) : "v"(Cq), "v"(dy));
+    else
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %1, %2" SS_QP(0)
+            : "+v"(g[0]) : "v"(Cq), "v"(dy));
+}
+
 // The read-out of Eq. 2b for a lane's SPL states: y = sum_k C_k h[k], Cq holding C like Bq above.
 template <int SPL>
 __device__ __forceinline__ void readout_step_dpp(float& y, float Cq, const float (&h)[STATES_PER_LANE])

@@ -104,7 +104,7 @@ def test_workspace_size_formula():
     assert B.ss_workspace_bytes(8, 2048, 2048, 16, for_backward=False) > staged(8, 2048, 16)   # one row tile per compute unit: split
     assert B.ss_workspace_bytes(1, 1024, 1024, 16, for_backward=False) > staged(1, 1024, 16)   # few row tiles: split even when short
     assert B.ss_workspace_bytes(1, 256, 96, 16, for_backward=False) == staged(1, 96, 16)       # too short to split
-    # a very long sequence is not cut into thousands of short segments: at most 2048 workgroups per launch
+    # a very long sequence is not cut into thousands of short segments: each workgroup has a fixed cost
     split = B.ss_workspace_bytes(1, 1024, 1 << 18, 16, for_backward=False) - staged(1, 1 << 18, 16)
     assert 0 < split <= 128 * 1024 * 17 * 4 + 512
 
