@@ -29,7 +29,7 @@ inline int slots(const ss_step_params* p) { return p->dstate * ((p->flags & SS_C
 
 // Split of the sequence across workgroups.  The scan kernels run one workgroup per 64 rows
 // of a batch entry; when that fills the chip badly and the sequence is long, L is cut into
-// segments (multiples of 32 steps) that are scanned
+// segments (multiples of 64 steps) that are scanned
 // concurrently and stitched with a carry pass (Appendix D: the scan continues from the
 // state the previous chunk ended in; here the chunks run in parallel from aggregates).
 struct SegPlan {
@@ -50,13 +50,15 @@ double launch_cost(long n, long len)
 
 long segment_length(int L, long nseg)
 {
-    long len = ((L + nseg - 1) / nseg + 31) / 32 * 32;
+    // whole pairs of 32-step chunks: the forward kernel issues the traffic of an even chunk and the
+    // odd one after it together
+    long len = ((L + nseg - 1) / nseg + 63) / 64 * 64;
     // A segment length that is a large power of two makes every workgroup walk the memory
-    // channels in lockstep (all segment starts alias); an odd multiple of 32 steps staggers them
+    // channels in lockstep (all segment starts alias); an odd multiple of 64 steps staggers them
     // (measured: 7-12 % on the 2^20-step workload).  Short segments are staggered only when
     // there are hundreds of them; otherwise the shorter last segment costs more than the
     // aliasing does (measured on 8K- and 64K-step sequences).
-    if (nseg > 1 && len % 256 == 0) len += len >= 2048 ? 160 : (nseg >= 256 ? 32 : 0);
+    if (nseg > 1 && len % 256 == 0) len += len >= 2048 ? 192 : (nseg >= 256 ? 64 : 0);
     return len;
 }
 

@@ -223,11 +223,18 @@ template <> struct io8<float> {
         r.b = make_float4(__uint_as_float(y.x), __uint_as_float(y.y), __uint_as_float(y.z), __uint_as_float(y.w));
         return r;
     }
-    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[8])
+    struct packed { uint4 a, b; };   // eight elements as stored
+    static __device__ __forceinline__ packed pack(const float (&v)[8])
     {
-        buf_store16(rs, off, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
-        buf_store16(rs, off + 16, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
+        return {make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])),
+                make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7]))};
     }
+    static __device__ __forceinline__ void store_packed(rsrc_t rs, uint32_t off, const packed& x)   // dropped if off is out of range
+    {
+        buf_store16(rs, off, x.a);
+        buf_store16(rs, off + 16, x.b);
+    }
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[8]) { store_packed(rs, off, pack(v)); }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[8])
     {
         v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
@@ -273,10 +280,13 @@ template <> struct io8<bf16_t> {
         r.w = buf_load16_once(rs, off);
         return r;
     }
-    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[8])
+    typedef uint4 packed;   // eight elements as stored
+    static __device__ __forceinline__ packed pack(const float (&v)[8])
     {
-        buf_store16(rs, off, make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])));
+        return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
     }
+    static __device__ __forceinline__ void store_packed(rsrc_t rs, uint32_t off, packed x) { buf_store16(rs, off, x); }   // dropped if off is out of range
+    static __device__ __forceinline__ void store_buf(rsrc_t rs, uint32_t off, const float (&v)[8]) { store_packed(rs, off, pack(v)); }
     static __device__ __forceinline__ void unpack(const raw& r, float (&v)[8])
     {
         v[0] = bf16_lo(r.w.x); v[1] = bf16_hi(r.w.x);

@@ -54,7 +54,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));   // MFMA operand a
 // has to cover the previous chunk's stores.
 template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false,
           int FUSED_KS = 0, int SPL = STATES_PER_LANE, bool PAT = false>
-__global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
+__global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS == 0) ? 2 : 1) scan_fwd_kernel(const FwdArgs a)
 {
     static_assert(!PAT || (VEC && BCFIX == 0 && !CPLX && !STAGED), "PAT: vector path, real state, selective B and C");
     constexpr int NGC = CHUNK_T / GROUP_T;
@@ -254,8 +254,39 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 if (rt_col + 8 * j < a.Rp) *reinterpret_cast<bf16x8_t*>(&s_rT[rt_t][rt_col + 8 * j]) = rld[j].v;
         }
     };
+    // The wait the compiler puts before a chunk's first use of its inputs allows as many memory
+    // operations in flight as the shortest path into that point issues after them.  The way in from
+    // here must not be that path, or every iteration would drain the stores it has just issued: the
+    // first chunk's requests go out first and stay in that order.
     issue_loads(c_begin, std::integral_constant<int, 0>{});
+    __builtin_amdgcn_sched_barrier(0);
     if constexpr (PF > 1) issue_loads(c_begin + 1, std::integral_constant<int, 1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    // PAIR (16-bit elements): a 32-step chunk is 64 bytes of a row, half a 128-byte line.  Writes of
+    // half lines reach about half the throughput of whole lines (and reads somewhat less than whole
+    // ones), so the traffic of an even chunk and the odd one after it (segments start at even
+    // chunks) is issued together: both chunks' inputs are requested in the odd chunk's phase A, tensor
+    // by tensor, and the even chunk's results wait in registers for the odd chunk's.
+    constexpr bool PAIR = PAT && sizeof(T) == 2 && FUSED_KS == 0 && PF == 2;
+    auto issue_pair = [&](int c0) {   // chunks c0 (slot 0) and c0 + 1 (slot 1)
+      if constexpr (PAIR) {
+        uint32_t off[2], boff[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int c = c0 + s;
+            const int t0 = c * CHUNK_T + pq * SLICE;
+            off[s] = (t0 + SLICE <= L && c < c_end) ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
+            const int ts = c * CHUNK_T + s_tq * GROUP_T;
+            boff[s] = (ts < L && c < c_end) ? bc_row_off + (uint32_t)ts * (uint32_t)sizeof(T) : BUF_OFF;
+        }
+        ru_[0] = io8<T>::load_buf(bu, off[0]); ru_[1] = io8<T>::load_buf(bu, off[1]);
+        rd_[0] = io8<T>::load_buf(bd, off[0]); rd_[1] = io8<T>::load_buf(bd, off[1]);
+        rz_[0] = io8<T>::load_buf(bz, off[0]); rz_[1] = io8<T>::load_buf(bz, off[1]);
+        rp_[0] = io8<T>::load_buf(bp, off[0]); rp_[1] = io8<T>::load_buf(bp, off[1]);
+        rbc_[0] = io4<T>::load_buf(bbc, boff[0]); rbc_[1] = io4<T>::load_buf(bbc, boff[1]);
+      }
+    };
+    typename io8<T>::packed held_y{}, held_o{};
     if constexpr (FUSED_KS > 0) {
         issue_r(c_begin);
         stage_r();
@@ -337,7 +368,11 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
             }
         };
         save_ckpt(c * (CHUNK_T / CKPT_T));
-        if (VEC || c + PF < c_end) issue_loads(c + PF, slot_tag);  // in flight during the scans below (VEC: switched off past the end, not branched around)
+        if constexpr (PAIR) {
+            if constexpr (SLOT == 1) issue_pair(c + 1);
+        } else {
+            if (VEC || c + PF < c_end) issue_loads(c + PF, slot_tag);  // in flight during the scans below (VEC: switched off past the end, not branched around)
+        }
         if constexpr (FUSED_KS > 0) {
             stage_r();          // r of chunk c + 1, requested a chunk ago; read by project() after the recurrence
             issue_r(c + 2);
@@ -481,7 +516,25 @@ __global__ void __launch_bounds__(THREADS) scan_fwd_kernel(const FwdArgs a)
                 for (int j = 0; j < SLICE; ++j) y8[j] += p8[j];
             }
             const uint32_t off = nv == SLICE ? row_off + (uint32_t)t0 * (uint32_t)sizeof(T) : BUF_OFF;
-            if constexpr (VEC) {
+            if constexpr (PAIR) {
+                const typename io8<T>::packed py = io8<T>::pack(y8);   // y before the gate, for the backward pass's dz (if kept)
+                if (has_z) {
+#pragma unroll
+                    for (int j = 0; j < SLICE; ++j) y8[j] *= z8[j] * sigmoid_fast(z8[j]);
+                }
+                const typename io8<T>::packed po = io8<T>::pack(y8);
+                if (SLOT == 0 && c + 1 < c_end) {   // wait for the odd chunk
+                    held_y = py;
+                    held_o = po;
+                } else {
+                    // the even chunk before an odd one is whole; a lone even chunk has nothing waiting
+                    const uint32_t off_e = SLOT == 1 ? row_off + (uint32_t)(t0 - CHUNK_T) * (uint32_t)sizeof(T) : BUF_OFF;
+                    io8<T>::store_packed(by, off_e, held_y);
+                    io8<T>::store_packed(by, off, py);
+                    io8<T>::store_packed(bo, off_e, held_o);
+                    io8<T>::store_packed(bo, off, po);
+                }
+            } else if constexpr (VEC) {
                 io8<T>::store_buf(by, off, y8);   // y before the gate, for the backward pass's dz (if kept)
                 if (has_z) {
 #pragma unroll

@@ -185,6 +185,128 @@ static double time_ms(F launch, int reps)
     return best;
 }
 
+// The scan kernels' access pattern without their arithmetic.  A workgroup of 256 threads owns 64
+// rows of row_bytes each (consecutive rows row_bytes apart, as in a (B, D, L) tensor) and walks along
+// them; per trip it reads PIECE bytes of every row from each of NIN tensors and writes PIECE bytes of
+// every row to each of NOUT tensors, VB bytes per thread and request, with the reads requested DEPTH
+// trips ahead.  PIECE = 64, VB = 16 is the forward scan (a 32-step chunk of bf16), PIECE = 32, VB = 8
+// the backward scan (a 16-step block); larger pieces show what longer contiguous runs would buy.
+template <int VB> struct piece_t;
+template <> struct piece_t<16> { typedef u32x4 type; };
+template <> struct piece_t<8> { typedef uint32_t __attribute__((ext_vector_type(2))) type; };
+template <int PIECE, int VB, int NIN, int NOUT, int DEPTH>
+__global__ void __launch_bounds__(256, 2) tile_stream(const char* __restrict__ src, char* __restrict__ dst, long tensor_bytes,
+                                                       int row_bytes, int ntrips)
+{
+    typedef typename piece_t<VB>::type V;
+    constexpr int TPR = PIECE / VB;                      // threads per row
+    constexpr int RPP = 256 / TPR;                       // rows per pass
+    constexpr int PASSES = 64 / RPP > 0 ? 64 / RPP : 1;  // passes over the 64 rows (threads past row 63 idle)
+    const int tid = threadIdx.x;
+    const int r = tid / TPR, q = tid % TPR;
+    if (r >= 64) return;
+    const long base = (long)blockIdx.x * 64 * row_bytes + (long)r * row_bytes + q * VB;
+    V buf[DEPTH][PASSES][NIN];
+    uint32_t acc = 0;   // keeps the reads alive when nothing is written
+    auto issue = [&](int trip, int slot) {
+        const int tr = trip < ntrips ? trip : ntrips - 1;
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p)
+#pragma unroll
+            for (int i = 0; i < NIN; ++i)
+                buf[slot][p][i] = __builtin_nontemporal_load(reinterpret_cast<const V*>(src + i * tensor_bytes + base + (long)p * RPP * row_bytes + (long)tr * PIECE));
+    };
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) issue(d, d);
+    for (int trip = 0; trip < ntrips; trip += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                V v = buf[d][p][0];
+#pragma unroll
+                for (int i = 1; i < NIN; ++i) v ^= buf[d][p][i];
+                acc ^= v.x;
+#pragma unroll
+                for (int o = 0; o < NOUT; ++o)
+                    *reinterpret_cast<V*>(dst + o * tensor_bytes + base + (long)p * RPP * row_bytes + (long)(trip + d) * PIECE) = v + (uint32_t)o;
+            }
+            issue(trip + d + DEPTH, d);
+        }
+    }
+    if (acc == 0x12345678u) *reinterpret_cast<uint32_t*>(dst) = acc;
+}
+
+template <int PIECE, int VB, int NIN, int NOUT, int DEPTH>
+static void run_tile(const char* what, const char* src, char* dst, int reps)
+{
+    const int rows = 8 * 4096, row_bytes = 2048 * 2;   // batch 8, 4096 channels, 2048 steps of bf16
+    const long tensor_bytes = (long)rows * row_bytes;
+    const int ntrips = row_bytes / PIECE;              // a multiple of DEPTH
+    const double ms = time_ms([&] { tile_stream<PIECE, VB, NIN, NOUT, DEPTH><<<dim3(rows / 64), dim3(256), 0, 0>>>(src, dst, tensor_bytes, row_bytes, ntrips); }, reps);
+    const double bytes = (double)(NIN + NOUT) * tensor_bytes;
+    printf("row tiles, %3d-byte pieces (%2d B/thread), %d in + %d out, %d trips ahead: %7.3f ms  %7.1f GB/s   [%s]\n", PIECE, VB, NIN, NOUT, DEPTH, ms,
+           bytes / (ms * 1e6), what);
+}
+
+// The same, with the scan kernels' thread mapping kept (thread = row tid / 4, quarter tid % 4 of a
+// 4 * VB-byte piece) and a trip covering SPLIT such pieces of every row, requested and written back
+// to back: what grouping the traffic of SPLIT chunks buys without changing who owns which element.
+template <int VB, int SPLIT, int NIN, int NOUT, int DEPTH>
+__global__ void __launch_bounds__(256, 2) tile_stream_split(const char* __restrict__ src, char* __restrict__ dst, long tensor_bytes,
+                                                             int row_bytes, int ntrips)
+{
+    typedef typename piece_t<VB>::type V;
+    constexpr int SUB = 4 * VB, PIECE = SUB * SPLIT;
+    const int tid = threadIdx.x;
+    const int r = tid >> 2, q = tid & 3;
+    const long base = (long)blockIdx.x * 64 * row_bytes + (long)r * row_bytes + q * VB;
+    V buf[DEPTH][SPLIT][NIN];
+    uint32_t acc = 0;
+    auto issue = [&](int trip, int slot) {
+        const int tr = trip < ntrips ? trip : ntrips - 1;
+#pragma unroll
+        for (int i = 0; i < NIN; ++i)
+#pragma unroll
+            for (int j = 0; j < SPLIT; ++j)
+                buf[slot][j][i] = __builtin_nontemporal_load(reinterpret_cast<const V*>(src + i * tensor_bytes + base + (long)tr * PIECE + j * SUB));
+    };
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) issue(d, d);
+    for (int trip = 0; trip < ntrips; trip += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            V v[SPLIT];
+#pragma unroll
+            for (int j = 0; j < SPLIT; ++j) {
+                v[j] = buf[d][j][0];
+#pragma unroll
+                for (int i = 1; i < NIN; ++i) v[j] ^= buf[d][j][i];
+                acc ^= v[j].x;
+            }
+#pragma unroll
+            for (int o = 0; o < NOUT; ++o)
+#pragma unroll
+                for (int j = 0; j < SPLIT; ++j)
+                    *reinterpret_cast<V*>(dst + o * tensor_bytes + base + (long)(trip + d) * PIECE + j * SUB) = v[j] + (uint32_t)o;
+            issue(trip + d + DEPTH, d);
+        }
+    }
+    if (acc == 0x12345678u) *reinterpret_cast<uint32_t*>(dst) = acc;
+}
+
+template <int VB, int SPLIT, int NIN, int NOUT, int DEPTH>
+static void run_tile_split(const char* what, const char* src, char* dst, int reps)
+{
+    const int rows = 8 * 4096, row_bytes = 2048 * 2;
+    const long tensor_bytes = (long)rows * row_bytes;
+    const int ntrips = row_bytes / (4 * VB * SPLIT);
+    const double ms = time_ms([&] { tile_stream_split<VB, SPLIT, NIN, NOUT, DEPTH><<<dim3(rows / 64), dim3(256), 0, 0>>>(src, dst, tensor_bytes, row_bytes, ntrips); }, reps);
+    const double bytes = (double)(NIN + NOUT) * tensor_bytes;
+    printf("row tiles, %d x %2d-byte pieces back to back, %d in + %d out, %d trips ahead: %7.3f ms  %7.1f GB/s   [%s]\n", SPLIT, 4 * VB, NIN, NOUT, DEPTH, ms,
+           bytes / (ms * 1e6), what);
+}
+
 template <int MODE>
 static void run_alu(const char* name, double instr_per_trip_per_wave, const char* what, float* out, int reps)
 {
@@ -236,6 +358,26 @@ int main(int argc, char** argv)
         printf("stream 1 GiB, %5d workgroups: read %7.1f GB/s   write %7.1f GB/s   copy %7.1f GB/s (read+write)\n", blocks,
                bytes / (r * 1e6), bytes / (w * 1e6), 2.0 * bytes / (c * 1e6));
     }
+    // (B, D, L) = (8, 4096, 2048) bf16 tensors: 7 inputs + 4 outputs of 128 MiB fit the two 1 GiB buffers
+    run_tile<64, 16, 3, 4, 2>("forward scan: u, delta, z in; out, y and 4 bytes/step of checkpoints out", (const char*)src, (char*)dst, reps);
+    run_tile<64, 16, 3, 2, 2>("forward scan without the checkpoints", (const char*)src, (char*)dst, reps);
+    run_tile<128, 16, 3, 4, 2>("the same bytes in 128-byte pieces", (const char*)src, (char*)dst, reps);
+    run_tile<256, 16, 3, 4, 2>("the same bytes in 256-byte pieces", (const char*)src, (char*)dst, reps);
+    run_tile<64, 16, 3, 4, 4>("forward scan, four trips ahead", (const char*)src, (char*)dst, reps);
+    run_tile<32, 8, 7, 3, 2>("backward scan: u, delta, z, dout, y + 4 bytes/step of checkpoints in; du, ddelta, dz out", (const char*)src, (char*)dst, reps);
+    run_tile<32, 8, 7, 3, 4>("backward scan, four trips ahead", (const char*)src, (char*)dst, reps);
+    run_tile<64, 16, 7, 3, 2>("the same bytes in 64-byte pieces", (const char*)src, (char*)dst, reps);
+    run_tile<128, 16, 7, 3, 2>("the same bytes in 128-byte pieces", (const char*)src, (char*)dst, reps);
+    run_tile<64, 16, 3, 0, 2>("reads only, 64-byte pieces", (const char*)src, (char*)dst, reps);
+    run_tile<64, 16, 1, 4, 2>("mostly writes, 64-byte pieces", (const char*)src, (char*)dst, reps);
+    run_tile_split<16, 2, 3, 4, 2>("forward bytes, two chunks' traffic grouped", (const char*)src, (char*)dst, reps);
+    run_tile_split<16, 4, 3, 4, 2>("forward bytes, four chunks' traffic grouped", (const char*)src, (char*)dst, reps);
+    run_tile_split<16, 4, 3, 4, 1>("forward bytes, four chunks' traffic grouped, one trip ahead", (const char*)src, (char*)dst, reps);
+    run_tile_split<8, 2, 7, 3, 2>("backward bytes, two blocks' traffic grouped", (const char*)src, (char*)dst, reps);
+    run_tile_split<8, 4, 7, 3, 2>("backward bytes, four blocks' traffic grouped", (const char*)src, (char*)dst, reps);
+    run_tile_split<8, 8, 7, 3, 1>("backward bytes, eight blocks' traffic grouped, one trip ahead", (const char*)src, (char*)dst, reps);
+    run_tile_split<16, 2, 1, 4, 2>("mostly writes, two 64-byte pieces back to back", (const char*)src, (char*)dst, reps);
+    run_tile_split<16, 4, 1, 4, 2>("mostly writes, four 64-byte pieces back to back", (const char*)src, (char*)dst, reps);
     CHECK(hipFree(src));
     CHECK(hipFree(dst));
     CHECK(hipFree(out));
