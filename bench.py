@@ -277,7 +277,7 @@ def decode_bench(dev, tokens=512):
 
 
 def layer_bench(dev, workload, iters=20):
-    """The layer around the scan at the headline shape (conv + SiLU, projections through rocBLAS,
+    """The layer around the scan at the headline shape (conv + SiLU, projections,
     scan, gate; backward with recomputation), and its convolution kernels against the HBM roofline."""
     import torch
     from paper_2312_00752_amd import binding as B
@@ -335,7 +335,7 @@ def layer_bench(dev, workload, iters=20):
         for i in range(128):
             B.ss_layer_step(h, cs, xs[i % 8], zs[i % 8], *args[2:], scratch=sscr, out_t=o_t)
     dec_ms = timed(decode) if iters >= 5 else None
-    # the same 128 steps replayed from a HIP graph (the rocBLAS products capture like the kernels)
+    # the same 128 steps replayed from a HIP graph (every step of the layer is a kernel launch)
     dec_graph_us = None
     if dec_ms is not None:
         graph = torch.cuda.CUDAGraph()

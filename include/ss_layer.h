@@ -18,11 +18,10 @@
  *
  * Rules as in ss_scan.h (device pointers owned by the caller, dense row-major layouts, io
  * tensors 16-byte aligned, float32 ones 4-byte aligned, outputs overwritten, host-side
- * validation, SS_OK or a negative code), with one difference: the two projections are plain
- * GEMMs and are handed to rocBLAS, which is looked up at run time (librocblas.so.5); the
- * first layer call on a device creates a rocBLAS handle, which allocates.  If rocBLAS cannot
- * be loaded or refuses a call the result is SS_ERR_BACKEND.  `saved` and `scratch` must be
- * 256-byte aligned; seqlen must be >= 1 and dstate <= SS_MAX_DSTATE.
+ * validation, SS_OK or a negative code).  The two projections and their gradients run on this
+ * library's own matrix-core kernels like every other step: no backend library is loaded and no
+ * call allocates.  `saved` and `scratch` must be 256-byte aligned; seqlen must be >= 1 and
+ * dstate <= SS_MAX_DSTATE.
  *      x, z, out, dout, dx, dz : (B, D, L)     io_dtype
  *      W_x                     : (R+2N, D)     io_dtype   rows: r (R), B (N), C (N)
  *      W_dt                    : (D, R)        io_dtype
@@ -40,7 +39,7 @@
 extern "C" {
 #endif
 
-#define SS_ERR_BACKEND (-7) /* rocBLAS could not be loaded or refused a call */
+#define SS_ERR_BACKEND (-7) /* reserved: no current entry point returns it (there is no backend library) */
 
 typedef struct {
     int32_t batch, dim, seqlen, dstate, dt_rank, conv_width; /* B, D, L, N, R, W             */
@@ -100,9 +99,9 @@ size_t ss_layer_step_scratch_bytes(const ss_layer_step_params *p);
 /* One token of the layer in recurrent mode (Section 2): the conv window slides by one sample,
  * the projections become (B, D) x (D, R+2N) and (B, R) x (R, D) products, and Eq. 2a/2b are
  * applied once; constant time and memory per token.  bf16 calls with D % 32 == 0, R % 8 == 0,
- * R <= 256, N <= 16 and 16-byte aligned W_x, W_dt and h run on hand-written kernels only
- * (deterministic; no backend library is loaded); other calls use the GEMM backend and can
- * return SS_ERR_BACKEND. */
+ * R <= 256, N <= 16 and 16-byte aligned W_x, W_dt and h take three launches (both projections
+ * on the matrix cores, delta_t formed inside the state update); other calls form the two
+ * products with the general projection kernel first.  Deterministic either way. */
 int ss_layer_step(const ss_layer_step_params *p, void *stream);
 
 #ifdef __cplusplus

@@ -512,7 +512,7 @@ const char* ss_strerror(int code)
     case SS_ERR_ALIGN: return "a pointer is not aligned as required";
     case SS_ERR_WORKSPACE: return "workspace missing or too small";
     case SS_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
-    case SS_ERR_BACKEND: return "rocBLAS could not be loaded or refused a call";
+    case SS_ERR_BACKEND: return "backend failure (reserved; not returned by any current entry point)";
     default: return "unknown error code";
     }
 }

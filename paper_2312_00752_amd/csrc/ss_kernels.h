@@ -120,4 +120,17 @@ int step_strided(const ss_step_params* p, long bc_stride, void* stream);
 // ss_step for the layer's decode: delta_t, B_t, C_t come from the float32 projection output
 // P (B, ldp) = [r; B; C] and W_dt (D, R) (see StepArgs); p's delta_t, B_t, C_t are ignored.
 int step_projected(const ss_step_params* p, const float* P, const void* W_dt, int R, int ldp, void* stream);
+
+// C[i] (M x N, row pitch ldc) = op(A[i]) (M x K) op(B[i]) (K x N) [+ C[i]] for i < batch, float
+// accumulation.  Element (m, k) of op(A[i]) is A[i * a_batch + m * a_m + k * a_k], element (k, n) of
+// op(B[i]) is B[i * b_batch + k * b_k + n * b_n] (strides in elements, so either operand may be stored
+// transposed).  A and B are bf16 or float (bf16); C is float if c_float, else like A and B.
+struct GemmArgs {
+    int M, N, K, batch;
+    const void* A; long a_m, a_k, a_batch;
+    const void* B; long b_k, b_n, b_batch;
+    void* C; long ldc, c_batch;
+    bool bf16, c_float, accumulate;
+};
+int gemm(const GemmArgs& g, hipStream_t stream);
 }  // namespace ss

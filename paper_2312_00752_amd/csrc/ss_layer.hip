@@ -1,17 +1,13 @@
 // Selective SSM layer: conv -> SiLU -> projections -> scan -> gate, forward and backward
 // with recomputation (see include/ss_layer.h).
 //
-// The scan and the convolution are this library's own kernels.  The two projections are
-// plain GEMMs on dense operands and go to rocBLAS, resolved with dlopen so that the library
-// itself carries no link-time dependency on it.  Everything is laid out so that the GEMMs
-// need no transposed copies: with the sequence axis last, a batch entry of u is a (D, L)
-// row-major matrix, [r;B;C] = W_x @ u lands directly in the (B, N, L) layout the scan reads
+// The scan, the convolution and the projections are all this library's own kernels (ss::gemm for
+// the projections and their gradients).  Everything is laid out so that no product needs a
+// transposed copy of a (B, D, L) tensor: with the sequence axis last, a batch entry of u is a
+// (D, L) row-major matrix, [r;B;C] = W_x @ u lands directly in the (B, N, L) layout the scan reads
 // (B and C are rows R.. of the result: the scan is told the batch stride), and
 // delta_raw = W_dt @ r lands in the (B, D, L) layout of the scan's step-size input.
-#include <dlfcn.h>
 #include <hip/hip_runtime.h>
-#include <mutex>
-#include <rocblas/rocblas.h>  // types and signatures only; the functions are looked up at run time
 
 #include "ss_device.h"
 #include "ss_kernels.h"
@@ -22,61 +18,19 @@ namespace {
 inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// ---- rocBLAS, looked up once ------------------------------------------------------------------
-struct Blas {
-    decltype(&rocblas_create_handle) create = nullptr;
-    decltype(&rocblas_set_stream) set_stream = nullptr;
-    decltype(&rocblas_gemm_strided_batched_ex) gemm = nullptr;
-    bool ok = false;
-    static constexpr int kMaxDevices = 64;
-    rocblas_handle handle[kMaxDevices] = {};
-    std::mutex mu;
-};
-Blas g_blas;
-std::once_flag g_blas_once;
-
-void load_blas()
+// C[i] (M x N) = op(A[i]) (M x K) @ op(B[i]) (K x N) + beta * C[i] (beta 0 or 1), all ROW-major with
+// row pitches lda/ldb/ldc of the stored matrices and element strides sA/sB/sC between batch
+// entries; C is float32 if c_float, else in the io dtype.
+bool gemm_rm(hipStream_t st, bool tA, bool tB, int M, int N, int K, const void* A, int lda, long sA,
+             const void* B, int ldb, long sB, float beta, void* C, int ldc, long sC, int batch, bool bf16, bool c_float = false)
 {
-    void* so = dlopen("librocblas.so.5", RTLD_NOW | RTLD_LOCAL);
-    if (!so) so = dlopen("librocblas.so", RTLD_NOW | RTLD_LOCAL);
-    if (!so) so = dlopen("/opt/rocm/lib/librocblas.so.5", RTLD_NOW | RTLD_LOCAL);
-    if (!so) return;
-    g_blas.create = reinterpret_cast<decltype(g_blas.create)>(dlsym(so, "rocblas_create_handle"));
-    g_blas.set_stream = reinterpret_cast<decltype(g_blas.set_stream)>(dlsym(so, "rocblas_set_stream"));
-    g_blas.gemm = reinterpret_cast<decltype(g_blas.gemm)>(dlsym(so, "rocblas_gemm_strided_batched_ex"));
-    g_blas.ok = g_blas.create && g_blas.set_stream && g_blas.gemm;
-}
-
-// Handle of the current device, bound to `stream`; nullptr if rocBLAS is unavailable.
-rocblas_handle blas_handle(hipStream_t stream)
-{
-    std::call_once(g_blas_once, load_blas);
-    if (!g_blas.ok) return nullptr;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= Blas::kMaxDevices) return nullptr;
-    std::lock_guard<std::mutex> lock(g_blas.mu);
-    if (!g_blas.handle[dev] && g_blas.create(&g_blas.handle[dev]) != rocblas_status_success) {
-        g_blas.handle[dev] = nullptr;
-        return nullptr;
-    }
-    if (g_blas.set_stream(g_blas.handle[dev], stream) != rocblas_status_success) return nullptr;
-    return g_blas.handle[dev];
-}
-
-// C[i] (M x N) = op(A[i]) (M x K) @ op(B[i]) (K x N) + beta * C[i], all ROW-major with row
-// pitches lda/ldb/ldc of the stored matrices and element strides sA/sB/sC between batch
-// entries.  A row-major matrix is the column-major matrix of its transpose, so the product
-// is handed to rocBLAS as C^T = op(B)^T op(A)^T with the operands swapped.
-bool gemm_rm(rocblas_handle h, bool tA, bool tB, int M, int N, int K, const void* A, int lda, long sA,
-             const void* B, int ldb, long sB, float beta, void* C, int ldc, long sC, int batch, bool bf16)
-{
-    const float alpha = 1.0f;
-    const rocblas_datatype t = bf16 ? rocblas_datatype_bf16_r : rocblas_datatype_f32_r;
-    const rocblas_status st = g_blas.gemm(
-        h, tB ? rocblas_operation_transpose : rocblas_operation_none,
-        tA ? rocblas_operation_transpose : rocblas_operation_none, N, M, K, &alpha, B, t, ldb, sB, A, t, lda, sA,
-        &beta, C, t, ldc, sC, C, t, ldc, sC, batch, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
-    return st == rocblas_status_success;
+    ss::GemmArgs g{};
+    g.M = M; g.N = N; g.K = K; g.batch = batch;
+    g.A = A; g.a_m = tA ? 1 : lda; g.a_k = tA ? lda : 1; g.a_batch = sA;
+    g.B = B; g.b_k = tB ? 1 : ldb; g.b_n = tB ? ldb : 1; g.b_batch = sB;
+    g.C = C; g.ldc = ldc; g.c_batch = sC;
+    g.bf16 = bf16; g.c_float = c_float || !bf16; g.accumulate = beta != 0.0f;
+    return ss::gemm(g, st) == SS_OK;
 }
 
 // ---- small kernels around the GEMMs -----------------------------------------------------------
@@ -233,7 +187,7 @@ SavedLayout saved_layout(const ss_layer_params* p)
 
 // scratch: forward  [u][delta][P and the scan's split scratch, used if nothing is saved][r transposed and padded, bf16]
 //          backward [u][delta][du][ddelta][dP (B,Mx,L) io][dB, dC (B,N,L) f32]
-//                   [partials of dW_dt (B,D,R) io][partials of dW_x (B,Mx,D) io]
+//                   [partials of dW_dt (B,D,R) f32][partials of dW_x (B,Mx,D) f32]
 struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, rT, du, ddelta, dP, dB, dC, part_dt, part_x, total; };
 ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
 {
@@ -256,8 +210,8 @@ ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
         w.dP = take(s.B * s.Mx * s.L * s.esz);
         w.dB = take(s.B * s.N * s.L * sizeof(float));
         w.dC = take(s.B * s.N * s.L * sizeof(float));
-        w.part_dt = take(s.B * s.D * s.R * s.esz);
-        w.part_x = take(s.B * s.Mx * s.D * s.esz);
+        w.part_dt = take(s.B * s.D * s.R * sizeof(float));
+        w.part_x = take(s.B * s.Mx * s.D * sizeof(float));
     }
     w.total = off;
     return w;
@@ -275,7 +229,7 @@ int check_layer(const ss_layer_params* p, bool bwd)
     if (p->dstate > SS_MAX_DSTATE || p->conv_width > SS_CONV_MAX_WIDTH) return SS_ERR_UNSUPPORTED;
     if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
     if (p->flags != 0) return SS_ERR_UNSUPPORTED;
-    // rocBLAS takes 32-bit sizes
+    // the projections take 32-bit sizes
     if ((long)p->dim * p->dt_rank >= 0x7fffffffL || (long)p->dim * (p->dt_rank + 2 * p->dstate) >= 0x7fffffffL)
         return SS_ERR_UNSUPPORTED;
     if (!p->x || !p->z || !p->conv_w || !p->conv_b || !p->W_x || !p->W_dt || !p->dt_bias || !p->A || !p->Dskip)
@@ -330,8 +284,6 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     int rc = check_layer(p, false);
     if (rc != SS_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rocblas_handle h = blas_handle(st);
-    if (!h) return SS_ERR_BACKEND;
     const Shape s = shape_of(p);
     const bool bf16 = p->io_dtype == SS_BF16;
     const ScratchLayout sc = scratch_layout(p, false);
@@ -350,7 +302,7 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     }
     if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
     // [r;B;C] = W_x @ u
-    if (!gemm_rm(h, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16))
+    if (!gemm_rm(st, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16))
         return SS_ERR_BACKEND;
     ss_fwd_params f = scan_params(p);
     f.u = u; f.delta = delta; f.z = p->z;
@@ -381,7 +333,7 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
         if (rc != SS_ERR_UNSUPPORTED) return rc;   // otherwise nothing was enqueued: take the general path
     }
     // delta_raw = W_dt @ r
-    if (!gemm_rm(h, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
+    if (!gemm_rm(st, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
         return SS_ERR_BACKEND;
     return ss::scan_fwd_strided(&f, (long)Mx * L, stream);
 }
@@ -400,8 +352,6 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
     for (const void* g : f32)
         if (!aligned_to(g, 4)) return SS_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rocblas_handle h = blas_handle(st);
-    if (!h) return SS_ERR_BACKEND;
     const Shape s = shape_of(p);
     const bool bf16 = p->io_dtype == SS_BF16;
     const ScratchLayout sc = scratch_layout(p, true);
@@ -418,7 +368,7 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
     // recompute the two cheap intermediates
     ss_conv_params c = conv_params(p, u);
     if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
-    if (!gemm_rm(h, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
+    if (!gemm_rm(st, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
         return SS_ERR_BACKEND;
 
     // the scan
@@ -437,9 +387,9 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
     if ((rc = ss::scan_bwd_strided(&b, (long)Mx * L, stream)) != SS_OK) return rc;
 
     // delta_raw = W_dt @ r:  dr = W_dt^T @ ddelta  (rows 0..R-1 of dP),  dW_dt = sum_b ddelta r^T
-    if (!gemm_rm(h, true, false, R, L, D, p->W_dt, R, 0, ddelta, L, (long)D * L, 0.0f, dP, L, (long)Mx * L, B, bf16))
+    if (!gemm_rm(st, true, false, R, L, D, p->W_dt, R, 0, ddelta, L, (long)D * L, 0.0f, dP, L, (long)Mx * L, B, bf16))
         return SS_ERR_BACKEND;
-    if (!gemm_rm(h, false, true, D, R, L, ddelta, L, (long)D * L, P, L, (long)Mx * L, 0.0f, part_dt, R, (long)D * R, B, bf16))
+    if (!gemm_rm(st, false, true, D, R, L, ddelta, L, (long)D * L, P, L, (long)Mx * L, 0.0f, part_dt, R, (long)D * R, B, bf16, true))
         return SS_ERR_BACKEND;
     // rows R.. of dP from the scan's float32 dB, dC
     {
@@ -450,19 +400,14 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
         if (hipGetLastError() != hipSuccess) return SS_ERR_LAUNCH;
     }
     // [r;B;C] = W_x @ u:  du += W_x^T @ dP,  dW_x = sum_b dP u^T
-    if (!gemm_rm(h, true, false, D, L, Mx, p->W_x, D, 0, dP, L, (long)Mx * L, 1.0f, du, L, (long)D * L, B, bf16))
+    if (!gemm_rm(st, true, false, D, L, Mx, p->W_x, D, 0, dP, L, (long)Mx * L, 1.0f, du, L, (long)D * L, B, bf16))
         return SS_ERR_BACKEND;
-    if (!gemm_rm(h, false, true, Mx, D, L, dP, L, (long)Mx * L, u, L, (long)D * L, 0.0f, part_x, D, (long)Mx * D, B, bf16))
+    if (!gemm_rm(st, false, true, Mx, D, L, dP, L, (long)Mx * L, u, L, (long)D * L, 0.0f, part_x, D, (long)Mx * D, B, bf16, true))
         return SS_ERR_BACKEND;
     {
         const long n_dt = (long)D * R, n_x = (long)Mx * D;
-        if (bf16) {
-            hipLaunchKernelGGL(sum_partials_kernel<ss::bf16_t>, dim3((unsigned)((n_dt + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const ss::bf16_t*>(part_dt), B, n_dt, q->dW_dt);
-            hipLaunchKernelGGL(sum_partials_kernel<ss::bf16_t>, dim3((unsigned)((n_x + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const ss::bf16_t*>(part_x), B, n_x, q->dW_x);
-        } else {
-            hipLaunchKernelGGL(sum_partials_kernel<float>, dim3((unsigned)((n_dt + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const float*>(part_dt), B, n_dt, q->dW_dt);
-            hipLaunchKernelGGL(sum_partials_kernel<float>, dim3((unsigned)((n_x + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const float*>(part_x), B, n_x, q->dW_x);
-        }
+        hipLaunchKernelGGL(sum_partials_kernel<float>, dim3((unsigned)((n_dt + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const float*>(part_dt), B, n_dt, q->dW_dt);
+        hipLaunchKernelGGL(sum_partials_kernel<float>, dim3((unsigned)((n_x + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const float*>(part_x), B, n_x, q->dW_x);
         if (hipGetLastError() != hipSuccess) return SS_ERR_LAUNCH;
     }
     // u = SiLU(conv(x))
@@ -530,13 +475,11 @@ int ss_layer_step(const ss_layer_step_params* p, void* stream)
         return ss::step_projected(&s, P_acc, p->W_dt, R, Mx, stream);
     }
 
-    rocblas_handle h = blas_handle(st);
-    if (!h) return SS_ERR_BACKEND;
     int rc = ss_conv_step(&c, stream);
     if (rc != SS_OK) return rc;
     // [r;B;C]_t (B, Mx) = u_t (B, D) @ W_x^T;   delta_t (B, D) = r_t (B, R) @ W_dt^T
-    if (!gemm_rm(h, false, true, B, Mx, D, u_t, D, 0, p->W_x, D, 0, 0.0f, P_t, Mx, 0, 1, bf16)) return SS_ERR_BACKEND;
-    if (!gemm_rm(h, false, true, B, D, R, P_t, Mx, 0, p->W_dt, R, 0, 0.0f, delta_t, D, 0, 1, bf16)) return SS_ERR_BACKEND;
+    if (!gemm_rm(st, false, true, B, Mx, D, u_t, D, 0, p->W_x, D, 0, 0.0f, P_t, Mx, 0, 1, bf16)) return SS_ERR_BACKEND;
+    if (!gemm_rm(st, false, true, B, D, R, P_t, Mx, 0, p->W_dt, R, 0, 0.0f, delta_t, D, 0, 1, bf16)) return SS_ERR_BACKEND;
     s.delta_t = delta_t;
     s.B_t = P_t + (size_t)R * esz;
     s.C_t = P_t + (size_t)(R + N) * esz;

@@ -154,7 +154,7 @@ def test_layer_steps_replayed_from_a_hip_graph():
     def run():
         for i in range(steps):
             B.ss_layer_step(h, cs, xs[i], zs[i], *weights, scratch=scratch, out_t=outs[i])
-    run()                                   # eager; also creates the rocBLAS handle outside the capture
+    run()                                   # eager, outside the capture
     torch.cuda.synchronize()
     want_out, want_h = outs.clone(), h.clone()
     ref = inn.inner_fwd(rnd=_rnd("bf16"), **{k: w[k] for k in PARAMS})
