@@ -104,6 +104,38 @@ size_t ss_layer_step_scratch_bytes(const ss_layer_step_params *p);
  * products with the general projection kernel first.  Deterministic either way. */
 int ss_layer_step(const ss_layer_step_params *p, void *stream);
 
+/* The products behind the layer's projections (Algorithm 2: the linear maps s_B, s_C of
+ * Section 3.2 and the low-rank Delta projection of Section 3.6) and their gradients, callable
+ * on their own:
+ *     C[i] (M x N) = op(A[i]) (M x K)  op(B[i]) (K x N)   [+ C[i] with SS_GEMM_ACCUMULATE],  i < batch,
+ * accumulated in float32.  Element (m, k) of op(A[i]) is A[i * a_batch + m * a_m + k * a_k] and
+ * element (k, n) of op(B[i]) is B[i * b_batch + k * b_k + n * b_n] (strides in elements, so either
+ * operand may be stored transposed; a batch stride of 0 shares an operand); C is row-major with
+ * row pitch ldc, float32 with SS_GEMM_C_FLOAT and in io_dtype otherwise.  A and B are io_dtype.
+ * bf16 products of the layer's three shapes (few output rows with a long contraction over the rows
+ * of B; many output rows with a contraction of at most 160; both operands contiguous along the
+ * contraction index with a float32 result) run on matrix-core kernels when sizes are multiples of
+ * 64 (rows / columns of the big side), 16 (the small side, at most 160) and pointers and strides
+ * are multiples of 16 bytes; everything else, and every call with SS_GEMM_GENERAL, runs on a
+ * general kernel.  Device pointers; C must not overlap A or B.  SS_OK, SS_ERR_NULL,
+ * SS_ERR_SHAPE (negative size), SS_ERR_UNSUPPORTED (dtype, unknown flag, more than 65535 batch
+ * entries or 64-row tiles) or SS_ERR_LAUNCH. */
+#define SS_GEMM_C_FLOAT    1u
+#define SS_GEMM_ACCUMULATE 2u
+#define SS_GEMM_GENERAL    4u
+typedef struct {
+    int32_t M, N, K, batch;
+    int32_t io_dtype;           /* ss_dtype of A and B (and of C without SS_GEMM_C_FLOAT)         */
+    uint32_t flags;             /* SS_GEMM_*                                                      */
+    const void *A;
+    int64_t a_m, a_k, a_batch;
+    const void *B;
+    int64_t b_k, b_n, b_batch;
+    void *C;
+    int64_t ldc, c_batch;
+} ss_gemm_params;
+int ss_proj_gemm(const ss_gemm_params *p, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

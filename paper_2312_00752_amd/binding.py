@@ -87,6 +87,15 @@ class LayerStepParams(ctypes.Structure):
                 ("scratch", _vp), ("scratch_bytes", ctypes.c_size_t)]
 
 
+class GemmParams(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int32), ("N", ctypes.c_int32), ("K", ctypes.c_int32), ("batch", ctypes.c_int32),
+                ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("A", _vp), ("a_m", ctypes.c_int64), ("a_k", ctypes.c_int64), ("a_batch", ctypes.c_int64),
+                ("B", _vp), ("b_k", ctypes.c_int64), ("b_n", ctypes.c_int64), ("b_batch", ctypes.c_int64),
+                ("C", _vp), ("ldc", ctypes.c_int64), ("c_batch", ctypes.c_int64)]
+
+
+SS_GEMM_C_FLOAT, SS_GEMM_ACCUMULATE, SS_GEMM_GENERAL = 1, 2, 4
 SS_ERR_BACKEND = -7
 SS_CONV_SILU, SS_CONV_HAS_BIAS, SS_CONV_HAS_STATE, SS_CONV_WRITE_STATE = 1, 2, 4, 8
 SS_CONV_MAX_WIDTH = 4
@@ -131,6 +140,8 @@ def lib():
         l.ss_layer_step.restype = ctypes.c_int
         l.ss_layer_step.argtypes = [ctypes.POINTER(LayerStepParams), _vp]
         l.ss_strerror.restype = ctypes.c_char_p
+        l.ss_proj_gemm.argtypes = [ctypes.POINTER(GemmParams), _vp]
+        l.ss_proj_gemm.restype = ctypes.c_int
         l.ss_strerror.argtypes = [ctypes.c_int]
         l.ss_version.restype = ctypes.c_int
         l.ss_version.argtypes = []
@@ -585,3 +596,50 @@ def ss_layer_bwd(dout, x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scrat
     if rc != SS_OK:
         raise SsError(rc)
     return g
+
+
+def ss_proj_gemm(A, B, C, trans_a=False, trans_b=False, accumulate=False, general=False, stream=None):
+    """C[i] = op(A[i]) @ op(B[i]) (+ C[i]) on the layer's projection kernels.  A, B, C are 2-D or
+    3-D (leading batch axis) tensors whose last axis is contiguous; a 2-D operand is shared by all
+    batch entries.  ``trans_a`` / ``trans_b``: the operand is stored transposed ((K, M) / (N, K)).
+    C is float32 or of the operands' dtype."""
+    import torch
+    def view(t):
+        if t.stride(-1) != 1:
+            raise ValueError("the last axis must be contiguous")
+        return (t.shape[0], t.stride(0), t.stride(1)) if t.dim() == 3 else (1, 0, t.stride(0))
+    (ba, sa, lda), (bb, sb, ldb), (bc, sc, ldc) = view(A), view(B), view(C)
+    if C.dim() == 3 and C.shape[0] > 1 and sc == 0:
+        raise ValueError("C needs its own batch entries")
+    p = GemmParams()
+    p.M, p.N = C.shape[-2], C.shape[-1]
+    p.K = A.shape[-2] if trans_a else A.shape[-1]
+    kb = B.shape[-1] if trans_b else B.shape[-2]
+    ma = A.shape[-1] if trans_a else A.shape[-2]
+    nb_ = B.shape[-2] if trans_b else B.shape[-1]
+    if kb != p.K or ma != p.M or nb_ != p.N or A.dtype != B.dtype:
+        raise ValueError("shapes or dtypes do not agree")
+    p.batch = bc if C.dim() == 3 else 1
+    for t, n in ((A, ba), (B, bb)):
+        if t.dim() == 3 and n != p.batch:
+            raise ValueError("batch sizes do not agree")
+    p.io_dtype = _io_code(A)
+    if C.dtype == torch.float32:
+        p.flags |= SS_GEMM_C_FLOAT
+    elif C.dtype != A.dtype:
+        raise ValueError("C must be float32 or of the operands' dtype")
+    if accumulate:
+        p.flags |= SS_GEMM_ACCUMULATE
+    if general:
+        p.flags |= SS_GEMM_GENERAL
+    p.A, p.B, p.C = A.data_ptr(), B.data_ptr(), C.data_ptr()
+    p.a_m, p.a_k = (1, lda) if trans_a else (lda, 1)
+    p.b_k, p.b_n = (1, ldb) if trans_b else (ldb, 1)
+    p.a_batch, p.b_batch, p.ldc, p.c_batch = sa, sb, ldc, sc
+    for t in (A, B, C):
+        if not t.is_cuda:
+            raise ValueError("device tensors expected")
+    rc = lib().ss_proj_gemm(ctypes.byref(p), _stream(stream))
+    if rc != SS_OK:
+        raise SsError(rc)
+    return C

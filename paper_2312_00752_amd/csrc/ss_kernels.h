@@ -131,6 +131,7 @@ struct GemmArgs {
     const void* B; long b_k, b_n, b_batch;
     void* C; long ldc, c_batch;
     bool bf16, c_float, accumulate;
+    bool general;   // take the general kernel even where a matrix-core kernel fits (for verification)
 };
 int gemm(const GemmArgs& g, hipStream_t stream);
 }  // namespace ss

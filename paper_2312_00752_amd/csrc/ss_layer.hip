@@ -149,6 +149,34 @@ __global__ void transpose_r_kernel(const ss::bf16_t* __restrict__ P, long bstrid
     }
 }
 
+// dst (cols, rows) = src (rows, cols)^T for a weight matrix, 32 x 32 tiles through LDS; block (32, 8),
+// grid (cols / 32 rounded up, rows / 32 rounded up).
+template <typename T>
+__global__ void transpose_weight_kernel(const T* __restrict__ src, T* __restrict__ dst, int rows, int cols)
+{
+    __shared__ T tile[32][33];
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    const int tx = threadIdx.x, ty = threadIdx.y;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = r0 + ty + 8 * i, c = c0 + tx;
+        if (r < rows && c < cols) tile[ty + 8 * i][tx] = src[(size_t)r * cols + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = c0 + ty + 8 * i, r = r0 + tx;
+        if (r < rows && c < cols) dst[(size_t)c * rows + r] = tile[tx][ty + 8 * i];
+    }
+}
+template <typename T>
+bool transpose_weight(const void* src, void* dst, int rows, int cols, hipStream_t st)
+{
+    hipLaunchKernelGGL(transpose_weight_kernel<T>, dim3((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32)), dim3(32, 8), 0, st,
+                       static_cast<const T*>(src), static_cast<T*>(dst), rows, cols);
+    return hipGetLastError() == hipSuccess;
+}
+
 // ---- buffers -------------------------------------------------------------------------------------
 struct Shape {
     size_t B, D, L, N, R, Mx, esz;
@@ -188,7 +216,8 @@ SavedLayout saved_layout(const ss_layer_params* p)
 // scratch: forward  [u][delta][P and the scan's split scratch, used if nothing is saved][r transposed and padded, bf16]
 //          backward [u][delta][du][ddelta][dP (B,Mx,L) io][dB, dC (B,N,L) f32]
 //                   [partials of dW_dt (B,D,R) f32][partials of dW_x (B,Mx,D) f32]
-struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, rT, du, ddelta, dP, dB, dC, part_dt, part_x, total; };
+//                   [W_dt transposed (R,D) io][W_x transposed (D,Mx) io]
+struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, rT, du, ddelta, dP, dB, dC, part_dt, part_x, WdtT, WxT, total; };
 ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
 {
     const Shape s = shape_of(p);
@@ -212,6 +241,8 @@ ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
         w.dC = take(s.B * s.N * s.L * sizeof(float));
         w.part_dt = take(s.B * s.D * s.R * sizeof(float));
         w.part_x = take(s.B * s.Mx * s.D * sizeof(float));
+        w.WdtT = take(s.R * s.D * s.esz);
+        w.WxT = take(s.D * s.Mx * s.esz);
     }
     w.total = off;
     return w;
@@ -303,7 +334,7 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
     // [r;B;C] = W_x @ u
     if (!gemm_rm(st, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16))
-        return SS_ERR_BACKEND;
+        return SS_ERR_LAUNCH;
     ss_fwd_params f = scan_params(p);
     f.u = u; f.delta = delta; f.z = p->z;
     f.Bmat = P + (size_t)R * L * s.esz;
@@ -334,7 +365,7 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     }
     // delta_raw = W_dt @ r
     if (!gemm_rm(st, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
-        return SS_ERR_BACKEND;
+        return SS_ERR_LAUNCH;
     return ss::scan_fwd_strided(&f, (long)Mx * L, stream);
 }
 
@@ -369,7 +400,7 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
     ss_conv_params c = conv_params(p, u);
     if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
     if (!gemm_rm(st, false, false, D, L, R, p->W_dt, R, 0, P, L, (long)Mx * L, 0.0f, delta, L, (long)D * L, B, bf16))
-        return SS_ERR_BACKEND;
+        return SS_ERR_LAUNCH;
 
     // the scan
     ss_bwd_params b{};
@@ -386,11 +417,17 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
     b.dA = q->dA; b.dD = q->dD; b.ddelta_bias = q->ddt_bias;
     if ((rc = ss::scan_bwd_strided(&b, (long)Mx * L, stream)) != SS_OK) return rc;
 
+    // The two products with a transposed weight take it from a transposed copy (a megabyte each), so
+    // that their first operand is contiguous along the contraction index like everywhere else.
+    char *WdtT = scratch + sc.WdtT, *WxT = scratch + sc.WxT;
+    if (!(bf16 ? transpose_weight<ss::bf16_t>(p->W_dt, WdtT, D, R, st) : transpose_weight<float>(p->W_dt, WdtT, D, R, st)) ||
+        !(bf16 ? transpose_weight<ss::bf16_t>(p->W_x, WxT, Mx, D, st) : transpose_weight<float>(p->W_x, WxT, Mx, D, st)))
+        return SS_ERR_LAUNCH;
     // delta_raw = W_dt @ r:  dr = W_dt^T @ ddelta  (rows 0..R-1 of dP),  dW_dt = sum_b ddelta r^T
-    if (!gemm_rm(st, true, false, R, L, D, p->W_dt, R, 0, ddelta, L, (long)D * L, 0.0f, dP, L, (long)Mx * L, B, bf16))
-        return SS_ERR_BACKEND;
+    if (!gemm_rm(st, false, false, R, L, D, WdtT, D, 0, ddelta, L, (long)D * L, 0.0f, dP, L, (long)Mx * L, B, bf16))
+        return SS_ERR_LAUNCH;
     if (!gemm_rm(st, false, true, D, R, L, ddelta, L, (long)D * L, P, L, (long)Mx * L, 0.0f, part_dt, R, (long)D * R, B, bf16, true))
-        return SS_ERR_BACKEND;
+        return SS_ERR_LAUNCH;
     // rows R.. of dP from the scan's float32 dB, dC
     {
         const long total = (long)B * 2 * N * L;
@@ -400,10 +437,10 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
         if (hipGetLastError() != hipSuccess) return SS_ERR_LAUNCH;
     }
     // [r;B;C] = W_x @ u:  du += W_x^T @ dP,  dW_x = sum_b dP u^T
-    if (!gemm_rm(st, true, false, D, L, Mx, p->W_x, D, 0, dP, L, (long)Mx * L, 1.0f, du, L, (long)D * L, B, bf16))
-        return SS_ERR_BACKEND;
+    if (!gemm_rm(st, false, false, D, L, Mx, WxT, Mx, 0, dP, L, (long)Mx * L, 1.0f, du, L, (long)D * L, B, bf16))
+        return SS_ERR_LAUNCH;
     if (!gemm_rm(st, false, true, Mx, D, L, dP, L, (long)Mx * L, u, L, (long)D * L, 0.0f, part_x, D, (long)Mx * D, B, bf16, true))
-        return SS_ERR_BACKEND;
+        return SS_ERR_LAUNCH;
     {
         const long n_dt = (long)D * R, n_x = (long)Mx * D;
         hipLaunchKernelGGL(sum_partials_kernel<float>, dim3((unsigned)((n_dt + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const float*>(part_dt), B, n_dt, q->dW_dt);
@@ -478,12 +515,32 @@ int ss_layer_step(const ss_layer_step_params* p, void* stream)
     int rc = ss_conv_step(&c, stream);
     if (rc != SS_OK) return rc;
     // [r;B;C]_t (B, Mx) = u_t (B, D) @ W_x^T;   delta_t (B, D) = r_t (B, R) @ W_dt^T
-    if (!gemm_rm(st, false, true, B, Mx, D, u_t, D, 0, p->W_x, D, 0, 0.0f, P_t, Mx, 0, 1, bf16)) return SS_ERR_BACKEND;
-    if (!gemm_rm(st, false, true, B, D, R, P_t, Mx, 0, p->W_dt, R, 0, 0.0f, delta_t, D, 0, 1, bf16)) return SS_ERR_BACKEND;
+    if (!gemm_rm(st, false, true, B, Mx, D, u_t, D, 0, p->W_x, D, 0, 0.0f, P_t, Mx, 0, 1, bf16)) return SS_ERR_LAUNCH;
+    if (!gemm_rm(st, false, true, B, D, R, P_t, Mx, 0, p->W_dt, R, 0, 0.0f, delta_t, D, 0, 1, bf16)) return SS_ERR_LAUNCH;
     s.delta_t = delta_t;
     s.B_t = P_t + (size_t)R * esz;
     s.C_t = P_t + (size_t)(R + N) * esz;
     return ss::step_strided(&s, Mx, stream);
+}
+
+int ss_proj_gemm(const ss_gemm_params* p, void* stream)
+{
+    if (!p) return SS_ERR_NULL;
+    if (p->M < 0 || p->N < 0 || p->K < 0 || p->batch < 0) return SS_ERR_SHAPE;
+    if (p->io_dtype != SS_F32 && p->io_dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+    if (p->flags & ~(SS_GEMM_C_FLOAT | SS_GEMM_ACCUMULATE | SS_GEMM_GENERAL)) return SS_ERR_UNSUPPORTED;
+    if (p->M == 0 || p->N == 0 || p->batch == 0) return SS_OK;
+    if (!p->C || (p->K > 0 && (!p->A || !p->B))) return SS_ERR_NULL;   // K = 0: an empty sum, A and B are not read
+    ss::GemmArgs g{};
+    g.M = p->M; g.N = p->N; g.K = p->K; g.batch = p->batch;
+    g.A = p->A; g.a_m = p->a_m; g.a_k = p->a_k; g.a_batch = p->a_batch;
+    g.B = p->B; g.b_k = p->b_k; g.b_n = p->b_n; g.b_batch = p->b_batch;
+    g.C = p->C; g.ldc = p->ldc; g.c_batch = p->c_batch;
+    g.bf16 = p->io_dtype == SS_BF16;
+    g.c_float = (p->flags & SS_GEMM_C_FLOAT) || !g.bf16;
+    g.accumulate = p->flags & SS_GEMM_ACCUMULATE;
+    g.general = p->flags & SS_GEMM_GENERAL;
+    return ss::gemm(g, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
         names |= set(re.findall(r"\b(ss_[a-z_]+)\s*\(", hdr))
     assert {"ss_scan_fwd", "ss_scan_bwd", "ss_step", "ss_workspace_bytes", "ss_strerror", "ss_version",
             "ss_conv_fwd", "ss_conv_bwd", "ss_conv_step", "ss_layer_fwd", "ss_layer_bwd", "ss_layer_step",
-            "ss_layer_saved_bytes", "ss_layer_scratch_bytes", "ss_layer_step_scratch_bytes"} <= names
+            "ss_layer_saved_bytes", "ss_layer_scratch_bytes", "ss_layer_step_scratch_bytes", "ss_proj_gemm"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -326,3 +326,22 @@ def test_static_scratch_forward_rejections():
     assert f(ctypes.byref(p), None) == B.SS_ERR_WORKSPACE
     hdr = open(os.path.join(ROOT, "include", "ss_scan.h")).read()
     assert "#define SS_STATIC_SCRATCH_BYTES (64u << 20)" in hdr
+
+
+def test_projection_product_rejections():
+    g = B.GemmParams()
+    call = lambda: B.lib().ss_proj_gemm(ctypes.byref(g), None)
+    assert B.lib().ss_proj_gemm(None, None) == B.SS_ERR_NULL
+    g.M, g.N, g.K, g.batch, g.io_dtype = 4, 4, 4, 1, B.SS_BF16
+    assert call() == B.SS_ERR_NULL                      # no operands
+    g.A = g.B = g.C = FAKE
+    g.M = -1
+    assert call() == B.SS_ERR_SHAPE
+    g.M = 4; g.io_dtype = 7
+    assert call() == B.SS_ERR_UNSUPPORTED
+    g.io_dtype = B.SS_BF16; g.flags = 8
+    assert call() == B.SS_ERR_UNSUPPORTED               # unknown flag
+    g.flags = 0; g.batch = 70000
+    assert call() == B.SS_ERR_UNSUPPORTED               # more batch entries than a launch takes
+    g.batch = 0
+    assert call() == B.SS_OK                            # nothing to do
