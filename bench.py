@@ -569,12 +569,17 @@ def main():
                     + [g for g in sets[0].grads.values() if g is not None])
 
     if args.copy_calibration:
+        # Two plain streaming kernels of known size for the traffic counters: the L2's read-request
+        # counter does not tell 64-byte from 128-byte requests, and these two issue one kind each
+        # (measured: the negation 128-byte requests, the narrowing copy 64-byte ones).
         a = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
+        c = torch.empty(48 * 1024 * 1024, dtype=torch.bfloat16, device=dev)
         torch.cuda.synchronize()
-        torch.neg(a, out=b)  # a plain streaming kernel: reads 256 MiB, writes 256 MiB
+        torch.neg(a, out=b)              # reads 256 MiB, writes 256 MiB
+        c.copy_(a[:48 * 1024 * 1024])    # reads 192 MiB, writes 96 MiB
         torch.cuda.synchronize()
-        del a, b
+        del a, b, c
 
     # Timed region: exactly K steps, bracketed by synchronisation; the library launches on torch's
     # current stream, so events recorded on that stream bracket the forward and the backward call.
