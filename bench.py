@@ -606,13 +606,13 @@ def main():
         # Dominant kernel: the backward scan (the backward call = zero-fill + scan + finalize; the scan
         # kernel is > 98 % of it).  Graded bound: HBM, algorithmic bytes of one backward launch over its
         # duration.  `traffic` is the launch's measured HBM bytes (rocprofv3 counters, kept in profiles/).
-        "roofline": {"bound": "hbm", "kernel": "scan_bwd_kernel",
+        "roofline": {"bound": "hbm", "kernel": "scan_bwd_dpp_kernel",
                      "achieved": bwd_b / (bwd_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": bwd_b / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": traffic.get("scan_bwd_kernel_hbm_bytes")},
         # The same launch against the vector ALU, which is what limits it: algorithmic flops (12
         # multiply-adds + 1 exponential per token, channel and state) against both fp32 vector peaks.
-        "alu_roofline": {"bound": "alu", "kernel": "scan_bwd_kernel", "achieved": bwd_flops / (bwd_ms * 1e-3) / 1e12,
+        "alu_roofline": {"bound": "alu", "kernel": "scan_bwd_dpp_kernel", "achieved": bwd_flops / (bwd_ms * 1e-3) / 1e12,
                          "unit": "TFLOP/s", "peak_unpacked_fp32": VALU_PEAK_TFLOPS,
                          "frac_of_unpacked_peak": bwd_flops / (bwd_ms * 1e-3) / 1e12 / VALU_PEAK_TFLOPS,
                          "peak_published_packed_fp32": VALU_PEAK_PUBLISHED_TFLOPS,

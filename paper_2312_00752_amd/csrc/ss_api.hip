@@ -450,7 +450,7 @@ int step_strided(const ss_step_params* p, long bc_stride, void* stream)
 
 int step_projected(const ss_step_params* p, const float* P, const void* W_dt, int R, int ldp, void* stream)
 {
-    if (!P || !W_dt) return SS_ERR_NULL;
+    if (!p || !P || !W_dt) return SS_ERR_NULL;
     if (p->io_dtype != SS_BF16 || R > 256 || p->dstate > 16 || ldp > 256 + 2 * 16) return SS_ERR_UNSUPPORTED;
     return step_impl(p, 0, P, W_dt, R, ldp, stream);
 }
