@@ -54,7 +54,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));   // MFMA operand a
 // has to cover the previous chunk's stores.
 template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false,
           int FUSED_KS = 0, int SPL = STATES_PER_LANE, bool PAT = false>
-__global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS == 0) ? 2 : 1) scan_fwd_kernel(const FwdArgs a)
+__global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS <= 4) ? 2 : 1) scan_fwd_kernel(const FwdArgs a)
 {
     static_assert(!PAT || (VEC && BCFIX == 0 && !CPLX && !STAGED), "PAT: vector path, real state, selective B and C");
     constexpr int NGC = CHUNK_T / GROUP_T;
@@ -267,7 +267,7 @@ __global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS == 0) ? 2 : 
     // ones), so the traffic of an even chunk and the odd one after it (segments start at even
     // chunks) is issued together: both chunks' inputs are requested in the odd chunk's phase A, tensor
     // by tensor, and the even chunk's results wait in registers for the odd chunk's.
-    constexpr bool PAIR = PAT && sizeof(T) == 2 && FUSED_KS == 0 && PF == 2;
+    constexpr bool PAIR = PAT && sizeof(T) == 2 && PF == 2;
     auto issue_pair = [&](int c0) {   // chunks c0 (slot 0) and c0 + 1 (slot 1)
       if constexpr (PAIR) {
         uint32_t off[2], boff[2];
@@ -280,7 +280,7 @@ __global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS == 0) ? 2 : 
             boff[s] = (ts < L && c < c_end) ? bc_row_off + (uint32_t)ts * (uint32_t)sizeof(T) : BUF_OFF;
         }
         ru_[0] = io8<T>::load_buf(bu, off[0]); ru_[1] = io8<T>::load_buf(bu, off[1]);
-        rd_[0] = io8<T>::load_buf(bd, off[0]); rd_[1] = io8<T>::load_buf(bd, off[1]);
+        if constexpr (FUSED_KS == 0) { rd_[0] = io8<T>::load_buf(bd, off[0]); rd_[1] = io8<T>::load_buf(bd, off[1]); }
         rz_[0] = io8<T>::load_buf(bz, off[0]); rz_[1] = io8<T>::load_buf(bz, off[1]);
         rp_[0] = io8<T>::load_buf(bp, off[0]); rp_[1] = io8<T>::load_buf(bp, off[1]);
         rbc_[0] = io4<T>::load_buf(bbc, boff[0]); rbc_[1] = io4<T>::load_buf(bbc, boff[1]);

@@ -198,8 +198,8 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(const bf16_t* __restrict__
     f32x4_t acc[MAXST];
 #pragma unroll
     for (int ct = 0; ct < MAXST; ++ct) acc[ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    // one named set of registers per slot, and the step written out per slot (a macro): register
-    // sets reached through references or indexed arrays are left in scratch memory by the compiler
+    // one named set of registers per slot, and the step written out per slot (a macro), so that every
+    // register set is addressed statically
     u32x4 sr0[5], sr1[5], sr2[5], sr3[5];
     uint4 ar0[2], ar1[2], ar2[2], ar3[2];
 #define SS_NT_ISSUE(s_, SR, AR)                                          \
@@ -271,10 +271,17 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict
     const int xp = tid >> 3, xo = tid & 7;   // pair of rows, group of eight columns
     const bf16_t* __restrict__ xrow = X + b * x_batch + (long)(2 * xp) * x_ld + n0 + 8 * xo;
     const int ST = S >> 4;
+    // The four waves split the S x 64 tile two by two: wave (wv, wc) has half of the output's row tiles and
+    // column tiles 2 wc, 2 wc + 1, so that every weight fragment read from LDS feeds two MFMAs (with a wave
+    // per column tile each wave read the whole weight slab and LDS was the limit: 78 -> 68 us).  The same
+    // split of gemm_nt_kernel doubles its global fragment loads and registers and measured slower (61 -> 88 us).
+    const int wv = w >> 1, wc = w & 1;
+    const int RH = (ST + 1) >> 1;
+    constexpr int MAXRH = MAXST / 2;
     const int nsteps = K / KSLAB;
-    f32x4_t acc[MAXST];
+    f32x4_t acc[MAXRH][2];
 #pragma unroll
-    for (int rt = 0; rt < MAXST; ++rt) acc[rt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int ri = 0; ri < MAXRH; ++ri) acc[ri][0] = acc[ri][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     u32x4 wr0[5], wr1[5], wr2[5], wr3[5];   // one named set of registers per slot, steps written out (see gemm_nt_kernel)
     uint4 xr0[2], xr1[2], xr2[2], xr3[2];
 #define SS_ROWS_ISSUE(s_, WR, XR)                                        \
@@ -297,12 +304,14 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict
         SS_ROWS_ISSUE((s_) + PD, WR, XR) /* this slot's slab went into LDS a step ago */                              \
         _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                                              \
         {                                                                                                             \
-            const uint32_t* xq = &Xp[BUF][16 * ks + 4 * g][16 * w + j];                                               \
-            const uint4 bf = make_uint4(xq[0], xq[XPITCH], xq[2 * XPITCH], xq[3 * XPITCH]);                           \
-            _Pragma("unroll") for (int rt = 0; rt < MAXST; ++rt) if (rt < ST)                                         \
+            const uint32_t* xq = &Xp[BUF][16 * ks + 4 * g][32 * wc + j];                                              \
+            const uint4 bf0 = make_uint4(xq[0], xq[XPITCH], xq[2 * XPITCH], xq[3 * XPITCH]);                          \
+            const uint4 bf1 = make_uint4(xq[16], xq[XPITCH + 16], xq[2 * XPITCH + 16], xq[3 * XPITCH + 16]);          \
+            _Pragma("unroll") for (int ri = 0; ri < MAXRH; ++ri) if (ri < RH && wv * RH + ri < ST)                    \
             {                                                                                                         \
-                const uint4 af = *reinterpret_cast<const uint4*>(&Ws[BUF][16 * rt + j][32 * ks + 8 * g]);             \
-                acc[rt] = mfma_bf16(af, bf, acc[rt]);                                                                 \
+                const uint4 af = *reinterpret_cast<const uint4*>(&Ws[BUF][16 * (wv * RH + ri) + j][32 * ks + 8 * g]); \
+                acc[ri][0] = mfma_bf16(af, bf0, acc[ri][0]);                                                          \
+                acc[ri][1] = mfma_bf16(af, bf1, acc[ri][1]);                                                          \
             }                                                                                                         \
         }                                                                                                             \
         if ((s_) + 1 < nsteps) SS_ROWS_FILL((BUF) ^ 1, WRN, XRN)                                                      \
@@ -327,12 +336,15 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict
 #undef SS_ROWS_STEP
 #undef SS_ROWS_FILL
 #undef SS_ROWS_ISSUE
-    bf16_t* __restrict__ o = Out + b * o_batch + n0 + 16 * w + j;
+    bf16_t* __restrict__ o = Out + b * o_batch + n0 + 32 * wc + j;
 #pragma unroll
-    for (int rt = 0; rt < MAXST; ++rt)
-        if (rt < ST) {
+    for (int ri = 0; ri < MAXRH; ++ri)
+        if (ri < RH && wv * RH + ri < ST) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[(long)(16 * rt + 4 * g + i) * o_ld] = bf16_t(f32_to_bf16_bits(acc[rt][i]));
+            for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    o[(long)(16 * (wv * RH + ri) + 4 * g + i) * o_ld + 16 * c2] = bf16_t(f32_to_bf16_bits(acc[ri][c2][i]));
         }
 }
 
