@@ -349,17 +349,17 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict
 }
 
 // Out (M x N per batch entry, bf16) [+]= W (M x K, contiguous along K) Y (K x N, contiguous along N).
-// grid (N / 64, M / (64 * MT), batch).  K % 32 == 0, K <= 160, N % 64 == 0, M % (64 * MT) == 0.
-constexpr int COLS_MT = 4;   // 64-row tiles of the result per workgroup (the small operand is prepared once for all)
+// grid (N / 64, M / (64 * mtiles), batch), mtiles = 64-row tiles of the result per workgroup (the small operand is
+// prepared once for all of them).  K % 32 == 0, K <= 160, N % 64 == 0, M % (64 * mtiles) == 0.
 __global__ void __launch_bounds__(256) gemm_cols_kernel(const bf16_t* __restrict__ W, long w_ld, const bf16_t* __restrict__ Y,
                                                          long y_ld, long y_batch, bf16_t* __restrict__ Out, long o_ld, long o_batch,
-                                                         int K, int accumulate)
+                                                         int K, int accumulate, int mtiles)
 {
     __shared__ __attribute__((aligned(16))) uint32_t Yp[MAXST * 8][XPITCH];        // pairs of contraction indices x 64 columns
-    __shared__ __attribute__((aligned(16))) float Os[64][64 + 4];                 // a tile of the result on its way out
+    __shared__ __attribute__((aligned(16))) float Os[64][64 + 4];                 // a tile of the result on its way out (two of them, one barrier per tile: slower, 71 -> 76 us)
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
     const int n0 = blockIdx.x * 64;
-    const int m_base = blockIdx.y * 64 * COLS_MT;
+    const int m_base = blockIdx.y * 64 * mtiles;
     const long b = blockIdx.z;
     const bf16_t* __restrict__ y = Y + b * y_batch + n0;
     const int KS = K >> 5;   // 32-wide contraction steps (<= 5)
@@ -391,12 +391,12 @@ __global__ void __launch_bounds__(256) gemm_cols_kernel(const bf16_t* __restrict
     for (int ks = 0; ks < MAXST / 2; ++ks)
         if (ks < KS) wf[ks] = *reinterpret_cast<const uint4*>(wrow + 32 * ks);
     bf16_t* __restrict__ o = Out + b * o_batch + n0;
-    for (int mt = 0; mt < COLS_MT; ++mt) {
+    for (int mt = 0; mt < mtiles; ++mt) {
         const int m0 = m_base + 64 * mt;
         uint4 wc[MAXST / 2];
 #pragma unroll
         for (int ks = 0; ks < MAXST / 2; ++ks) wc[ks] = wf[ks];
-        if (mt + 1 < COLS_MT) {
+        if (mt + 1 < mtiles) {
 #pragma unroll
             for (int ks = 0; ks < MAXST / 2; ++ks)
                 if (ks < KS) wf[ks] = *reinterpret_cast<const uint4*>(wrow + (long)64 * (mt + 1) * w_ld + 32 * ks);
@@ -472,10 +472,17 @@ int launch_fast(const GemmArgs& g, hipStream_t stream)
                                g.a_batch, B, g.b_k, g.b_batch, C, g.ldc, g.c_batch, g.M, g.K);
             return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_LAUNCH;
         }
-        if (g.K % 32 == 0 && g.K <= MAXST * 16 && g.M % (64 * COLS_MT) == 0 && g.M / (64 * COLS_MT) <= 65535 && g.a_batch == 0) {
-            hipLaunchKernelGGL(gemm_cols_kernel, dim3((unsigned)(g.N / 64), (unsigned)(g.M / (64 * COLS_MT)), (unsigned)g.batch),
-                               dim3(256), 0, stream, A, g.a_m, B, g.b_k, g.b_batch, C, g.ldc, g.c_batch, g.K, g.accumulate ? 1 : 0);
-            return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_LAUNCH;
+        if (g.K % 32 == 0 && g.K <= MAXST * 16 && g.M % 64 == 0 && g.a_batch == 0) {
+            // as many 64-row tiles per workgroup as divide M, up to 16, while the launch keeps >= 1024 workgroups
+            int mtiles = 1;
+            const long cols = (long)(g.N / 64) * g.batch;
+            for (int c = 16; c > 1; c >>= 1)
+                if ((g.M / 64) % c == 0 && cols * (g.M / 64 / c) >= 1024) { mtiles = c; break; }
+            if (g.M / (64 * mtiles) <= 65535) {
+                hipLaunchKernelGGL(gemm_cols_kernel, dim3((unsigned)(g.N / 64), (unsigned)(g.M / (64 * mtiles)), (unsigned)g.batch),
+                                   dim3(256), 0, stream, A, g.a_m, B, g.b_k, g.b_batch, C, g.ldc, g.c_batch, g.K, g.accumulate ? 1 : 0, mtiles);
+                return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_LAUNCH;
+            }
         }
     }
     return SS_ERR_UNSUPPORTED;
