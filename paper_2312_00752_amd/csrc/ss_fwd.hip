@@ -311,7 +311,9 @@ __global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS <= 4) ? 2 : 
         const typename io8<T>::raw ru = ru_[SLOT], rd = rd_[SLOT], rz = rz_[SLOT];
         const typename io4<T>::raw rbc = rbc_[SLOT];
         float p8[SLICE];
-        if constexpr (VEC) io8<T>::unpack(rp_[SLOT], p8);
+        if constexpr (VEC) {
+            if (acc_on) io8<T>::unpack(rp_[SLOT], p8);   // uniform: only with more than 16 states
+        }
         if constexpr (PAT) {
             float bc4[GROUP_T];
             io4<T>::unpack(rbc, bc4);
@@ -330,11 +332,16 @@ __global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS <= 4) ? 2 : 
         if (has_z) io8<T>::unpack(rz, z8);
         {
             float dt8[SLICE], du8[SLICE];
+            // PAT without the in-kernel projection: a slice is whole or empty, and an empty one was read as
+            // zeros; a bias of -1e30 (0 without softplus) then makes its step sizes exactly 0, the identity of
+            // the recurrence, without a select per element
+            constexpr bool ZERO_BY_BIAS = PAT && FUSED_KS == 0;
+            const float bias_e = !ZERO_BY_BIAS || nv == SLICE ? bias : (softplus ? -1e30f : 0.0f);
 #pragma unroll
             for (int j = 0; j < SLICE; ++j) {
-                float x = v8[j] + bias, sp, sg;
+                float x = v8[j] + bias_e, sp, sg;
                 if (softplus) softplus_sigmoid(x, sp, sg); else sp = x;
-                sp = (j < nv) ? sp : 0.0f;
+                if constexpr (!ZERO_BY_BIAS) sp = (j < nv) ? sp : 0.0f;
                 dt8[j] = sp;
                 du8[j] = ZOH ? u8[j] : sp * u8[j];
                 if (AGG) sum_dt += sp;
@@ -506,9 +513,11 @@ __global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS <= 4) ? 2 : 
                 y8[4] += p1.x; y8[5] += p1.y; y8[6] += p1.z; y8[7] += p1.w;
             }
             const int nvs = p_ok ? nv : 0;
-            if constexpr (VEC) {   // states beyond the first 16: add to what the earlier groups left (zeros otherwise)
+            if constexpr (VEC) {   // states beyond the first 16: add to what the earlier groups left
+                if (acc_on) {
 #pragma unroll
-                for (int j = 0; j < SLICE; ++j) y8[j] += p8[j];
+                    for (int j = 0; j < SLICE; ++j) y8[j] += p8[j];
+                }
             } else if (a.acc_y) {
                 const T* prev = (has_z ? static_cast<const T*>(a.ysave) : static_cast<const T*>(a.out)) + prow * L + t0;
                 io8<T>::unpack(io8<T>::template load<VEC>(prev, nvs), p8);
