@@ -117,7 +117,11 @@ int ss_layer_step(const ss_layer_step_params *p, void *stream);
  * contraction index with a float32 result) run on matrix-core kernels when sizes are multiples of
  * 64 (rows / columns of the big side), 16 (the small side, at most 160) and pointers and strides
  * are multiples of 16 bytes; everything else, and every call with SS_GEMM_GENERAL, runs on a
- * general kernel.  Device pointers; C must not overlap A or B.  SS_OK, SS_ERR_NULL,
+ * general kernel.  `workspace` is optional device memory (256-byte aligned) that the call may
+ * overwrite: with ss_proj_gemm_workspace_bytes(p) bytes of it, a product of the first shape with
+ * fewer than 512 column tiles x batch entries and K >= 4096, a multiple of 512, splits its
+ * contraction over two workgroups per tile (float32 shares, summed by a second kernel); the
+ * result may then differ from the unsplit one in the last bf16 digit.  Device pointers; C must not overlap A or B.  SS_OK, SS_ERR_NULL,
  * SS_ERR_SHAPE (negative size), SS_ERR_UNSUPPORTED (dtype, unknown flag, more than 65535 batch
  * entries or 64-row tiles) or SS_ERR_LAUNCH. */
 #define SS_GEMM_C_FLOAT    1u
@@ -133,8 +137,13 @@ typedef struct {
     int64_t b_k, b_n, b_batch;
     void *C;
     int64_t ldc, c_batch;
+    void *workspace;            /* optional, see above; NULL: never split                        */
+    size_t workspace_bytes;
 } ss_gemm_params;
 int ss_proj_gemm(const ss_gemm_params *p, void *stream);
+/* Bytes of workspace with which ss_proj_gemm may split the contraction of *p (reads M, N, batch;
+ * 0 for a NULL or negative-size argument).  Smaller or absent workspaces are valid: no split. */
+size_t ss_proj_gemm_workspace_bytes(const ss_gemm_params *p);
 
 #ifdef __cplusplus
 }

@@ -92,7 +92,8 @@ class GemmParams(ctypes.Structure):
                 ("io_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
                 ("A", _vp), ("a_m", ctypes.c_int64), ("a_k", ctypes.c_int64), ("a_batch", ctypes.c_int64),
                 ("B", _vp), ("b_k", ctypes.c_int64), ("b_n", ctypes.c_int64), ("b_batch", ctypes.c_int64),
-                ("C", _vp), ("ldc", ctypes.c_int64), ("c_batch", ctypes.c_int64)]
+                ("C", _vp), ("ldc", ctypes.c_int64), ("c_batch", ctypes.c_int64),
+                ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t)]
 
 
 SS_GEMM_C_FLOAT, SS_GEMM_ACCUMULATE, SS_GEMM_GENERAL = 1, 2, 4
@@ -142,6 +143,8 @@ def lib():
         l.ss_strerror.restype = ctypes.c_char_p
         l.ss_proj_gemm.argtypes = [ctypes.POINTER(GemmParams), _vp]
         l.ss_proj_gemm.restype = ctypes.c_int
+        l.ss_proj_gemm_workspace_bytes.argtypes = [ctypes.POINTER(GemmParams)]
+        l.ss_proj_gemm_workspace_bytes.restype = ctypes.c_size_t
         l.ss_strerror.argtypes = [ctypes.c_int]
         l.ss_version.restype = ctypes.c_int
         l.ss_version.argtypes = []
@@ -598,11 +601,13 @@ def ss_layer_bwd(dout, x, z, conv_w, conv_b, W_x, W_dt, dt_bias, A, Dskip, scrat
     return g
 
 
-def ss_proj_gemm(A, B, C, trans_a=False, trans_b=False, accumulate=False, general=False, stream=None):
+def ss_proj_gemm(A, B, C, trans_a=False, trans_b=False, accumulate=False, general=False, stream=None, workspace=None):
     """C[i] = op(A[i]) @ op(B[i]) (+ C[i]) on the layer's projection kernels.  A, B, C are 2-D or
     3-D (leading batch axis) tensors whose last axis is contiguous; a 2-D operand is shared by all
     batch entries.  ``trans_a`` / ``trans_b``: the operand is stored transposed ((K, M) / (N, K)).
-    C is float32 or of the operands' dtype."""
+    C is float32 or of the operands' dtype.  ``workspace``: optional uint8 device tensor of
+    ``ss_proj_gemm_workspace_bytes(C)`` bytes that lets a product with few rows and columns split its
+    contraction across workgroups."""
     import torch
     def view(t):
         if t.stride(-1) != 1:
@@ -639,7 +644,19 @@ def ss_proj_gemm(A, B, C, trans_a=False, trans_b=False, accumulate=False, genera
     for t in (A, B, C):
         if not t.is_cuda:
             raise ValueError("device tensors expected")
+    if workspace is not None:
+        if not workspace.is_cuda:
+            raise ValueError("device tensors expected")
+        p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     rc = lib().ss_proj_gemm(ctypes.byref(p), _stream(stream))
     if rc != SS_OK:
         raise SsError(rc)
     return C
+
+
+def ss_proj_gemm_workspace_bytes(C):
+    """Bytes of workspace with which ``ss_proj_gemm`` may split the contraction of a product with result ``C``."""
+    p = GemmParams()
+    p.M, p.N = C.shape[-2], C.shape[-1]
+    p.batch = C.shape[0] if C.dim() == 3 else 1
+    return int(lib().ss_proj_gemm_workspace_bytes(ctypes.byref(p)))

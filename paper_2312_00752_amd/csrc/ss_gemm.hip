@@ -174,6 +174,8 @@ __device__ __forceinline__ void pair_rows(uint4 lo, uint4 hi, uint4& out0, uint4
 // of the L2.  Requests past the last slab re-read the last slab (never used) instead of branching, so
 // that the compiler's wait counts stay those of the steady state.
 constexpr int PD = 4;
+constexpr long ROWS_MIN_WGS = 512;   // two workgroups of gemm_rows_kernel fit on each of the 256 CUs
+constexpr int ROWS_MIN_SPLIT_K = 4096;   // shorter contractions lose more to the second launch than they gain (K = 1536: 21 -> 25 us)
 __device__ __forceinline__ uint4 load16_stream(const bf16_t* p)
 {
     const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
@@ -257,19 +259,25 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(const bf16_t* __restrict__
 }
 
 // Out (S x N per batch entry, bf16) = W (S x K, contiguous along K) X (K x N, contiguous along N).
-// grid (N / 64, batch).  K % (64 * PD) == 0, N % 64 == 0, S % 16 == 0, S <= 160.
+// grid (N / 64, batch, parts).  K % (64 * PD * parts) == 0, N % 64 == 0, S % 16 == 0, S <= 160.
+// With parts > 1 workgroup (., ., z) contracts over the z-th part of K and leaves its float32 share in
+// Part[z][batch entry][S][N] for rows_reduce_kernel: a product with few columns would otherwise put a single
+// workgroup on a CU, with nothing to run while that one waits at its barrier.
 __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict__ W, long w_ld, long w_batch,
                                                          const bf16_t* __restrict__ X, long x_ld, long x_batch,
-                                                         bf16_t* __restrict__ Out, long o_ld, long o_batch, int S, int K)
+                                                         bf16_t* __restrict__ Out, long o_ld, long o_batch, int S, int K,
+                                                         float* __restrict__ Part)
 {
     __shared__ __attribute__((aligned(16))) bf16_t Ws[2][MAXST * 16][KP];
     __shared__ __attribute__((aligned(16))) uint32_t Xp[2][KSLAB / 2][XPITCH];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
     const int n0 = blockIdx.x * 64;
     const long b = blockIdx.y;
-    const bf16_t* __restrict__ wm = W + b * w_batch;
+    const int kper = K / (int)gridDim.z;
+    const long kbase = (long)blockIdx.z * kper;
+    const bf16_t* __restrict__ wm = W + b * w_batch + kbase;
     const int xp = tid >> 3, xo = tid & 7;   // pair of rows, group of eight columns
-    const bf16_t* __restrict__ xrow = X + b * x_batch + (long)(2 * xp) * x_ld + n0 + 8 * xo;
+    const bf16_t* __restrict__ xrow = X + b * x_batch + (kbase + 2 * xp) * x_ld + n0 + 8 * xo;
     const int ST = S >> 4;
     // The four waves split the S x 64 tile two by two: wave (wv, wc) has half of the output's row tiles and
     // column tiles 2 wc, 2 wc + 1, so that every weight fragment read from LDS feeds two MFMAs (with a wave
@@ -278,7 +286,7 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict
     const int wv = w >> 1, wc = w & 1;
     const int RH = (ST + 1) >> 1;
     constexpr int MAXRH = MAXST / 2;
-    const int nsteps = K / KSLAB;
+    const int nsteps = kper / KSLAB;
     f32x4_t acc[MAXRH][2];
 #pragma unroll
     for (int ri = 0; ri < MAXRH; ++ri) acc[ri][0] = acc[ri][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -336,6 +344,19 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict
 #undef SS_ROWS_STEP
 #undef SS_ROWS_FILL
 #undef SS_ROWS_ISSUE
+    if (gridDim.z > 1) {
+        const long ncols = (long)gridDim.x * 64;
+        float* __restrict__ pp = Part + ((long)blockIdx.z * gridDim.y + b) * S * ncols + n0 + 32 * wc + j;
+#pragma unroll
+        for (int ri = 0; ri < MAXRH; ++ri)
+            if (ri < RH && wv * RH + ri < ST) {
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pp[(long)(16 * (wv * RH + ri) + 4 * g + i) * ncols + 16 * c2] = acc[ri][c2][i];
+            }
+        return;
+    }
     bf16_t* __restrict__ o = Out + b * o_batch + n0 + 32 * wc + j;
 #pragma unroll
     for (int ri = 0; ri < MAXRH; ++ri)
@@ -346,6 +367,34 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const bf16_t* __restrict
                 for (int i = 0; i < 4; ++i)
                     o[(long)(16 * (wv * RH + ri) + 4 * g + i) * o_ld + 16 * c2] = bf16_t(f32_to_bf16_bits(acc[ri][c2][i]));
         }
+}
+
+// Out[b][row][8 c ..+7] (bf16) = sum over the parts of Part[part][b][row][8 c ..+7]; one thread per eight columns.
+__global__ void __launch_bounds__(256) rows_reduce_kernel(const float* __restrict__ Part, int parts, long part_stride,
+                                                           bf16_t* __restrict__ Out, long o_ld, long o_batch, int S, int ncols,
+                                                           long items)
+{
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= items) return;
+    const int per_row = ncols >> 3;
+    const int c8 = (int)(idx % per_row);
+    const long br = idx / per_row;
+    const int row = (int)(br % S);
+    const long b = br / S;
+    const float* __restrict__ src = Part + br * ncols + 8 * c8;
+    float4 lo = *reinterpret_cast<const float4*>(src), hi = *reinterpret_cast<const float4*>(src + 4);
+    for (int z = 1; z < parts; ++z) {
+        const float4 l2 = *reinterpret_cast<const float4*>(src + z * part_stride);
+        const float4 h2 = *reinterpret_cast<const float4*>(src + z * part_stride + 4);
+        lo.x += l2.x; lo.y += l2.y; lo.z += l2.z; lo.w += l2.w;
+        hi.x += h2.x; hi.y += h2.y; hi.z += h2.z; hi.w += h2.w;
+    }
+    uint4 o;
+    o.x = f32_to_bf16_bits(lo.x) | ((uint32_t)f32_to_bf16_bits(lo.y) << 16);
+    o.y = f32_to_bf16_bits(lo.z) | ((uint32_t)f32_to_bf16_bits(lo.w) << 16);
+    o.z = f32_to_bf16_bits(hi.x) | ((uint32_t)f32_to_bf16_bits(hi.y) << 16);
+    o.w = f32_to_bf16_bits(hi.z) | ((uint32_t)f32_to_bf16_bits(hi.w) << 16);
+    *reinterpret_cast<uint4*>(Out + b * o_batch + (long)row * o_ld + 8 * c8) = o;
 }
 
 // Out (M x N per batch entry, bf16) [+]= W (M x K, contiguous along K) Y (K x N, contiguous along N).
@@ -468,8 +517,18 @@ int launch_fast(const GemmArgs& g, hipStream_t stream)
         mult8(g.a_batch) && mult8(g.b_batch) && mult8(g.ldc) && mult8(g.c_batch)) {
         bf16_t* C = static_cast<bf16_t*>(g.C);
         if (!g.accumulate && g.M % 16 == 0 && g.M <= MAXST * 16 && g.K % (KSLAB * PD) == 0) {
-            hipLaunchKernelGGL(gemm_rows_kernel, dim3((unsigned)(g.N / 64), (unsigned)g.batch), dim3(256), 0, stream, A, g.a_m,
-                               g.a_batch, B, g.b_k, g.b_batch, C, g.ldc, g.c_batch, g.M, g.K);
+            // fewer than two workgroups per CU: two parts if the workspace holds two float32 shares (headline shape: 66 -> 57 us both launches together; four parts measured slower)
+            const long wgs = (long)(g.N / 64) * g.batch;
+            const size_t share = (size_t)g.batch * g.M * g.N * sizeof(float);
+            const int parts = (wgs < ROWS_MIN_WGS && g.K >= ROWS_MIN_SPLIT_K && g.K % (KSLAB * PD * 2) == 0 && g.split_ws && 2 * share <= g.split_ws_bytes) ? 2 : 1;
+            hipLaunchKernelGGL(gemm_rows_kernel, dim3((unsigned)(g.N / 64), (unsigned)g.batch, (unsigned)parts), dim3(256), 0, stream,
+                               A, g.a_m, g.a_batch, B, g.b_k, g.b_batch, C, g.ldc, g.c_batch, g.M, g.K, static_cast<float*>(g.split_ws));
+            if (parts > 1) {
+                const long items = (long)g.batch * g.M * (g.N / 8);
+                hipLaunchKernelGGL(rows_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream,
+                                   static_cast<const float*>(g.split_ws), parts, (long)g.batch * g.M * g.N, C, g.ldc, g.c_batch, g.M,
+                                   g.N, items);
+            }
             return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_LAUNCH;
         }
         if (g.K % 32 == 0 && g.K <= MAXST * 16 && g.M % 64 == 0 && g.a_batch == 0) {

@@ -132,6 +132,10 @@ struct GemmArgs {
     void* C; long ldc, c_batch;
     bool bf16, c_float, accumulate;
     bool general;   // take the general kernel even where a matrix-core kernel fits (for verification)
+    // optional device memory for float32 shares of the result (up to 4 * batch * M * N floats are used): lets a
+    // product with few output rows and few columns split its contraction across workgroups
+    void* split_ws;
+    size_t split_ws_bytes;
 };
 int gemm(const GemmArgs& g, hipStream_t stream);
 }  // namespace ss

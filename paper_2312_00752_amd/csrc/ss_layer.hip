@@ -22,7 +22,8 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // row pitches lda/ldb/ldc of the stored matrices and element strides sA/sB/sC between batch
 // entries; C is float32 if c_float, else in the io dtype.
 bool gemm_rm(hipStream_t st, bool tA, bool tB, int M, int N, int K, const void* A, int lda, long sA,
-             const void* B, int ldb, long sB, float beta, void* C, int ldc, long sC, int batch, bool bf16, bool c_float = false)
+             const void* B, int ldb, long sB, float beta, void* C, int ldc, long sC, int batch, bool bf16, bool c_float = false,
+             void* split_ws = nullptr, size_t split_ws_bytes = 0)
 {
     ss::GemmArgs g{};
     g.M = M; g.N = N; g.K = K; g.batch = batch;
@@ -30,6 +31,7 @@ bool gemm_rm(hipStream_t st, bool tA, bool tB, int M, int N, int K, const void* 
     g.B = B; g.b_k = tB ? 1 : ldb; g.b_n = tB ? ldb : 1; g.b_batch = sB;
     g.C = C; g.ldc = ldc; g.c_batch = sC;
     g.bf16 = bf16; g.c_float = c_float || !bf16; g.accumulate = beta != 0.0f;
+    g.split_ws = split_ws; g.split_ws_bytes = split_ws_bytes;
     return ss::gemm(g, st) == SS_OK;
 }
 
@@ -217,7 +219,8 @@ SavedLayout saved_layout(const ss_layer_params* p)
 //          backward [u][delta][du][ddelta][dP (B,Mx,L) io][dB, dC (B,N,L) f32]
 //                   [partials of dW_dt (B,D,R) f32][partials of dW_x (B,Mx,D) f32]
 //                   [W_dt transposed (R,D) io][W_x transposed (D,Mx) io]
-struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, rT, du, ddelta, dP, dB, dC, part_dt, part_x, WdtT, WxT, total; };
+//          both     [float32 shares of a projection whose contraction is split across workgroups (B,Mx,L) x 2]
+struct ScratchLayout { size_t u, delta, P, scan_ws, scan_ws_bytes, rT, du, ddelta, dP, dB, dC, part_dt, part_x, WdtT, WxT, gsplit, gsplit_bytes, total; };
 ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
 {
     const Shape s = shape_of(p);
@@ -244,6 +247,8 @@ ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
         w.WdtT = take(s.R * s.D * s.esz);
         w.WxT = take(s.D * s.Mx * s.esz);
     }
+    w.gsplit_bytes = 2 * s.B * s.Mx * s.L * sizeof(float);
+    w.gsplit = take(w.gsplit_bytes);
     w.total = off;
     return w;
 }
@@ -333,7 +338,8 @@ int ss_layer_fwd(const ss_layer_params* p, void* stream)
     }
     if ((rc = ss_conv_fwd(&c, stream)) != SS_OK) return rc;
     // [r;B;C] = W_x @ u
-    if (!gemm_rm(st, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16))
+    if (!gemm_rm(st, false, false, Mx, L, D, p->W_x, D, 0, u, L, (long)D * L, 0.0f, P, L, (long)Mx * L, B, bf16, false,
+                 scratch + sc.gsplit, sc.gsplit_bytes))
         return SS_ERR_LAUNCH;
     ss_fwd_params f = scan_params(p);
     f.u = u; f.delta = delta; f.z = p->z;
@@ -424,7 +430,8 @@ int ss_layer_bwd(const ss_layer_bwd_params* q, void* stream)
         !(bf16 ? transpose_weight<ss::bf16_t>(p->W_x, WxT, Mx, D, st) : transpose_weight<float>(p->W_x, WxT, Mx, D, st)))
         return SS_ERR_LAUNCH;
     // delta_raw = W_dt @ r:  dr = W_dt^T @ ddelta  (rows 0..R-1 of dP),  dW_dt = sum_b ddelta r^T
-    if (!gemm_rm(st, false, false, R, L, D, WdtT, D, 0, ddelta, L, (long)D * L, 0.0f, dP, L, (long)Mx * L, B, bf16))
+    if (!gemm_rm(st, false, false, R, L, D, WdtT, D, 0, ddelta, L, (long)D * L, 0.0f, dP, L, (long)Mx * L, B, bf16, false,
+                 scratch + sc.gsplit, sc.gsplit_bytes))
         return SS_ERR_LAUNCH;
     if (!gemm_rm(st, false, true, D, R, L, ddelta, L, (long)D * L, P, L, (long)Mx * L, 0.0f, part_dt, R, (long)D * R, B, bf16, true))
         return SS_ERR_LAUNCH;
@@ -540,7 +547,17 @@ int ss_proj_gemm(const ss_gemm_params* p, void* stream)
     g.c_float = (p->flags & SS_GEMM_C_FLOAT) || !g.bf16;
     g.accumulate = p->flags & SS_GEMM_ACCUMULATE;
     g.general = p->flags & SS_GEMM_GENERAL;
+    if (p->workspace && aligned_to(p->workspace, 256)) {
+        g.split_ws = p->workspace;
+        g.split_ws_bytes = p->workspace_bytes;
+    }
     return ss::gemm(g, static_cast<hipStream_t>(stream));
+}
+
+size_t ss_proj_gemm_workspace_bytes(const ss_gemm_params* p)
+{
+    if (!p || p->M < 0 || p->N < 0 || p->batch < 0) return 0;
+    return 2 * (size_t)p->batch * (size_t)p->M * (size_t)p->N * sizeof(float);
 }
 
 }  // extern "C"

@@ -20,7 +20,8 @@ def test_library_exports_every_declared_symbol():
         names |= set(re.findall(r"\b(ss_[a-z_]+)\s*\(", hdr))
     assert {"ss_scan_fwd", "ss_scan_bwd", "ss_step", "ss_workspace_bytes", "ss_strerror", "ss_version",
             "ss_conv_fwd", "ss_conv_bwd", "ss_conv_step", "ss_layer_fwd", "ss_layer_bwd", "ss_layer_step",
-            "ss_layer_saved_bytes", "ss_layer_scratch_bytes", "ss_layer_step_scratch_bytes", "ss_proj_gemm"} <= names
+            "ss_layer_saved_bytes", "ss_layer_scratch_bytes", "ss_layer_step_scratch_bytes", "ss_proj_gemm",
+            "ss_proj_gemm_workspace_bytes"} <= names
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -345,3 +346,9 @@ def test_projection_product_rejections():
     assert call() == B.SS_ERR_UNSUPPORTED               # more batch entries than a launch takes
     g.batch = 0
     assert call() == B.SS_OK                            # nothing to do
+    size = B.lib().ss_proj_gemm_workspace_bytes
+    assert size(None) == 0
+    g.M, g.N, g.batch = 160, 2048, 8
+    assert size(ctypes.byref(g)) == 2 * 8 * 160 * 2048 * 4   # two float32 shares of the result
+    g.N = -1
+    assert size(ctypes.byref(g)) == 0

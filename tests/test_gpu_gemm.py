@@ -19,7 +19,7 @@ def _rand(shape, dtype, seed):
     return (torch.randn(shape, generator=g) * 0.5).to(dtype).to(DEV)
 
 
-def _check(A, Bm, C0, trans_a, trans_b, accumulate, general, c_dtype):
+def _check(A, Bm, C0, trans_a, trans_b, accumulate, general, c_dtype, workspace=None):
     """Operands on the GPU (views keep their strides); compare with the float64 product of the same (rounded) operands."""
     a64 = A.cpu().double().transpose(-1, -2) if trans_a else A.cpu().double()
     b64 = Bm.cpu().double().transpose(-1, -2) if trans_b else Bm.cpu().double()
@@ -29,7 +29,7 @@ def _check(A, Bm, C0, trans_a, trans_b, accumulate, general, c_dtype):
         ref = ref + C.cpu().double()
     else:
         C.fill_(float("nan"))   # every element must be written
-    B.ss_proj_gemm(A, Bm, C, trans_a=trans_a, trans_b=trans_b, accumulate=accumulate, general=general)
+    B.ss_proj_gemm(A, Bm, C, trans_a=trans_a, trans_b=trans_b, accumulate=accumulate, general=general, workspace=workspace)
     torch.cuda.synchronize()
     got = C.cpu().double()
     assert torch.isfinite(got).all()
@@ -69,6 +69,30 @@ def test_layer_products_bf16(name, nb, D, L, R, Mx, general):
     _check(u, r, None, False, True, False, general, torch.float32)
     # dW_x partials = dP u^T
     _check(P, u, None, False, True, False, general, torch.float32)
+
+
+@pytest.mark.parametrize("nb,D,L,Mx", [(2, 4096, 256, 96), (1, 4608, 192, 160), (3, 1024, 128, 16)])
+def test_split_contraction_with_workspace(nb, D, L, Mx):
+    """[r;B;C] = W_x u with few column tiles: with a workspace the contraction is split over two workgroups per
+    tile (D >= 4096, a multiple of 512), and the sum of the two float32 shares meets the same bounds.  A workspace that is
+    too small, or a contraction that does not divide, silently runs unsplit."""
+    bf = torch.bfloat16
+    u = _rand((nb, D, L), bf, 11)
+    W_x = _rand((Mx, D), bf, 12)
+    C = torch.empty((nb, Mx, L), dtype=bf, device=DEV)
+    need = B.ss_proj_gemm_workspace_bytes(C)
+    assert need == 2 * nb * Mx * L * 4
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=DEV)     # NaN patterns: every share must be written before it is read
+    _check(W_x, u, None, False, False, False, False, bf, workspace=ws)
+    _check(W_x, u, None, False, False, False, False, bf, workspace=ws[:need // 2])
+    # rows of a wider result (row pitch and batch stride of the caller's)
+    wide = torch.zeros((nb, Mx + 32, L + 64), dtype=bf, device=DEV)
+    view = wide[:, :Mx, :L]
+    B.ss_proj_gemm(W_x, u, view, workspace=ws)
+    torch.cuda.synchronize()
+    ref = torch.matmul(W_x.cpu().double(), u.cpu().double())
+    assert ((view.cpu().double() - ref).abs() <= 2.0 ** -8 * ref.abs() + 1e-3 * ref.abs().max()).all()
+    assert (wide[:, Mx:].abs().max() == 0) and (wide[:, :, L:].abs().max() == 0)   # nothing outside the result
 
 
 def test_transposed_operands_and_odd_sizes():
