@@ -131,6 +131,8 @@ __device__ __forceinline__ void reduce_take_n(float (*red)[RED_PITCH], float* ac
 // dA instead of being reduced over the rows of the workgroup.
 // The exact-ZOH and time-invariant-B/C variants need more registers than two workgroups per
 // compute unit leave (they spilled hundreds); they are built for one workgroup per unit instead.
+// (Exact ZOH with sixteen states and whole 16-byte pieces runs on scan_bwd_dpp_kernel; this kernel
+// takes its other shapes.)
 template <typename T, bool VEC, bool FULLN, bool ZOH, int BCFIX = 0, bool CPLX = false>
 __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd_kernel(const BwdArgs a)
 {
@@ -522,8 +524,15 @@ struct BwdSmemDpp {
 
 
 // SPL: slots per lane the state phases are built for (see scan_fwd_kernel).
-template <typename T, int SPL>
-__global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs a)
+// ZOH: the exact zero-order-hold B-bar of Eq. 4, b = phi B u with phi = (abar - 1)/A.  The LDS tile that
+// otherwise carries dt*u then carries u, the recompute sweep keeps phi_t instead of abar_t (abar = 1 + phi A,
+// one multiply-add in the adjoint sweep), and with g the gradient reaching h_t
+//     ddt = sum_n abar (g h_prev A + g B u)          du = sum_n (g phi) B + Dskip dy
+//     dB  = sum_d (g phi) u                          dA_n += g abar h_prev dt + g B u dphi/dA,
+// where g dphi/dA = (abar g dt - g phi)/A needs neither a division nor dphi itself; for |dt A| < 2^-7, where
+// that difference cancels (and for A = 0), it is g dt^2 (1/2 + dt A/3) instead, and phi is dt (1 + x/2 + x^2/6).
+template <typename T, int SPL, bool ZOH = false>
+__global__ void __launch_bounds__(THREADS, ZOH ? 1 : 2) scan_bwd_dpp_kernel(const BwdArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     BwdSmemDpp& sm = *reinterpret_cast<BwdSmemDpp*>(smem_raw);
@@ -573,6 +582,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
     const int sd = s_ok ? d0 + lane : f.D - 1;
     const long srow = (long)b * f.D + sd;
     float A2[STATES_PER_LANE], dA[STATES_PER_LANE];
+    float An[STATES_PER_LANE], invA[STATES_PER_LANE];   // exact ZOH only
     f32x4_t ag4;
     bool n_ok[STATES_PER_LANE];
 #pragma unroll
@@ -580,7 +590,9 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
         const int n = slot_state(w, k, f.il);
         n_ok[k] = n < N && k < SPL;
         const int nc = n_ok[k] ? n : 0;
-        A2[k] = (n_ok[k] ? f.A[(long)sd * NS + nc] : 0.0f) * LOG2E;
+        An[k] = n_ok[k] ? f.A[(long)sd * NS + nc] : 0.0f;
+        A2[k] = An[k] * LOG2E;
+        invA[k] = An[k] == 0.0f ? 0.0f : 1.0f / An[k];
         if (seg == f.nseg - 1) ag4[k] = (n_ok[k] && a.dh_last) ? a.dh_last[srow * NS + nc] : 0.0f;  // abar_L g_L := dh_last
         else ag4[k] = a.seg_g[(seg_rows + srow) * NPAD + w * STATES_PER_LANE + k];
         dA[k] = 0.0f;
@@ -668,7 +680,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
                 if (softplus) softplus_sigmoid(x, sp, sg); else { sp = x; sg = sg_lin; }
                 dt4[j] = sp;
                 sg4[j] = sg;
-                du4[j] = sp * u4[j];
+                du4[j] = ZOH ? u4[j] : sp * u4[j];
                 dy4[j] = o4[j];
             }
             if (has_z) {
@@ -697,7 +709,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
         __builtin_amdgcn_s_setprio(2);
         constexpr int NG = BT / GROUP_T;
         constexpr int GPT = STATES_PER_LANE / SPL;   // groups of steps per tile of the cross-row reduction
-        f32x4_t as4[BT], hs4[BT];   // abar_t and h_t
+        f32x4_t as4[BT], hs4[BT];   // abar_t (exact ZOH: phi_t) and h_t
         {
             f32x4_t h4 = {hck4.x, hck4.y, hck4.z, hck4.w};
 #pragma unroll
@@ -714,10 +726,19 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
                     float bu[STATES_PER_LANE];
                     input_step_dpp<SPL>(bu, f4_get(Bp, j), du);
                     f32x4_t ab = {1.f, 1.f, 1.f, 1.f};
+                    if constexpr (ZOH) ab = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int k = 0; k < SPL; ++k) {
-                        ab[k] = exp2_fast(dt * A2[k]);                    // Eq. 4
-                        h4[k] = fmaf(ab[k], h4[k], bu[k]);                // Eq. 2a
+                        if constexpr (ZOH) {                              // bu holds B u
+                            const float x2 = dt * A2[k];
+                            const float abar = exp2_fast(x2);             // Eq. 4
+                            const float phi = zoh_phi_fast(dt, x2, abar, invA[k]);
+                            h4[k] = fmaf(abar, h4[k], phi * bu[k]);       // Eq. 2a
+                            ab[k] = phi;
+                        } else {
+                            ab[k] = exp2_fast(dt * A2[k]);                // Eq. 4
+                            h4[k] = fmaf(ab[k], h4[k], bu[k]);            // Eq. 2a
+                        }
                     }
                     as4[tl + j] = ab;
                     hs4[tl + j] = h4;
@@ -745,9 +766,31 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
             for (int j = GROUP_T - 1; j >= 0; --j) {
                 const int t = tl + j;
                 const float dt = f4_get(dt4, j), du = f4_get(du4, j), dy = f4_get(dy4, j);
+                dd[j] = 0.0f;
+                if constexpr (ZOH) {
+                    float gk[STATES_PER_LANE] = {ag4[0], ag4[1], ag4[2], ag4[3]};
+                    adjoint_input_dpp<SPL>(gk, f4_get(Cp, j), dy);         // g = C dy + abar+ g+
+                    float Bu[STATES_PER_LANE], gphi[STATES_PER_LANE] = {0.f, 0.f, 0.f, 0.f};
+                    input_step_dpp<SPL>(Bu, f4_get(Bp, j), du);            // B u  (the tile carries u)
+                    const float dt2 = dt * dt;
+#pragma unroll
+                    for (int k = 0; k < SPL; ++k) {
+                        const float phi = as4[t][k];
+                        ag4[k] = fmaf(phi, An[k], 1.0f) * gk[k];           // abar g: flows on to h_{t-1}
+                        const float gh = ag4[k] * (t > 0 ? hs4[t > 0 ? t - 1 : 0][k] : f4_get(hck4, k));   // g abar h_{t-1}
+                        gphi[k] = gk[k] * phi;
+                        const float x2 = dt * A2[k];
+                        const float direct = fmaf(ag4[k], dt, -gphi[k]) * invA[k];
+                        const float series = (gk[k] * dt2) * fmaf(x2, LN2 / 3.0f, 0.5f);
+                        const float gdphi = select_small(x2, ZOH_SMALL_X2, series, direct);   // g dphi/dA
+                        dA[k] = fmaf(gh, dt, fmaf(Bu[k], gdphi, dA[k]));
+                        dd[j] = fmaf(gh, An[k], fmaf(Bu[k], ag4[k], dd[j]));
+                        dBv[j * STATES_PER_LANE + k] = gphi[k] * du;
+                    }
+                    readout_step_dpp<SPL>(sb[j], f4_get(Bp, j), gphi);     // sb = sum_k B_k g_k phi_k
+                } else {
                 f32x4_t g4 = ag4;
                 adjoint_step_dpp<SPL>(g4, sb[j], f4_get(Cp, j), f4_get(Bp, j), dy);   // g = C dy + abar+ g+;  sb = sum_k B_k g_k
-                dd[j] = 0.0f;
 #pragma unroll
                 for (int k = 0; k < SPL; ++k) {
                     ag4[k] = as4[t][k] * g4[k];                         // flows on to h_{t-1}
@@ -755,6 +798,7 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
                     dA[k] = fmaf(gh, dt, dA[k]);
                     dd[j] = fmaf(gh, A2[k], dd[j]);
                     dBv[j * STATES_PER_LANE + k] = g4[k] * du;
+                }
                 }
             }
             *reinterpret_cast<float4*>(&sm.pdd[w][lane][tl]) = make_float4(dd[0], dd[1], dd[2], dd[3]);
@@ -794,8 +838,8 @@ __global__ void __launch_bounds__(THREADS, 2) scan_bwd_dpp_kernel(const BwdArgs 
 #pragma unroll
             for (int j = 0; j < BSL; ++j) {
                 const float dt = f4_get(dt4, j), dy = f4_get(dy4, j);
-                const float ddt = fmaf(u4[j], sb4[j], LN2 * dd4[j]);
-                du4[j] = fmaf(dt, sb4[j], Dsk * dy);
+                const float ddt = ZOH ? dd4[j] : fmaf(u4[j], sb4[j], LN2 * dd4[j]);
+                du4[j] = ZOH ? fmaf(Dsk, dy, sb4[j]) : fmaf(dt, sb4[j], Dsk * dy);
                 dl4[j] = ddt * sg4[j];             // 0 on an empty slice: its sg is 0
                 dD_acc = fmaf(dy, u4[j], dD_acc);
                 db_acc += dl4[j];
@@ -1223,7 +1267,7 @@ static int launch_scan_bwd_complex(const BwdArgs& a, dim3 grid, hipStream_t stre
 }
 
 // the common case (scan_bwd_dpp_kernel), with the adjoint aggregates of a split sequence first
-template <typename T, bool FULLN, int SPL>
+template <typename T, bool FULLN, int SPL, bool ZOH = false>
 static int launch_scan_bwd_dpp(const BwdArgs& a, dim3 grid, hipStream_t stream)
 {
     if (a.f.nseg > 1) {
@@ -1231,7 +1275,7 @@ static int launch_scan_bwd_dpp(const BwdArgs& a, dim3 grid, hipStream_t stream)
         const long n = (long)a.f.B * a.f.D * NPAD;
         carry_bwd_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(a);
     }
-    auto kern = scan_bwd_dpp_kernel<T, SPL>;
+    auto kern = scan_bwd_dpp_kernel<T, SPL, ZOH>;
     static std::atomic<bool> lds_ok[MAX_DEVICES];   // this launcher is instantiated once per kernel
     if (!allow_backward_lds_once(reinterpret_cast<const void*>(kern), lds_ok, sizeof(BwdSmemDpp))) return -1;
     kern<<<dim3(grid.x, (unsigned)a.f.nseg), dim3(THREADS), sizeof(BwdSmemDpp), stream>>>(a);
@@ -1253,7 +1297,9 @@ static int launch_scan_bwd(const BwdArgs& a, dim3 grid, hipStream_t stream)
     if (bcfix == 1) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 1>(a, grid, stream);
     if (bcfix == 2) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 2>(a, grid, stream);
     if (bcfix == 3) return launch_scan_bwd_fixed<T, VEC, FULLN, ZOH, 3>(a, grid, stream);
-    if constexpr (VEC && !ZOH) {   // real state, first-order B-bar, selective B and C, whole 16-byte pieces
+    if constexpr (VEC && FULLN && ZOH) {   // exact ZOH: the same kernel, built for sixteen states
+        return launch_scan_bwd_dpp<T, FULLN, STATES_PER_LANE, true>(a, grid, stream);
+    } else if constexpr (VEC && !ZOH) {   // real state, first-order B-bar, selective B and C, whole 16-byte pieces
         if constexpr (!FULLN) {    // fewer than 16 states dealt out to the waves: kernels built for 1 or 2 slots per lane
             const int spl = slots_for(a.f.N, a.f.il);
             if (spl == 1) return launch_scan_bwd_dpp<T, FULLN, 1>(a, grid, stream);

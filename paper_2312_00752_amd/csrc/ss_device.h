@@ -100,6 +100,28 @@ __device__ __forceinline__ zoh_terms zoh_phi(float dt, float A, float invA, floa
     return r;
 }
 
+// The same phi for the kernels that are short of registers and issue slots, from what the recurrence has
+// anyway (x2 = dt A log2 e, abar = 2^x2) and inv_A = 1/A (0 for A = 0): dt (1 + x/2 + x^2/6) for
+// |dt A| < 2^-7 (relative error < 3e-8; covers A = 0), (abar - 1)/A beyond (relative error of the
+// exponential's last bit over |dt A|, < 2e-5).
+constexpr float ZOH_SMALL_X2 = 0.0078125f * LOG2E;   // the threshold on dt * A * log2(e)
+// |x| < limit ? small : large, as a compare and a select.  Written out: from the conditional expression the
+// compiler builds a divergent branch per state and step (both sides under execution masks), which breaks an
+// unrolled sweep into hundreds of basic blocks and spills hundreds of registers.
+__device__ __forceinline__ float select_small(float x, float limit, float small, float large)
+{
+    float r;
+    asm("v_cmp_lt_f32_e64 vcc, |%1|, %2\n\t"
+        "v_cndmask_b32_e32 %0, %4, %3, vcc"
+        : "=v"(r) : "v"(x), "s"(limit), "v"(small), "v"(large) : "vcc");
+    return r;
+}
+__device__ __forceinline__ float zoh_phi_fast(float dt, float x2, float abar, float inv_A)
+{
+    const float series = dt * fmaf(x2, fmaf(x2, LN2 * LN2 / 6.0f, LN2 / 2.0f), 1.0f);
+    return select_small(x2, ZOH_SMALL_X2, series, (abar - 1.0f) * inv_A);
+}
+
 // Complex decay factor of one step, abar = exp(dt (Ar + i Ai)) = (re, im): the magnitude from
 // the exponential unit, the rotation from the hardware sine / cosine, which take their
 // argument in revolutions (the fraction is taken first; they are specified for |x| <= 256).

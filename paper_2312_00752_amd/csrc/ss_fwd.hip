@@ -54,7 +54,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));   // MFMA operand a
 // has to cover the previous chunk's stores.
 template <typename T, bool VEC, bool FULLN, bool AGG, bool ZOH, int BCFIX = 0, bool CPLX = false, bool STAGED = false,
           int FUSED_KS = 0, int SPL = STATES_PER_LANE, bool PAT = false>
-__global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS <= 4) ? 2 : 1) scan_fwd_kernel(const FwdArgs a)
+__global__ void __launch_bounds__(THREADS, (PAT && FUSED_KS <= 4 && !(ZOH && AGG)) ? 2 : 1) scan_fwd_kernel(const FwdArgs a)
 {
     static_assert(!PAT || (VEC && BCFIX == 0 && !CPLX && !STAGED), "PAT: vector path, real state, selective B and C");
     constexpr int NGC = CHUNK_T / GROUP_T;
@@ -465,8 +465,9 @@ __global__ void __launch_bounds__(THREADS, (PAT && !ZOH && FUSED_KS <= 4) ? 2 : 
                     input_step_dpp<SPL>(bu, f4_get(Bpc[g], j), du);
 #pragma unroll
                     for (int k = 0; k < SPL; ++k) {
-                        const float abar = exp2_fast(dt * A2[k]);                    // Eq. 4
-                        if (ZOH) bu[k] *= zoh_phi(dt, An[k], invA[k], abar, false).phi;
+                        const float x2 = dt * A2[k];
+                        const float abar = exp2_fast(x2);                            // Eq. 4
+                        if (ZOH) bu[k] *= zoh_phi_fast(dt, x2, abar, invA[k]);
                         h[k] = fmaf(abar, h[k], bu[k]);                              // Eq. 2a
                     }
                     if (!AGG) readout_step_dpp<SPL>(y, f4_get(Cpc[g], j), h);        // Eq. 2b
