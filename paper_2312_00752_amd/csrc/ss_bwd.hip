@@ -529,8 +529,9 @@ struct BwdSmemDpp {
 // one multiply-add in the adjoint sweep), and with g the gradient reaching h_t
 //     ddt = sum_n abar (g h_prev A + g B u)          du = sum_n (g phi) B + Dskip dy
 //     dB  = sum_d (g phi) u                          dA_n += g abar h_prev dt + g B u dphi/dA,
-// where g dphi/dA = (abar g dt - g phi)/A needs neither a division nor dphi itself; for |dt A| < 2^-7, where
-// that difference cancels (and for A = 0), it is g dt^2 (1/2 + dt A/3) instead, and phi is dt (1 + x/2 + x^2/6).
+// where g dphi/dA = (abar g dt - g phi)/A needs neither a division nor dphi itself.  That difference cancels
+// like dt A / 2 and so magnifies phi's own rounding error by 2 / |dt A|: below |dt A| = 2^-4 (and for A = 0)
+// the term is g dt^2 (1/2 + x/3 + x^2/8) instead.
 template <typename T, int SPL, bool ZOH = false>
 __global__ void __launch_bounds__(THREADS, ZOH ? 1 : 2) scan_bwd_dpp_kernel(const BwdArgs a)
 {
@@ -781,8 +782,8 @@ __global__ void __launch_bounds__(THREADS, ZOH ? 1 : 2) scan_bwd_dpp_kernel(cons
                         gphi[k] = gk[k] * phi;
                         const float x2 = dt * A2[k];
                         const float direct = fmaf(ag4[k], dt, -gphi[k]) * invA[k];
-                        const float series = (gk[k] * dt2) * fmaf(x2, LN2 / 3.0f, 0.5f);
-                        const float gdphi = select_small(x2, ZOH_SMALL_X2, series, direct);   // g dphi/dA
+                        const float series = (gk[k] * dt2) * fmaf(x2, fmaf(x2, LN2 * LN2 / 8.0f, LN2 / 3.0f), 0.5f);
+                        const float gdphi = select_small(x2, ZOH_SMALL_X2_GRAD, series, direct);   // g dphi/dA
                         dA[k] = fmaf(gh, dt, fmaf(Bu[k], gdphi, dA[k]));
                         dd[j] = fmaf(gh, An[k], fmaf(Bu[k], ag4[k], dd[j]));
                         dBv[j * STATES_PER_LANE + k] = gphi[k] * du;

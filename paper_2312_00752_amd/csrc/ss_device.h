@@ -105,6 +105,7 @@ __device__ __forceinline__ zoh_terms zoh_phi(float dt, float A, float invA, floa
 // |dt A| < 2^-7 (relative error < 3e-8; covers A = 0), (abar - 1)/A beyond (relative error of the
 // exponential's last bit over |dt A|, < 2e-5).
 constexpr float ZOH_SMALL_X2 = 0.0078125f * LOG2E;   // the threshold on dt * A * log2(e)
+constexpr float ZOH_SMALL_X2_GRAD = 0.0625f * LOG2E;  // the same for the gradient term that carries dphi/dA (backward pass)
 // |x| < limit ? small : large, as a compare and a select.  Written out: from the conditional expression the
 // compiler builds a divergent branch per state and step (both sides under execution masks), which breaks an
 // unrolled sweep into hundreds of basic blocks and spills hundreds of registers.
