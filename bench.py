@@ -75,20 +75,30 @@ def cpu_baseline(w, sample_dim):
 
 
 class ScanSet:
-    """One complete set of device buffers of a scan workload: inputs, output, workspace, gradients."""
+    """One complete set of device buffers of a scan workload: inputs, output, workspace, gradients.
+    The eight (B,D,L) tensors of a set (u, delta, z, dout, out, du, ddelta, dz) are contiguous as the
+    interface requires; with `skewed` they are carved from one allocation at mutually skewed addresses
+    (binding.empty_channel_skewed), without it each is an allocation of its own."""
 
-    def __init__(self, src, dev):
+    def __init__(self, src, dev, skewed=True):
         import torch
         from paper_2312_00752_amd import binding as B
-        self.t = {k: (v.clone() if v is not None else None) for k, v in src.items()}
+        self.t = {k: (v.clone() if v is not None else None) for k, v in src.items() if k not in ("u", "delta", "z", "dout")}
         t = self.t
-        nb, nd, nl = t["u"].shape
+        nb, nd, nl = src["u"].shape
+        if skewed:
+            bdl = B.empty_channel_skewed(8, (nb, nd, nl), src["u"].dtype, dev)
+        else:
+            bdl = [torch.empty_like(src["u"]) for _ in range(8)]
+        for k, buf in zip(("u", "delta", "z", "dout"), bdl):
+            buf.copy_(src[k])
+            t[k] = buf
         nn = t["A"].shape[1]
         f32 = torch.float32
-        self.out = torch.empty_like(t["u"])
+        self.out = bdl[4]
         self.ws = torch.empty(B.ss_workspace_bytes(nb, nd, nl, nn, io_dtype=B.SS_BF16 if t["u"].dtype == torch.bfloat16 else B.SS_F32),
                               dtype=torch.uint8, device=dev)
-        self.grads = {"du": torch.empty_like(t["u"]), "ddelta": torch.empty_like(t["u"]), "dz": torch.empty_like(t["u"]),
+        self.grads = {"du": bdl[5], "ddelta": bdl[6], "dz": bdl[7],
                       "dB": torch.empty(tuple(t["B"].shape), dtype=f32, device=dev),
                       "dC": torch.empty(tuple(t["C"].shape), dtype=f32, device=dev),
                       "dA": torch.empty(tuple(t["A"].shape), dtype=f32, device=dev),
@@ -184,7 +194,6 @@ def all_configs_bench(dev, steps=6):
         esz = 2 if io == "bf16" else 4
         src = device_inputs(name, dev)
         sets = [ScanSet(src, dev) for _ in range(2)]
-        del src
         # enough repetitions that the clocks have settled (a launch onto an idle chip runs ~10 % slower):
         # about 25 ms of warm-up and as much of timed work, from a first estimate of a step
         _, f0, b0, _, _ = time_rotating(sets, 2, 1)
@@ -197,6 +206,15 @@ def all_configs_bench(dev, steps=6):
                      "algorithmic_bytes": fb + bb,
                      "frac_of_hbm_peak": (fb + bb) / ((f_ms + b_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS}
         del sets
+        if (nl * esz) % (1 << 20) == 0:
+            # rows a large power of two apart: the same calls on tensors that are separate allocations
+            # (all at the same offset into the memory channels' interleave), for comparison
+            torch.cuda.empty_cache()
+            plain = [ScanSet(src, dev, skewed=False) for _ in range(2)]
+            _, fp, bp, _, _ = time_rotating(plain, n, n)
+            res[name]["fwd_bwd_ms_separate_allocations"] = fp[len(fp) // 2] + bp[len(bp) // 2]
+            del plain
+        del src
         torch.cuda.empty_cache()
     return res
 
@@ -602,7 +620,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": nb, "seqlen": nl, "d_inner": nd, "d_state": nn,
                    "io_dtype": w["io"], "state_dtype": "f32", "passes": "fwd(save)+bwd",
-                   "rotating_buffer_sets": len(sets), "bytes_per_set": set_bytes},
+                   "rotating_buffer_sets": len(sets), "bytes_per_set": set_bytes,
+                   "allocation": "contiguous (B,D,L) tensors, the eight of a set carved from one allocation 65 KiB apart"},
         # Dominant kernel: the backward scan (the backward call = zero-fill + scan + finalize; the scan
         # kernel is > 98 % of it).  Graded bound: HBM, algorithmic bytes of one backward launch over its
         # duration.  `traffic` is the launch's measured HBM bytes (rocprofv3 counters, kept in profiles/).

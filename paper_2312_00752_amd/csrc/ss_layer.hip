@@ -227,7 +227,11 @@ ScratchLayout scratch_layout(const ss_layer_params* p, bool bwd)
     ScratchLayout w{};
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off += round_up(bytes, 256); return at; };
-    const size_t T = s.B * s.D * s.L * s.esz;
+    // The (B,D,L) buffers start 65 KiB (a multiple of 256 bytes) further apart than their size: the scan
+    // touches all of them at the same row and step, and with rows a large power of two of bytes apart equal
+    // starting offsets into the memory channels' interleave would put all of that on one channel.
+    constexpr size_t SKEW = 66560;
+    const size_t T = s.B * s.D * s.L * s.esz + SKEW;
     w.u = take(T);
     w.delta = take(T);
     if (!bwd) {

@@ -352,3 +352,19 @@ def test_projection_product_rejections():
     assert size(ctypes.byref(g)) == 2 * 8 * 160 * 2048 * 4   # two float32 shares of the result
     g.N = -1
     assert size(ctypes.byref(g)) == 0
+
+
+def test_skewed_allocation_helper():
+    """Tensors for one call carved from one allocation: right shapes, contiguous, 256-byte aligned starts,
+    each 65 KiB further into the interleave than the one before, no overlap."""
+    import torch
+    ts = B.empty_channel_skewed(3, (2, 5, 64), torch.bfloat16, "cpu")
+    assert len(ts) == 3 and all(t.shape == (2, 5, 64) and t.dtype == torch.bfloat16 and t.is_contiguous() for t in ts)
+    nbytes = 2 * 5 * 64 * 2
+    starts = [t.data_ptr() for t in ts]
+    assert all((b - a) == (nbytes + 255) // 256 * 256 + B.CHANNEL_SKEW_BYTES for a, b in zip(starts, starts[1:]))
+    assert all((s_ - starts[0]) % 256 == 0 for s_ in starts)
+    for i, t in enumerate(ts):
+        t.fill_(float(i + 1))
+    assert [float(t.float().min()) for t in ts] == [1.0, 2.0, 3.0] and [float(t.float().max()) for t in ts] == [1.0, 2.0, 3.0]
+    assert B.empty_channel_skewed(0, (4,), torch.float32, "cpu") == []
