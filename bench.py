@@ -441,19 +441,17 @@ def paper_sweep(dev):
     for e in range(9, 20):
         nl = 1 << e
         mk = lambda *shape: torch.randn(*shape, device=dev, generator=gen).to(bf)
-        u, dl, z, do = mk(nb, nd, nl), mk(nb, nd, nl), mk(nb, nd, nl), mk(nb, nd, nl)
-        Bm, Cm = mk(nb, nn, nl), mk(nb, nn, nl)
-        A = -torch.arange(1, nn + 1, device=dev, dtype=torch.float32).repeat(nd, 1).contiguous()
-        Dk = torch.randn(nd, device=dev, generator=gen)
-        bias = torch.full((nd,), -4.0, device=dev)
-        out = torch.empty_like(u)
-        ws = torch.empty(max(256, B.ss_workspace_bytes(nb, nd, nl, nn, io_dtype=B.SS_BF16)), dtype=torch.uint8, device=dev)
+        src = {"u": mk(nb, nd, nl), "delta": mk(nb, nd, nl), "z": mk(nb, nd, nl), "dout": mk(nb, nd, nl),
+               "B": mk(nb, nn, nl), "C": mk(nb, nn, nl),
+               "A": -torch.arange(1, nn + 1, device=dev, dtype=torch.float32).repeat(nd, 1).contiguous(),
+               "Dskip": torch.randn(nd, device=dev, generator=gen), "delta_bias": torch.full((nd,), -4.0, device=dev)}
+        st = ScanSet(src, dev)   # tensors placed as in the main benchmark, gradients preallocated
+        del src
+        t = st.t
         ws0 = torch.empty(max(256, B.ss_workspace_bytes(nb, nd, nl, nn, for_backward=False, io_dtype=B.SS_BF16)),
                           dtype=torch.uint8, device=dev)
-        kw = dict(Dskip=Dk, z=z, delta_bias=bias, delta_softplus=True)
-        fi = lambda: B.ss_scan_fwd(u, dl, A, Bm, Cm, out=out, workspace=ws0, save_for_bwd=False, **kw)
-        fs = lambda: B.ss_scan_fwd(u, dl, A, Bm, Cm, out=out, workspace=ws, **kw)
-        bw = lambda: B.ss_scan_bwd(do, u, dl, A, Bm, Cm, ws, **kw)
+        fi = lambda: B.ss_scan_fwd(t["u"], t["delta"], t["A"], t["B"], t["C"], out=st.out, workspace=ws0, save_for_bwd=False, **st.kw)
+        fs, bw = st.fwd, st.bwd
         for _ in range(2):
             fi(); fs(); bw()
         torch.cuda.synchronize()
