@@ -156,7 +156,7 @@ __global__ void __launch_bounds__(THREADS, (ZOH || BCFIX != 0) ? 1 : 2) scan_bwd
     const long seg_rows = (long)seg * f.B * f.D;
 
     // ---- pointwise view: thread -> (row pr, 4-step slice pq) -----------------------------
-    const int pr = tid >> 2, pq = tid & 3;
+    const int pr = pointwise_row_pitch5(tid), pq = tid & 3;   // BPAD = 20 floats
     const bool p_ok = d0 + pr < f.D;
     const int pd = p_ok ? d0 + pr : f.D - 1;
     const long prow = (long)b * f.D + pd;
@@ -555,7 +555,7 @@ __global__ void __launch_bounds__(THREADS, ZOH ? 1 : 2) scan_bwd_dpp_kernel(cons
     const long seg_rows = (long)seg * f.B * f.D;
 
     // ---- pointwise view: thread -> (row pr, 4-step slice pq) -----------------------------
-    const int pr = tid >> 2, pq = tid & 3;
+    const int pr = pointwise_row_pitch5(tid), pq = tid & 3;   // BPAD = 20 floats
     const bool p_ok = d0 + pr < f.D;
     const int pd = p_ok ? d0 + pr : f.D - 1;
     const long prow = (long)b * f.D + pd;
@@ -902,7 +902,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_kernel(const BwdArgs a)
     const int c_begin = seg * (f.seg_len / CHUNK_T);
     const int c_end = min((L + CHUNK_T - 1) / CHUNK_T, (seg + 1) * (f.seg_len / CHUNK_T));
 
-    const int pr = tid >> 2, pq = tid & 3;
+    const int pr = pointwise_row_pitch9(tid), pq = tid & 3;   // TPAD = 36 floats
     const bool p_ok = d0 + pr < f.D;
     const int pd = p_ok ? d0 + pr : f.D - 1;
     const long prow = (long)b * f.D + pd;
@@ -1025,7 +1025,7 @@ __global__ void __launch_bounds__(THREADS) adjoint_agg_dpp_kernel(const BwdArgs 
     const int c_begin = seg * (f.seg_len / CHUNK_T);
     const int c_end = min((L + CHUNK_T - 1) / CHUNK_T, (seg + 1) * (f.seg_len / CHUNK_T));
 
-    const int pr = tid >> 2, pq = tid & 3;
+    const int pr = pointwise_row_pitch9(tid), pq = tid & 3;   // TPAD = 36 floats
     const bool p_ok = d0 + pr < f.D;
     const int pd = p_ok ? d0 + pr : f.D - 1;
     const float bias = (f.flags & F_HAS_DELTA_BIAS) ? f.bias[pd] : 0.0f;

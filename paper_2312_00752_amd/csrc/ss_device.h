@@ -549,6 +549,23 @@ __device__ __forceinline__ uint32_t touch_bc(const void* Bm, const void* Cm, int
     }
     return v;
 }
+// Rows of the pointwise view.  Four lanes share a row (one 16-byte piece of it each, or two), so sixteen
+// consecutive lanes - what the LDS serves together - hold four rows.  With consecutive rows and the padded
+// pitches that keep the one-lane-per-row view free of bank conflicts (five or nine pieces per row), those
+// sixteen lanes collided two-way (3-4 % of the backward kernel's time); with the rows picked as below they
+// touch sixteen different 16-byte slots.  A wave still owns sixteen consecutive rows, and the four lanes of
+// a row stay adjacent, so global accesses do not change.
+//   pitch 5, one piece per lane  (slot = 5 r + q):      rows r, r + 4, r + 8, r + 12
+//   pitch 9, pieces 2 q, 2 q + 1 (slot = 9 r + 2 q):    rows r, r + 1, r + 8, r + 9   (r even)
+__device__ __forceinline__ int pointwise_row_pitch5(int tid)
+{
+    return (tid >> 6) * 16 + ((tid >> 2) & 3) * 4 + ((tid >> 4) & 3);
+}
+__device__ __forceinline__ int pointwise_row_pitch9(int tid)
+{
+    const int m = (tid >> 2) & 3;
+    return (tid >> 6) * 16 + 2 * ((tid >> 4) & 3) + (m & 1) + 8 * (m >> 1);
+}
 __device__ __forceinline__ void consume_touch(uint32_t v) { asm volatile("" ::"v"(v)); }
 
 // ---- B and C as quad-broadcast operands ---------------------------------------------------

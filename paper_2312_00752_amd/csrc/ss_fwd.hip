@@ -83,7 +83,7 @@ __global__ void __launch_bounds__(THREADS, (PAT && FUSED_KS <= 4 && !(ZOH && AGG
     const int c_end = min((L + CHUNK_T - 1) / CHUNK_T, (seg + 1) * (a.seg_len / CHUNK_T));
 
     // ---- pointwise view: thread -> (row pr, slice pq) -----------------------------------
-    const int pr = tid >> 2, pq = tid & 3;
+    const int pr = pointwise_row_pitch9(tid), pq = tid & 3;   // TPAD = 36 floats
     const bool p_ok = d0 + pr < a.D;
     const int pd = p_ok ? d0 + pr : a.D - 1;  // out-of-range rows shadow the last row; stores masked
     const long prow = (long)b * a.D + pd;
