@@ -338,7 +338,8 @@ def ss_scan_bwd(dout, u, delta, A, Bmat, Cmat, workspace, Dskip=None, z=None, de
 
     Returns a dict with du, ddelta, dz, dB, dC, dA, dD, ddelta_bias, dh0 (None where the
     corresponding input was not given).  ``grads``: a dict an earlier call returned; its
-    tensors are written again instead of allocating new ones."""
+    tensors are written again instead of allocating new ones.  Freshly allocated du, ddelta and dz
+    are views into one allocation (``empty_channel_skewed``): it lives as long as any of them."""
     import torch
     f32 = torch.float32
     q = BwdParams()
